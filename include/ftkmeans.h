@@ -1,0 +1,149 @@
+/*
+ * ftkmeans.h -- C boundary of the MI355X (gfx950) K-means hot path.
+ *
+ * One Lloyd iteration of K-means (paper Section 2) is
+ *     assignment  label_i = argmin_j || X_i - C_j ||_2                       (Eq. 1)
+ *     update      C_j     = mean of the points with label j                  (Eq. 2)
+ * The assignment is evaluated through the expansion of Section 3.1.2,
+ *     || x - c ||^2 = sum_d x_d^2 + sum_d c_d^2 - 2 sum_d x_d c_d,
+ * whose last term is a dense [N x D] by [D x K] contraction on the matrix cores with the
+ * per-point argmin fused into its epilogue (Sections 3.1.3-3.1.5), optionally protected by
+ * the online checksum scheme of Sections 2.3 and 4 (detect, locate, correct one corrupted
+ * accumulator element per checked tile before the argmin reads it).
+ *
+ * Conventions common to every call
+ *   - N points, D features, K clusters.  X is [N x D], C is [K x D], both row-major and
+ *     contiguous, element type given by `dtype`.
+ *   - Every array pointer is a DEVICE pointer owned by the caller unless marked (host).
+ *     The library allocates no device memory: scratch comes from `workspace`, which must
+ *     hold at least ftk_workspace_bytes(...) bytes and be 256-byte aligned.  Workspace
+ *     contents need not survive between calls.
+ *   - Calls only enqueue work on `hip_stream` (a hipStream_t; NULL = the default stream)
+ *     and return without waiting, except where stated.  Calls that share a workspace must be
+ *     ordered on one stream.
+ *   - Distances are SQUARED Euclidean distances (the square root is dropped, Section 3.1.2).
+ *   - Exact ties go to the lowest centroid index.  An empty cluster keeps its centroid.
+ *   - Errors are reported by return code, never by abort; ftk_last_error() gives the text of
+ *     the last failure on the calling thread.  On error nothing has been enqueued.
+ */
+#ifndef FTKMEANS_H
+#define FTKMEANS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FTK_OK = 0,
+    FTK_EINVAL = 1,        /* bad shape, NULL pointer, unknown enum value            */
+    FTK_EALIGN = 2,        /* a pointer is not aligned to its element size / 256 B   */
+    FTK_EWORKSPACE = 3,    /* workspace missing or too small                         */
+    FTK_EDEVICE = 4,       /* a HIP runtime call failed or the device is not gfx950  */
+    FTK_EUNCORRECTABLE = 5 /* reserved: reported through ftk_ft_stats, not returned  */
+} ftk_status;
+
+typedef enum { FTK_F32 = 0, FTK_F64 = 1 } ftk_dtype;
+
+/* Fault-tolerance mode of the contraction (Section 4).
+ *   OFF     : no checksums.
+ *   DETECT  : checksums carried and verified, mismatches only counted.
+ *   CORRECT : a mismatching tile is repaired in place from its location-encoded checksums
+ *             (Section 4.1); if the location cannot be decoded the tile is recomputed. */
+typedef enum { FTK_FT_OFF = 0, FTK_FT_DETECT = 1, FTK_FT_CORRECT = 2 } ftk_ft_mode;
+
+/* One injected soft error (fault model of Section 2.1): flip `bit` of accumulator register
+ * `reg` of lane `lane`, in the `tile`-th output tile that wave `wave` of workgroup
+ * `workgroup` finishes, right after its matrix instructions and before verification.
+ * Fields other than `workgroup` are reduced modulo the extents ftk_assign_geometry reports,
+ * so every descriptor is valid; a workgroup index beyond the grid never fires. */
+typedef struct {
+    uint32_t workgroup, wave, tile, reg, lane, bit;
+} ftk_fault;
+
+/* Counters accumulated (atomically added to) by ftk_kmeans_assign; zero them beforehand. */
+typedef struct {
+    uint64_t tiles_checked;  /* per-lane-group checksum comparisons made                  */
+    uint64_t injected;       /* fault descriptors that fired                              */
+    uint64_t detected;       /* checksum mismatches above the threshold                   */
+    uint64_t corrected;      /* repaired from the decoded location                        */
+    uint64_t recomputed;     /* location not decodable -> tile recomputed                 */
+    uint64_t uncorrectable;  /* still mismatching after recomputation                     */
+    uint64_t refined;        /* points whose two best scores were closer than the
+                                rounding-error bound and were re-evaluated exactly        */
+} ftk_ft_stats;
+
+/* Launch geometry of the assignment kernel for a problem, for building fault lists. */
+typedef struct {
+    uint32_t workgroups, waves_per_workgroup, tiles_per_wave, regs_per_tile, lanes, bits;
+} ftk_geometry;
+
+/* Bytes of workspace sufficient for any of the three calls below on this problem. */
+size_t ftk_workspace_bytes(ftk_dtype dtype, int64_t N, int32_t D, int32_t K, ftk_ft_mode ft);
+
+ftk_status ftk_assign_geometry(ftk_dtype dtype, int64_t N, int32_t D, int32_t K, ftk_ft_mode ft,
+                               ftk_geometry *out /* (host) */);
+
+/* Assignment step, Eq. (1), Sections 3.1.2-3.1.5 and 4.
+ *   X [N x D], C [K x D]  in  : read only.
+ *   labels [N] int32      out : index of the nearest centroid.
+ *   mindist [N] (dtype)   out : squared distance to it, >= 0; may be NULL.
+ *   faults [n_faults]     in  : soft errors to inject; NULL / 0 for none.  Ignored when
+ *                               ft == FTK_FT_OFF is combined with n_faults == 0 only; with
+ *                               FT off, listed faults are still injected (and corrupt the
+ *                               result) so that the unprotected baseline can be observed.
+ *   stats                 i/o : counters, may be NULL.
+ * Requires 1 <= N, 1 <= D, 1 <= K, N*D < 2^40. */
+ftk_status ftk_kmeans_assign(ftk_dtype dtype, const void *X, const void *C, int64_t N, int32_t D,
+                             int32_t K, int32_t *labels, void *mindist, ftk_ft_mode ft,
+                             const ftk_fault *faults, int32_t n_faults, ftk_ft_stats *stats,
+                             void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Largest |x| over `count` elements, written as one double to out_absmax (device).
+ * ftk_kmeans_update needs it to fix the scale of its order-independent accumulation. */
+ftk_status ftk_absmax(ftk_dtype dtype, const void *X, int64_t count, double *out_absmax,
+                      void *hip_stream);
+
+/* Update step, Eq. (2), Sections 3.1.1-3.1.2 (sum the points of each cluster, then average).
+ *   X [N x D], labels [N] in  : labels must lie in [0, K).
+ *   C [K x D]             i/o : previous centroids in, new centroids out; rows of empty
+ *                               clusters are left untouched.
+ *   counts [K] int32      out : points per cluster.
+ *   x_absmax              in  : device scalar from ftk_absmax over X, or NULL to have it
+ *                               computed here (one more pass over X).
+ * The result is bitwise reproducible from run to run: sums are accumulated in 64-bit fixed
+ * point, which does not depend on the order of additions. */
+ftk_status ftk_kmeans_update(ftk_dtype dtype, const void *X, const int32_t *labels, int64_t N,
+                             int32_t D, int32_t K, void *C, int32_t *counts,
+                             const double *x_absmax, void *workspace, size_t workspace_bytes,
+                             void *hip_stream);
+
+/* Lloyd loop, Section 2: `iters` times { assign ; update }, fixed iteration count.
+ *   C_init [K x D]        in  : initial centroids, or NULL to take K distinct points of X
+ *                               chosen by Floyd sampling driven by SplitMix64(seed)
+ *                               (requires K <= N).
+ *   C_out [K x D]         out : centroids after the last update.
+ *   labels_out [N]        out : labels of the last assignment (taken against the centroids
+ *                               before the last update).
+ *   counts_out [K]        out : cluster sizes of that assignment.
+ *   inertia_per_iter      out : (host, may be NULL) sum of mindist of every iteration;
+ *                               when given, the call waits for the stream before returning.
+ *   stats                 i/o : fault-tolerance counters summed over iterations, may be NULL. */
+ftk_status ftk_kmeans_fit(ftk_dtype dtype, const void *X, int64_t N, int32_t D, int32_t K,
+                          int32_t iters, uint64_t seed, const void *C_init, void *C_out,
+                          int32_t *labels_out, int32_t *counts_out, double *inertia_per_iter,
+                          ftk_ft_mode ft, ftk_ft_stats *stats, void *workspace,
+                          size_t workspace_bytes, void *hip_stream);
+
+/* (host) K distinct indices in [0, N) by the seeded procedure ftk_kmeans_fit uses. */
+ftk_status ftk_seeded_indices(uint64_t seed, int64_t N, int32_t K, int64_t *idx_host);
+
+const char *ftk_last_error(void);
+const char *ftk_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FTKMEANS_H */

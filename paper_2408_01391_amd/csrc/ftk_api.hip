@@ -1,0 +1,332 @@
+// C-ABI entry points of libftkmeans: argument checks, planning, workspace carving, and the
+// host-side Lloyd loop (Section 2).  Everything numerical happens in the kernels.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "ftk_internal.h"
+
+namespace ftk {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+ftk_status hip_failed(hipError_t e, const char *what)
+{
+    set_error("HIP error %d (%s) in %s", (int)e, hipGetErrorString(e), what);
+    return FTK_EDEVICE;
+}
+
+void plan_generic(ftk_dtype dtype, int64_t N, int D, int K, AssignPlan &p);
+void plan_smalld(int64_t N, int D, int K, ftk_ft_mode ft, AssignPlan &p);
+bool smalld_supported(ftk_dtype dtype, int D, int K);
+ftk_status launch_assign_generic(const AssignCall &c, const AssignPlan &p, const Workspace &w,
+                                 hipStream_t st);
+ftk_status launch_assign_smalld(const AssignCall &c, const AssignPlan &p, const Workspace &w,
+                                hipStream_t st);
+
+AssignPlan plan_assign(ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft)
+{
+    AssignPlan p;
+    memset(&p, 0, sizeof(p));
+    if (smalld_supported(dtype, D, K))
+        plan_smalld(N, D, K, ft, p);
+    else
+        plan_generic(dtype, N, D, K, p);
+    return p;
+}
+
+ftk_status launch_assign(const AssignCall &c, const AssignPlan &p, const Workspace &w, hipStream_t st)
+{
+    return p.variant == VAR_SMALLD ? launch_assign_smalld(c, p, w, st)
+                                   : launch_assign_generic(c, p, w, st);
+}
+
+// The workspace is carved for the larger of the two kernel variants so that its size does not
+// depend on which one the dispatcher picks.
+Workspace carve_workspace(void *base, ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft)
+{
+    (void)ft;
+    const size_t esz = dtype == FTK_F32 ? 4 : 8;
+    const size_t D8 = (size_t)ceil_div(D, 8) * 8;
+    const size_t Kpad = (size_t)ceil_div(K, 512) * 512 + 512;   // multiple of every chunk size
+    const size_t ntiles = Kpad / 16;                            // smallest tile: 16 centroids
+    char *p = (char *)base;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        void *r = p ? (void *)(p + off) : nullptr;
+        off += align_up(bytes, 256);
+        return r;
+    };
+    Workspace w;
+    w.hcn = take(Kpad * esz);
+    w.scal = (double *)take(8 * sizeof(double));
+    w.chk_v1 = take(ntiles * D8 * esz);
+    w.chk_v2 = take(ntiles * D8 * esz);
+    w.chk_s = take(ntiles * 2 * esz);
+    w.wl_count = (int32_t *)take(4 * sizeof(int32_t));
+    w.wl = (int32_t *)take((size_t)N * sizeof(int32_t));
+    w.fx_sums = (int64_t *)take((size_t)K * D * sizeof(int64_t));
+    w.absmax = (double *)take(2 * sizeof(double));
+    w.C_cur = take((size_t)K * D * esz);
+    w.mindist = take((size_t)N * esz);
+    w.inertia = (double *)take(FIT_MAX_ITERS_IN_WS * sizeof(double));
+    w.partials = (double *)take(1024 * sizeof(double));
+    w.idx = (int64_t *)take((size_t)K * sizeof(int64_t));
+    w.total = off;
+    return w;
+}
+
+static ftk_status check_problem(ftk_dtype dtype, int64_t N, int D, int K, int ft)
+{
+    if (dtype != FTK_F32 && dtype != FTK_F64) {
+        set_error("unknown dtype %d", (int)dtype);
+        return FTK_EINVAL;
+    }
+    if (ft != FTK_FT_OFF && ft != FTK_FT_DETECT && ft != FTK_FT_CORRECT) {
+        set_error("unknown ft_mode %d", ft);
+        return FTK_EINVAL;
+    }
+    if (N < 1 || D < 1 || K < 1) {
+        set_error("need N >= 1, D >= 1, K >= 1 (got N=%lld D=%d K=%d)", (long long)N, D, K);
+        return FTK_EINVAL;
+    }
+    if (N > 0x7fffffffLL || (double)N * D >= 1099511627776.0 || (int64_t)K * D > (1LL << 31)) {
+        set_error("problem too large: N=%lld D=%d K=%d (need N < 2^31, N*D < 2^40, K*D <= 2^31)",
+                  (long long)N, D, K);
+        return FTK_EINVAL;
+    }
+    return FTK_OK;
+}
+
+static ftk_status check_ptr(const void *p, size_t align, const char *name)
+{
+    if (!p) {
+        set_error("%s is NULL", name);
+        return FTK_EINVAL;
+    }
+    if ((uintptr_t)p % align) {
+        set_error("%s is not %zu-byte aligned", name, align);
+        return FTK_EALIGN;
+    }
+    return FTK_OK;
+}
+
+static ftk_status check_workspace(void *ws, size_t bytes, size_t need)
+{
+    if (!ws || bytes < need) {
+        set_error("workspace of %zu bytes given, %zu needed", ws ? bytes : (size_t)0, need);
+        return FTK_EWORKSPACE;
+    }
+    if ((uintptr_t)ws % 256) {
+        set_error("workspace is not 256-byte aligned");
+        return FTK_EALIGN;
+    }
+    return FTK_OK;
+}
+
+static ftk_status check_device()
+{
+    static thread_local int checked_dev = -1;
+    int dev = 0;
+    FTK_TRY_HIP(hipGetDevice(&dev));
+    if (dev == checked_dev) return FTK_OK;
+    hipDeviceProp_t prop;
+    FTK_TRY_HIP(hipGetDeviceProperties(&prop, dev));
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) {
+        set_error("device %d is %s; this library is built for gfx950 only", dev, prop.gcnArchName);
+        return FTK_EDEVICE;
+    }
+    checked_dev = dev;
+    return FTK_OK;
+}
+
+static ftk_status assign_impl(const AssignCall &c, void *workspace, hipStream_t st)
+{
+    const AssignPlan p = plan_assign(c.dtype, c.N, c.D, c.K, c.ft);
+    const Workspace w = carve_workspace(workspace, c.dtype, c.N, c.D, c.K, c.ft);
+    FTK_TRY(launch_centroid_prologue(c, p, w, st));
+    FTK_TRY(launch_assign(c, p, w, st));
+    FTK_TRY(launch_refine(c, w, st));
+    return FTK_OK;
+}
+
+}  // namespace ftk
+
+using namespace ftk;
+
+extern "C" {
+
+const char *ftk_last_error(void) { return g_err; }
+const char *ftk_version(void) { return "ftkmeans 0.1 (gfx950)"; }
+
+size_t ftk_workspace_bytes(ftk_dtype dtype, int64_t N, int32_t D, int32_t K, ftk_ft_mode ft)
+{
+    if (check_problem(dtype, N, D, K, ft) != FTK_OK) return 0;
+    return carve_workspace(nullptr, dtype, N, D, K, ft).total;
+}
+
+ftk_status ftk_assign_geometry(ftk_dtype dtype, int64_t N, int32_t D, int32_t K, ftk_ft_mode ft,
+                               ftk_geometry *out)
+{
+    FTK_TRY(check_problem(dtype, N, D, K, ft));
+    if (!out) {
+        set_error("out is NULL");
+        return FTK_EINVAL;
+    }
+    const AssignPlan p = plan_assign(dtype, N, D, K, ft);
+    out->workgroups = (uint32_t)p.workgroups;
+    out->waves_per_workgroup = (uint32_t)p.waves;
+    out->tiles_per_wave = (uint32_t)p.tiles_per_wave;
+    out->regs_per_tile = (uint32_t)p.regs_per_tile;
+    out->lanes = 64;
+    out->bits = dtype == FTK_F32 ? 32 : 64;
+    return FTK_OK;
+}
+
+ftk_status ftk_kmeans_assign(ftk_dtype dtype, const void *X, const void *C, int64_t N, int32_t D,
+                             int32_t K, int32_t *labels, void *mindist, ftk_ft_mode ft,
+                             const ftk_fault *faults, int32_t n_faults, ftk_ft_stats *stats,
+                             void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    FTK_TRY(check_problem(dtype, N, D, K, ft));
+    const size_t esz = dtype == FTK_F32 ? 4 : 8;
+    FTK_TRY(check_ptr(X, esz, "X"));
+    FTK_TRY(check_ptr(C, esz, "C"));
+    FTK_TRY(check_ptr(labels, 4, "labels"));
+    if (mindist) FTK_TRY(check_ptr(mindist, esz, "mindist"));
+    if (n_faults < 0 || (n_faults > 0 && !faults)) {
+        set_error("n_faults=%d with faults=%p", n_faults, (const void *)faults);
+        return FTK_EINVAL;
+    }
+    if (stats) FTK_TRY(check_ptr(stats, 8, "stats"));
+    FTK_TRY(check_workspace(workspace, workspace_bytes, ftk_workspace_bytes(dtype, N, D, K, ft)));
+    FTK_TRY(check_device());
+    AssignCall c{dtype, X, C, N, D, K, labels, mindist, ft, faults, n_faults, stats};
+    return assign_impl(c, workspace, (hipStream_t)hip_stream);
+}
+
+ftk_status ftk_absmax(ftk_dtype dtype, const void *X, int64_t count, double *out_absmax, void *hip_stream)
+{
+    if (dtype != FTK_F32 && dtype != FTK_F64) {
+        set_error("unknown dtype %d", (int)dtype);
+        return FTK_EINVAL;
+    }
+    if (count < 1) {
+        set_error("count must be >= 1");
+        return FTK_EINVAL;
+    }
+    FTK_TRY(check_ptr(X, dtype == FTK_F32 ? 4 : 8, "X"));
+    FTK_TRY(check_ptr(out_absmax, 8, "out_absmax"));
+    FTK_TRY(check_device());
+    return launch_absmax(dtype, X, count, out_absmax, (hipStream_t)hip_stream);
+}
+
+ftk_status ftk_kmeans_update(ftk_dtype dtype, const void *X, const int32_t *labels, int64_t N,
+                             int32_t D, int32_t K, void *C, int32_t *counts, const double *x_absmax,
+                             void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    FTK_TRY(check_problem(dtype, N, D, K, FTK_FT_OFF));
+    const size_t esz = dtype == FTK_F32 ? 4 : 8;
+    FTK_TRY(check_ptr(X, esz, "X"));
+    FTK_TRY(check_ptr(labels, 4, "labels"));
+    FTK_TRY(check_ptr(C, esz, "C"));
+    FTK_TRY(check_ptr(counts, 4, "counts"));
+    if (x_absmax) FTK_TRY(check_ptr(x_absmax, 8, "x_absmax"));
+    FTK_TRY(check_workspace(workspace, workspace_bytes, ftk_workspace_bytes(dtype, N, D, K, FTK_FT_OFF)));
+    FTK_TRY(check_device());
+    hipStream_t st = (hipStream_t)hip_stream;
+    const Workspace w = carve_workspace(workspace, dtype, N, D, K, FTK_FT_OFF);
+    if (!x_absmax) {
+        FTK_TRY(launch_absmax(dtype, X, N * (int64_t)D, w.absmax, st));
+        x_absmax = w.absmax;
+    }
+    return launch_update(dtype, X, labels, N, D, K, C, counts, x_absmax, w, st);
+}
+
+ftk_status ftk_seeded_indices(uint64_t seed, int64_t N, int32_t K, int64_t *idx_host)
+{
+    if (K < 1 || N < K || !idx_host) {
+        set_error("need 1 <= K <= N and a destination (N=%lld K=%d)", (long long)N, K);
+        return FTK_EINVAL;
+    }
+    // Floyd's sampling of K distinct values from [0, N), driven by SplitMix64.
+    uint64_t state = seed;
+    auto next = [&state]() {
+        uint64_t z = (state += 0x9E3779B97F4A7C15ULL);
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+        return z ^ (z >> 31);
+    };
+    int filled = 0;
+    for (int64_t top = N - K; top < N; ++top) {
+        const int64_t pick = (int64_t)(next() % (uint64_t)(top + 1));
+        bool seen = false;
+        for (int i = 0; i < filled && !seen; ++i) seen = idx_host[i] == pick;
+        idx_host[filled++] = seen ? top : pick;
+    }
+    return FTK_OK;
+}
+
+ftk_status ftk_kmeans_fit(ftk_dtype dtype, const void *X, int64_t N, int32_t D, int32_t K,
+                          int32_t iters, uint64_t seed, const void *C_init, void *C_out,
+                          int32_t *labels_out, int32_t *counts_out, double *inertia_per_iter,
+                          ftk_ft_mode ft, ftk_ft_stats *stats, void *workspace,
+                          size_t workspace_bytes, void *hip_stream)
+{
+    FTK_TRY(check_problem(dtype, N, D, K, ft));
+    if (iters < 0 || iters > FIT_MAX_ITERS_IN_WS) {
+        set_error("iters must be in [0, %d]", FIT_MAX_ITERS_IN_WS);
+        return FTK_EINVAL;
+    }
+    const size_t esz = dtype == FTK_F32 ? 4 : 8;
+    FTK_TRY(check_ptr(X, esz, "X"));
+    if (C_init) FTK_TRY(check_ptr(C_init, esz, "C_init"));
+    FTK_TRY(check_ptr(C_out, esz, "C_out"));
+    FTK_TRY(check_ptr(labels_out, 4, "labels_out"));
+    FTK_TRY(check_ptr(counts_out, 4, "counts_out"));
+    if (stats) FTK_TRY(check_ptr(stats, 8, "stats"));
+    if (!C_init && K > N) {
+        set_error("seeded initialisation needs K <= N (N=%lld K=%d)", (long long)N, K);
+        return FTK_EINVAL;
+    }
+    FTK_TRY(check_workspace(workspace, workspace_bytes, ftk_workspace_bytes(dtype, N, D, K, ft)));
+    FTK_TRY(check_device());
+    hipStream_t st = (hipStream_t)hip_stream;
+    const Workspace w = carve_workspace(workspace, dtype, N, D, K, ft);
+
+    if (C_init) {
+        FTK_TRY_HIP(hipMemcpyAsync(w.C_cur, C_init, (size_t)K * D * esz, hipMemcpyDeviceToDevice, st));
+    } else {
+        std::vector<int64_t> idx((size_t)K);
+        FTK_TRY(ftk_seeded_indices(seed, N, K, idx.data()));
+        FTK_TRY_HIP(hipMemcpyAsync(w.idx, idx.data(), (size_t)K * sizeof(int64_t), hipMemcpyHostToDevice, st));
+        FTK_TRY_HIP(hipStreamSynchronize(st));  // idx lives on this stack frame
+        FTK_TRY(launch_gather_rows(dtype, X, D, w.idx, K, w.C_cur, st));
+    }
+    FTK_TRY(launch_absmax(dtype, X, N * (int64_t)D, w.absmax, st));
+    for (int t = 0; t < iters; ++t) {
+        AssignCall c{dtype, X, w.C_cur, N, D, K, labels_out, w.mindist, ft, nullptr, 0, stats};
+        FTK_TRY(assign_impl(c, workspace, st));
+        if (inertia_per_iter)
+            FTK_TRY(launch_sum_to_double(dtype, w.mindist, N, w.partials, w.inertia + t, st));
+        FTK_TRY(launch_update(dtype, X, labels_out, N, D, K, w.C_cur, counts_out, w.absmax, w, st));
+    }
+    FTK_TRY_HIP(hipMemcpyAsync(C_out, w.C_cur, (size_t)K * D * esz, hipMemcpyDeviceToDevice, st));
+    if (inertia_per_iter && iters > 0) {
+        FTK_TRY_HIP(hipMemcpyAsync(inertia_per_iter, w.inertia, (size_t)iters * sizeof(double),
+                                   hipMemcpyDeviceToHost, st));
+        FTK_TRY_HIP(hipStreamSynchronize(st));
+    }
+    return FTK_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,387 @@
+// Generic assignment kernel: any D, any K, fp32 and fp64.
+//
+// Computes, for every point, the centroid maximising the score
+//     s_ij = x_i . c_j - ||c_j||^2 / 2  =  ( ||x_i||^2 - ||x_i - c_j||^2 ) / 2
+// i.e. the expansion of Section 3.1.2 with the point norm (constant per point) left out of
+// the comparison.  The contraction runs on the matrix cores; the accumulators start at
+// -||c_j||^2/2 so the epilogue needs no norm arithmetic.  The arg-max is fused in registers
+// (Sections 3.1.3-3.1.5): a workgroup owns a block of points and sweeps all K centroids, so
+// no cross-workgroup combine (the lock/broadcast step of Section 3.1.4) is needed.
+//
+// Rounding: the expanded form cancels catastrophically when ||x||^2 dwarfs the gap between
+// the two nearest centroids.  The epilogue therefore keeps the three best scores and the two
+// best indices; a point whose runner-up lies within a rigorous rounding bound of the winner
+// is settled by evaluating the two candidates in direct-difference form in double, and a
+// point with three or more candidates inside the bound is queued for the refine kernel.
+#include <type_traits>
+
+#include "ftk_internal.h"
+#include "ftk_mma.h"
+
+namespace ftk {
+
+template <typename T>
+struct GenericArgs {
+    const T *X;
+    const T *C;
+    const T *hcn;        // half squared norms, padded with zeros to nkc*KC entries
+    const double *scal;  // scal[0] = max_j ||c_j||^2
+    int64_t N;
+    int D, K, D8, DQ, nkc;
+    int32_t *labels;
+    T *mindist;  // may be null
+    int32_t *wl;
+    int32_t *wl_count;
+    ftk_ft_stats *stats;
+    double band_coef;  // ambiguity band = band_coef * (||x|| * max||c|| + max||c||^2 / 2)
+};
+
+template <typename T>
+struct GenericCfg;
+template <>
+struct GenericCfg<float> {
+    static constexpr int PT = 2, KT = 4, WAVES = 4, DQMAX = 8;
+};
+template <>
+struct GenericCfg<double> {
+    static constexpr int PT = 4, KT = 4, WAVES = 4, DQMAX = 8;
+};
+
+// Running best-three scores and best-two indices of one point.
+template <typename T>
+struct Top3 {
+    T m1, m2, m3;
+    int i1, i2;
+};
+
+// Insert score s (centroid j).  Written on by-value locals so that every choice is a select
+// (v_cndmask) rather than a branch.
+template <typename T>
+__device__ __forceinline__ Top3<T> top3_insert(Top3<T> b, T s, int j)
+{
+    const T m1 = b.m1, m2 = b.m2, m3 = b.m3;
+    const int i1 = b.i1, i2 = b.i2;
+    const bool c1 = s > m1;
+    const bool c2 = s > m2;
+    const int i2a = c2 ? j : i2;
+    Top3<T> o;
+    o.i2 = c1 ? i1 : i2a;
+    o.i1 = c1 ? j : i1;
+    o.m3 = Mma<T>::med3(m2, m3, s);
+    o.m2 = Mma<T>::med3(m1, m2, s);
+    o.m1 = c1 ? s : m1;
+    return o;
+}
+
+template <typename T, bool ALIGNED>
+__global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a)
+{
+    using M = Mma<T>;
+    using Cfg = GenericCfg<T>;
+    using frag_t = typename M::frag_t;
+    using acc_t = typename M::acc_t;
+    constexpr int TM = M::TM, TN = M::TN, G = M::G, R = M::R, E = M::E;
+    constexpr int PT = Cfg::PT, KT = Cfg::KT, KC = KT * TM;
+
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int col = lane % TN;
+    const int g = lane / TN;
+    const int D = a.D;
+    const int SB = 8 * a.DQ * (int)sizeof(T) + 16;  // LDS row stride in bytes
+    const int ndc = (a.D8 / 8 + a.DQ - 1) / a.DQ;   // D-stages per K-chunk
+    const int nq = a.D8 / 8;                        // quads in total
+
+    const int64_t p0 = ((int64_t)blockIdx.x * Cfg::WAVES + wave) * (PT * TN);
+    const T *xrow[PT];
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt) {
+        int64_t p = p0 + pt * TN + col;
+        if (p >= a.N) p = a.N - 1;  // clamped rows are computed and discarded
+        xrow[pt] = a.X + p * D;
+    }
+
+    Top3<T> best[PT];
+    T xn[PT];
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt) {
+        best[pt].m1 = best[pt].m2 = best[pt].m3 = M::neg_inf();
+        best[pt].i1 = best[pt].i2 = 0;
+        xn[pt] = T(0);
+    }
+
+    // quad 0 of this wave's points; afterwards every quad is prefetched one step ahead and the
+    // prefetch wraps to quad 0 at the end of a K-chunk
+    frag_t xcur[PT];
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt) xcur[pt] = load_frag<T, ALIGNED>(xrow[pt], E * g, D);
+
+    for (int kc = 0; kc < a.nkc; ++kc) {
+        const int jbase = kc * KC;
+        acc_t acc[PT][KT];
+#pragma unroll
+        for (int t = 0; t < KT; ++t) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const T h = a.hcn[jbase + t * TM + M::row(r, g)];
+#pragma unroll
+                for (int pt = 0; pt < PT; ++pt) acc[pt][t][r] = -h;
+            }
+        }
+
+        for (int dc = 0; dc < ndc; ++dc) {
+            const int q0 = dc * a.DQ;
+            const int dq = min(a.DQ, nq - q0);
+            __syncthreads();  // readers of the previous stage are done
+            // stage C[jbase .. jbase+KC) x [8*q0 .. 8*(q0+dq)) into LDS, zero beyond K / D
+            {
+                const int ppr = dq * 8 / E;  // 16-byte pieces per row
+                for (int idx = tid; idx < KC * ppr; idx += 256) {
+                    const int rrow = idx / ppr;
+                    const int pc = idx - rrow * ppr;
+                    const int j = jbase + rrow;
+                    frag_t f;
+                    if (j < a.K) {
+                        f = load_frag<T, ALIGNED>(a.C + (int64_t)j * D, q0 * 8 + pc * E, D);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < E; ++e) f[e] = T(0);
+                    }
+                    *reinterpret_cast<frag_t *>(lds_raw + rrow * SB + pc * 16) = f;
+                }
+            }
+            __syncthreads();
+
+            for (int q = 0; q < dq; ++q) {
+                // prefetch the next quad of this wave's points (wraps to quad 0 at the end)
+                int qn = q0 + q + 1;
+                if (qn >= nq) qn = 0;
+                frag_t xnext[PT];
+#pragma unroll
+                for (int pt = 0; pt < PT; ++pt)
+                    xnext[pt] = load_frag<T, ALIGNED>(xrow[pt], qn * 8 + E * g, D);
+
+                if (kc == 0) {
+#pragma unroll
+                    for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+                        for (int e = 0; e < E; ++e) xn[pt] = fma(xcur[pt][e], xcur[pt][e], xn[pt]);
+                }
+#pragma unroll
+                for (int t = 0; t < KT; ++t) {
+                    const frag_t av = *reinterpret_cast<const frag_t *>(
+                        lds_raw + (t * TM + lane % TM) * SB + q * (8 * (int)sizeof(T)) + g * 16);
+#pragma unroll
+                    for (int e = 0; e < E; ++e)
+#pragma unroll
+                        for (int pt = 0; pt < PT; ++pt)
+                            acc[pt][t] = M::mma(av[e], xcur[pt][e], acc[pt][t]);
+                }
+#pragma unroll
+                for (int pt = 0; pt < PT; ++pt) xcur[pt] = xnext[pt];
+            }
+        }
+
+        // fused epilogue: running top-3 over this chunk's scores (rows beyond K only exist in the
+        // last chunk; the two variants keep the common path free of the bounds select)
+        auto epilogue = [&](auto tail_tag) {
+            constexpr bool TAIL = decltype(tail_tag)::value;
+#pragma unroll
+            for (int pt = 0; pt < PT; ++pt) {
+#pragma unroll
+                for (int t = 0; t < KT; ++t) {
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        const int j = jbase + t * TM + M::row(r, g);
+                        T s = acc[pt][t][r];
+                        if constexpr (TAIL) s = (j < a.K) ? s : M::neg_inf();
+                        best[pt] = top3_insert<T>(best[pt], s, j);
+                    }
+                }
+            }
+        };
+        if (jbase + KC > a.K)
+            epilogue(std::true_type{});
+        else
+            epilogue(std::false_type{});
+    }
+
+    // combine the lane groups that share a point
+    const T cmax2 = (T)a.scal[0];
+    const T cmax = sqrt(cmax2);
+    uint64_t n_refined = 0;
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt) {
+#pragma unroll
+        for (int mask = TN; mask < 64; mask <<= 1) {
+            const T b1 = shfl_xor_t(best[pt].m1, mask), b2 = shfl_xor_t(best[pt].m2, mask),
+                    b3 = shfl_xor_t(best[pt].m3, mask);
+            const int j1 = shfl_xor_t(best[pt].i1, mask), j2 = shfl_xor_t(best[pt].i2, mask);
+            best[pt] = top3_insert<T>(best[pt], b1, j1);
+            best[pt] = top3_insert<T>(best[pt], b2, j2);
+            best[pt].m3 = M::med3(best[pt].m2, best[pt].m3, b3);  // b3 <= b2 can never pass m2
+            xn[pt] += shfl_xor_t(xn[pt], mask);
+        }
+        const T m1 = best[pt].m1, m2 = best[pt].m2, m3 = best[pt].m3;
+        const int i1 = best[pt].i1, i2 = best[pt].i2;
+        // After the exchange both partners hold the same multiset of values but may order
+        // equal scores differently; everything below only depends on values, and candidate
+        // indices are made symmetric by ordering the pair.
+        const int64_t p = p0 + pt * TN + col;
+        const bool live = p < a.N;
+        const T bound = (T)a.band_coef * (sqrt(xn[pt]) * cmax + (T)0.5 * cmax2);
+        const bool amb2 = (m1 - m2) <= bound;
+        const bool amb3 = (m1 - m3) <= bound;
+        int label = i1;
+        T dist = xn[pt] - (T)2 * m1;
+        dist = dist > T(0) ? dist : T(0);
+        if (live && amb3) {
+            if (g == 0) {
+                const int pos = atomicAdd(a.wl_count, 1);
+                a.wl[pos] = (int32_t)p;
+            }
+        } else if (live && amb2) {
+            // two candidates: lane groups 0/1 each evaluate one of them exactly
+            const int ja = min(i1, i2), jb = max(i1, i2);
+            const int mine = (g & 1) ? jb : ja;
+            const double dm = exact_sqdist<T>(xrow[pt], a.C + (int64_t)mine * D, D);
+            const double dother = shfl_xor_t(dm, TN);
+            const double da = (g & 1) ? dother : dm;
+            const double db = (g & 1) ? dm : dother;
+            label = (db < da) ? jb : ja;  // equal distances: lower index
+            dist = (T)((db < da) ? db : da);
+            if (g == 0) n_refined += 1;
+        }
+        if (live && g == 0) {
+            a.labels[p] = label;
+            if (a.mindist) a.mindist[p] = dist;
+        }
+    }
+    if (a.stats) {
+        int n = (int)n_refined;
+#pragma unroll
+        for (int mask = 1; mask < 64; mask <<= 1) n += __shfl_xor(n, mask, 64);
+        if (lane == 0 && n) atomicAdd((unsigned long long *)&a.stats->refined, (unsigned long long)n);
+    }
+}
+
+// One wave per queued point: all K exact distances, wave-wide arg-min (lowest index on ties).
+template <typename T>
+__global__ __launch_bounds__(256) void refine_kernel(const T *X, const T *C, int D, int K,
+                                                     const int32_t *wl, const int32_t *wl_count,
+                                                     int32_t *labels, T *mindist, ftk_ft_stats *stats)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave_global = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int n_waves = (gridDim.x * blockDim.x) >> 6;
+    const int count = *wl_count;
+    for (int w = wave_global; w < count; w += n_waves) {
+        const int64_t p = wl[w];
+        const T *x = X + p * D;
+        double best = __builtin_huge_val();
+        int bj = 0x7fffffff;
+        for (int j = lane; j < K; j += 64) {
+            const double d = exact_sqdist<T>(x, C + (int64_t)j * D, D);
+            if (d < best) {  // j increases within a lane: first minimum kept
+                best = d;
+                bj = j;
+            }
+        }
+#pragma unroll
+        for (int mask = 1; mask < 64; mask <<= 1) {
+            const double ob = __shfl_xor(best, mask, 64);
+            const int oj = __shfl_xor(bj, mask, 64);
+            if (ob < best || (ob == best && oj < bj)) {
+                best = ob;
+                bj = oj;
+            }
+        }
+        if (lane == 0) {
+            labels[p] = bj == 0x7fffffff ? 0 : bj;
+            if (mindist) mindist[p] = (T)best;
+        }
+    }
+    if (stats && wave_global == 0 && lane == 0 && count > 0)
+        atomicAdd((unsigned long long *)&stats->refined, (unsigned long long)count);
+}
+
+template <typename T>
+static ftk_status launch_generic_t(const AssignCall &c, const AssignPlan &p, const Workspace &w,
+                                   hipStream_t st)
+{
+    GenericArgs<T> a;
+    a.X = (const T *)c.X;
+    a.C = (const T *)c.C;
+    a.hcn = (const T *)w.hcn;
+    a.scal = w.scal;
+    a.N = c.N;
+    a.D = c.D;
+    a.K = c.K;
+    a.D8 = p.D8;
+    a.DQ = p.DQ;
+    a.nkc = p.nkc;
+    a.labels = c.labels;
+    a.mindist = (T *)c.mindist;
+    a.wl = w.wl;
+    a.wl_count = w.wl_count;
+    a.stats = c.stats;
+    // |fl(s) - s| <= gamma * (|x|.|c| + |c|^2/2) with gamma = (D+4) * 2u (matrix-core products and
+    // accumulation each rounded once, factor two of slack); two scores -> twice that.
+    a.band_coef = 4.0 * (c.D + 4) * Mma<T>::kEps;
+    const bool aligned = (c.D % Mma<T>::E == 0) && ((uintptr_t)c.X % 16 == 0) && ((uintptr_t)c.C % 16 == 0);
+    dim3 grid((unsigned)p.workgroups), block(256);
+    if (aligned)
+        hipLaunchKernelGGL((assign_generic_kernel<T, true>), grid, block, p.lds_bytes, st, a);
+    else
+        hipLaunchKernelGGL((assign_generic_kernel<T, false>), grid, block, p.lds_bytes, st, a);
+    FTK_TRY_HIP(hipGetLastError());
+    return FTK_OK;
+}
+
+ftk_status launch_assign_generic(const AssignCall &c, const AssignPlan &p, const Workspace &w,
+                                 hipStream_t st)
+{
+    return c.dtype == FTK_F32 ? launch_generic_t<float>(c, p, w, st)
+                              : launch_generic_t<double>(c, p, w, st);
+}
+
+ftk_status launch_refine(const AssignCall &c, const Workspace &w, hipStream_t st)
+{
+    dim3 grid(1024), block(256);
+    if (c.dtype == FTK_F32)
+        hipLaunchKernelGGL((refine_kernel<float>), grid, block, 0, st, (const float *)c.X,
+                           (const float *)c.C, c.D, c.K, w.wl, w.wl_count, c.labels,
+                           (float *)c.mindist, c.stats);
+    else
+        hipLaunchKernelGGL((refine_kernel<double>), grid, block, 0, st, (const double *)c.X,
+                           (const double *)c.C, c.D, c.K, w.wl, w.wl_count, c.labels,
+                           (double *)c.mindist, c.stats);
+    FTK_TRY_HIP(hipGetLastError());
+    return FTK_OK;
+}
+
+void plan_generic(ftk_dtype dtype, int64_t N, int D, int K, AssignPlan &p)
+{
+    const bool f32 = dtype == FTK_F32;
+    p.variant = VAR_GENERIC;
+    p.TM = f32 ? Mma<float>::TM : Mma<double>::TM;
+    p.TN = f32 ? Mma<float>::TN : Mma<double>::TN;
+    p.PT = f32 ? GenericCfg<float>::PT : GenericCfg<double>::PT;
+    p.KT = f32 ? GenericCfg<float>::KT : GenericCfg<double>::KT;
+    p.waves = 4;
+    p.KC = p.KT * p.TM;
+    p.nkc = (int)ceil_div(K, p.KC);
+    p.D8 = (int)ceil_div(D, 8) * 8;
+    p.DQ = (int)((p.D8 / 8 < 8) ? p.D8 / 8 : 8);
+    p.points_per_wg = p.waves * p.PT * p.TN;
+    p.workgroups = ceil_div(N, p.points_per_wg);
+    p.tiles_per_wave = p.nkc * p.PT * p.KT;
+    p.regs_per_tile = f32 ? Mma<float>::R : Mma<double>::R;
+    const size_t esz = f32 ? 4 : 8;
+    p.lds_bytes = (size_t)(p.KC + p.KT) * (8 * p.DQ * esz + 16);
+}
+
+}  // namespace ftk

@@ -1,0 +1,105 @@
+// Internal declarations shared by the translation units of libftkmeans (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ftkmeans.h"
+
+namespace ftk {
+
+// ---- error reporting -------------------------------------------------------------------
+void set_error(const char *fmt, ...) __attribute__((format(printf, 1, 2)));
+ftk_status hip_failed(hipError_t e, const char *what);
+
+#define FTK_TRY_HIP(expr)                                      \
+    do {                                                       \
+        hipError_t e_ = (expr);                                \
+        if (e_ != hipSuccess) return ftk::hip_failed(e_, #expr); \
+    } while (0)
+
+#define FTK_TRY(expr)                  \
+    do {                               \
+        ftk_status s_ = (expr);        \
+        if (s_ != FTK_OK) return s_;   \
+    } while (0)
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ---- assignment kernel geometry ----------------------------------------------------------
+// One output tile of the matrix instruction covers TM centroids (rows, register axis) by TN
+// points (columns, lane axis).  A wave owns PT point tiles and keeps KT centroid tiles of
+// accumulators per point tile; a workgroup has 4 waves.
+enum AssignVariant : int {
+    VAR_GENERIC = 0,  // any D, any K: K in chunks of KT tiles, D streamed through LDS
+    VAR_SMALLD = 1    // fp32, D <= 32: point fragments stay in registers for the whole sweep
+};
+
+struct AssignPlan {
+    AssignVariant variant;
+    int TM, TN, PT, KT, waves;  // tile extents and per-wave blocking
+    int KC;                     // centroids per K-chunk (= KT*TM)
+    int nkc;                    // number of K-chunks
+    int D8;                     // D rounded up to a multiple of 8
+    int DQ;                     // quads (8 features) per LDS stage
+    int points_per_wg;
+    int64_t workgroups;
+    int tiles_per_wave;         // output tiles a wave finishes (fault addressing)
+    int regs_per_tile;
+    size_t lds_bytes;
+};
+AssignPlan plan_assign(ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft);
+
+// ---- workspace carving --------------------------------------------------------------------
+struct Workspace {
+    // assignment
+    void *hcn;          // [Kpad] half squared centroid norms (dtype), zero padded
+    double *scal;       // [8]   0: max_j ||c_j||^2 (as double bits, atomically maximised)
+    void *chk_v1;       // [nkc*KT][D8] per-tile plain checksum rows (dtype)
+    void *chk_v2;       // [nkc*KT][D8] per-tile weighted checksum rows (dtype)
+    void *chk_s;        // [nkc*KT][2]  their half-norm terms (dtype)
+    int32_t *wl_count;  // [4]   refine work-list length (+ padding)
+    int32_t *wl;        // [N]   refine work-list (point indices)
+    // update
+    int64_t *fx_sums;   // [K*D] fixed-point sums
+    double *absmax;     // [2]
+    // fit
+    void *C_cur;        // [K*D] running centroids (dtype)
+    void *mindist;      // [N]   (dtype)
+    double *inertia;    // [iters_max] per-iteration objective
+    double *partials;   // [1024] block partial sums
+    int64_t *idx;       // [K]   seeded initial point indices
+    size_t total;
+};
+constexpr int FIT_MAX_ITERS_IN_WS = 4096;
+Workspace carve_workspace(void *base, ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft);
+
+// ---- launches (each returns after enqueueing on `st`) ------------------------------------
+struct AssignCall {
+    ftk_dtype dtype;
+    const void *X, *C;
+    int64_t N;
+    int D, K;
+    int32_t *labels;
+    void *mindist;
+    ftk_ft_mode ft;
+    const ftk_fault *faults;
+    int n_faults;
+    ftk_ft_stats *stats;
+};
+ftk_status launch_centroid_prologue(const AssignCall &c, const AssignPlan &p, const Workspace &w,
+                                    hipStream_t st);
+ftk_status launch_assign(const AssignCall &c, const AssignPlan &p, const Workspace &w, hipStream_t st);
+ftk_status launch_refine(const AssignCall &c, const Workspace &w, hipStream_t st);
+
+ftk_status launch_absmax(ftk_dtype dtype, const void *X, int64_t count, double *out, hipStream_t st);
+ftk_status launch_update(ftk_dtype dtype, const void *X, const int32_t *labels, int64_t N, int D,
+                         int K, void *C, int32_t *counts, const double *absmax, const Workspace &w,
+                         hipStream_t st);
+ftk_status launch_gather_rows(ftk_dtype dtype, const void *X, int D, const int64_t *idx_dev, int K,
+                              void *C, hipStream_t st);
+ftk_status launch_sum_to_double(ftk_dtype dtype, const void *v, int64_t n, double *partials,
+                                double *out, hipStream_t st);
+
+}  // namespace ftk

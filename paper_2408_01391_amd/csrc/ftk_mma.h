@@ -1,0 +1,115 @@
+// Matrix-instruction traits for gfx950 and small device helpers (internal).
+//
+// Orientation used throughout: the A operand holds CENTROIDS (output rows, spread over the
+// accumulator registers of a lane), the B operand holds POINTS (output columns, one per
+// lane).  A lane therefore owns one point and sees that point's scores against several
+// centroids in its own registers, so the running arg-max of the fused epilogue
+// (paper Sections 3.1.3-3.1.5) and the per-point checksums (Section 4) need no cross-lane
+// traffic until the very end.
+//
+// Lane layouts (checked on hardware by tests/test_gpu_layout.py):
+//   v_mfma_f32_32x32x2_f32 : lane l supplies A[l%32][l/32] and B[l/32][l%32];
+//                            register r of lane l holds D[8*(r/4) + 4*(l/32) + r%4][l%32].
+//   v_mfma_f64_16x16x4_f64 : lane l supplies A[l%16][l/16] and B[l/16][l%16];
+//                            register r of lane l holds D[4*r + l/16][l%16].
+// The contraction index may be permuted freely as long as both operands use the same
+// permutation: lane group g = l/TN takes features 8q + E*g .. 8q + E*g + E-1 of "quad" q
+// (8 consecutive features), which makes every operand fetch one aligned 16-byte access.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+namespace ftk {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef double doublex4 __attribute__((ext_vector_type(4)));
+typedef double doublex2 __attribute__((ext_vector_type(2)));
+
+template <typename T>
+struct Mma;
+
+template <>
+struct Mma<float> {
+    static constexpr int TM = 32;  // centroids per tile
+    static constexpr int TN = 32;  // points per tile
+    static constexpr int G = 2;    // lane groups sharing a point
+    static constexpr int R = 16;   // accumulator registers per lane per tile
+    static constexpr int E = 4;    // elements per 16-byte fragment
+    using acc_t = floatx16;
+    using frag_t = floatx4;
+    static constexpr double kEps = 5.9604644775390625e-08;  // 2^-24
+    static __device__ __forceinline__ int row(int r, int g) { return 8 * (r >> 2) + 4 * g + (r & 3); }
+    static __device__ __forceinline__ acc_t mma(float a, float b, acc_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ float med3(float a, float b, float c)
+    {
+        return __builtin_amdgcn_fmed3f(a, b, c);
+    }
+    static __device__ __forceinline__ float neg_inf() { return -__builtin_huge_valf(); }
+};
+
+template <>
+struct Mma<double> {
+    static constexpr int TM = 16;
+    static constexpr int TN = 16;
+    static constexpr int G = 4;
+    static constexpr int R = 4;
+    static constexpr int E = 2;
+    using acc_t = doublex4;
+    using frag_t = doublex2;
+    static constexpr double kEps = 1.1102230246251565e-16;  // 2^-53
+    static __device__ __forceinline__ int row(int r, int g) { return 4 * r + g; }
+    static __device__ __forceinline__ acc_t mma(double a, double b, acc_t c)
+    {
+        return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ double med3(double a, double b, double c)
+    {
+        // median of three; callers pass a >= b
+        return fmax(b, fmin(a, c));
+    }
+    static __device__ __forceinline__ double neg_inf() { return -__builtin_huge_val(); }
+};
+
+// E consecutive elements of a row starting at feature d0, zero beyond D.
+template <typename T, bool ALIGNED>
+__device__ __forceinline__ typename Mma<T>::frag_t load_frag(const T *row, int d0, int D)
+{
+    using F = typename Mma<T>::frag_t;
+    F f;
+    if constexpr (ALIGNED) {
+        if (d0 < D) {
+            f = *reinterpret_cast<const F *>(row + d0);
+        } else {
+#pragma unroll
+            for (int e = 0; e < Mma<T>::E; ++e) f[e] = T(0);
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < Mma<T>::E; ++e) f[e] = (d0 + e < D) ? row[d0 + e] : T(0);
+    }
+    return f;
+}
+
+// Squared distance in the direct-difference form of the basic kernel (Section 3.1.1),
+// accumulated in double.  Used to settle points whose best scores are closer than the
+// rounding-error bound of the expanded form.
+template <typename T>
+__device__ __forceinline__ double exact_sqdist(const T *x, const T *c, int D)
+{
+    double s = 0.0;
+    for (int d = 0; d < D; ++d) {
+        double diff = (double)x[d] - (double)c[d];
+        s = fma(diff, diff, s);
+    }
+    return s;
+}
+
+__device__ __forceinline__ float shfl_xor_t(float v, int m) { return __shfl_xor(v, m, 64); }
+__device__ __forceinline__ double shfl_xor_t(double v, int m) { return __shfl_xor(v, m, 64); }
+__device__ __forceinline__ int shfl_xor_t(int v, int m) { return __shfl_xor(v, m, 64); }
+
+}  // namespace ftk

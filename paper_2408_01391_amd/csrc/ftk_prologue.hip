@@ -1,0 +1,261 @@
+// Small helper kernels around the assignment step: centroid norms (the "simple kernels" of
+// Section 3.1.2), per-tile checksum rows of the centroid operand (the Y e1 / Y e2 encodings
+// of Section 4.1), |x| maximum, row gather for the initial centroids, and a fixed-order sum.
+#include "ftk_internal.h"
+#include "ftk_mma.h"
+
+namespace ftk {
+
+__global__ void reset_assign_state_kernel(double *scal, int32_t *wl_count)
+{
+    if (threadIdx.x == 0) {
+        scal[0] = 0.0;
+        wl_count[0] = 0;
+    }
+}
+
+// One wave per centroid row j < Kpad: hcn[j] = ||c_j||^2 / 2 (accumulated in double), zero for
+// the padding rows; scal[0] = max_j ||c_j||^2 via an integer max on the bit pattern (valid for
+// non-negative doubles).
+template <typename T>
+__global__ __launch_bounds__(256) void centroid_norms_kernel(const T *C, int D, int K, int Kpad, T *hcn,
+                                                             double *scal)
+{
+    const int lane = threadIdx.x & 63;
+    const int j = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    if (j >= Kpad) return;
+    double s = 0.0;
+    if (j < K) {
+        const T *c = C + (int64_t)j * D;
+        for (int d = lane; d < D; d += 64) {
+            const double v = (double)c[d];
+            s = fma(v, v, s);
+        }
+    }
+#pragma unroll
+    for (int mask = 32; mask >= 1; mask >>= 1) s += __shfl_xor(s, mask, 64);
+    if (lane == 0) {
+        hcn[j] = (T)(0.5 * s);
+        if (j < K) atomicMax((unsigned long long *)scal, (unsigned long long)__double_as_longlong(s));
+    }
+}
+
+// Checksum rows of one centroid tile (TM consecutive centroids): thread d forms
+//   v1[d] = sum_r c_{r,d}            (weights e1 = 1)
+//   v2[d] = sum_r (r+1) c_{r,d}      (weights e2 = 1..TM)
+// in double and rounds once; thread 0 also forms the matching sums of the half norms.
+template <typename T>
+__global__ __launch_bounds__(256) void centroid_checksum_kernel(const T *C, const T *hcn, int D, int D8,
+                                                                int K, int TM, T *v1, T *v2, T *cs)
+{
+    const int tile = blockIdx.x;
+    const int j0 = tile * TM;
+    for (int d = threadIdx.x; d < D8; d += blockDim.x) {
+        double s1 = 0.0, s2 = 0.0;
+        if (d < D) {
+            for (int r = 0; r < TM; ++r) {
+                const int j = j0 + r;
+                if (j >= K) break;
+                const double v = (double)C[(int64_t)j * D + d];
+                s1 += v;
+                s2 = fma((double)(r + 1), v, s2);
+            }
+        }
+        v1[(int64_t)tile * D8 + d] = (T)s1;
+        v2[(int64_t)tile * D8 + d] = (T)s2;
+    }
+    if (threadIdx.x == 0) {
+        double h1 = 0.0, h2 = 0.0;
+        for (int r = 0; r < TM; ++r) {
+            const int j = j0 + r;
+            if (j >= K) break;
+            const double h = (double)hcn[j];
+            h1 += h;
+            h2 = fma((double)(r + 1), h, h2);
+        }
+        cs[2 * tile] = (T)h1;
+        cs[2 * tile + 1] = (T)h2;
+    }
+}
+
+ftk_status launch_centroid_prologue(const AssignCall &c, const AssignPlan &p, const Workspace &w,
+                                    hipStream_t st)
+{
+    hipLaunchKernelGGL(reset_assign_state_kernel, dim3(1), dim3(64), 0, st, w.scal, w.wl_count);
+    const int Kpad = p.nkc * p.KC;
+    const int blocks = (int)ceil_div(Kpad, 4);
+    const int ntiles = p.nkc * p.KT;
+    if (c.dtype == FTK_F32) {
+        hipLaunchKernelGGL((centroid_norms_kernel<float>), dim3(blocks), dim3(256), 0, st,
+                           (const float *)c.C, c.D, c.K, Kpad, (float *)w.hcn, w.scal);
+        if (c.ft != FTK_FT_OFF)
+            hipLaunchKernelGGL((centroid_checksum_kernel<float>), dim3(ntiles), dim3(256), 0, st,
+                               (const float *)c.C, (const float *)w.hcn, c.D, p.D8, c.K, p.TM,
+                               (float *)w.chk_v1, (float *)w.chk_v2, (float *)w.chk_s);
+    } else {
+        hipLaunchKernelGGL((centroid_norms_kernel<double>), dim3(blocks), dim3(256), 0, st,
+                           (const double *)c.C, c.D, c.K, Kpad, (double *)w.hcn, w.scal);
+        if (c.ft != FTK_FT_OFF)
+            hipLaunchKernelGGL((centroid_checksum_kernel<double>), dim3(ntiles), dim3(256), 0, st,
+                               (const double *)c.C, (const double *)w.hcn, c.D, p.D8, c.K, p.TM,
+                               (double *)w.chk_v1, (double *)w.chk_v2, (double *)w.chk_s);
+    }
+    FTK_TRY_HIP(hipGetLastError());
+    return FTK_OK;
+}
+
+// ---- |x| maximum ---------------------------------------------------------------------------
+__global__ void reset_double_kernel(double *p)
+{
+    if (threadIdx.x == 0) p[0] = 0.0;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void absmax_kernel(const T *X, int64_t count, double *out)
+{
+    double m = 0.0;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
+        const double v = fabs((double)X[i]);
+        m = v > m ? v : m;  // NaN never raises the maximum
+    }
+#pragma unroll
+    for (int mask = 32; mask >= 1; mask >>= 1) {
+        const double o = __shfl_xor(m, mask, 64);
+        m = o > m ? o : m;
+    }
+    if ((threadIdx.x & 63) == 0 && m > 0.0)
+        atomicMax((unsigned long long *)out, (unsigned long long)__double_as_longlong(m));
+}
+
+// 16-byte vectorised variant for aligned, large inputs
+template <typename T>
+__global__ __launch_bounds__(256) void absmax_vec_kernel(const T *X, int64_t nvec, double *out)
+{
+    using F = typename Mma<T>::frag_t;
+    constexpr int E = Mma<T>::E;
+    const F *Xv = reinterpret_cast<const F *>(X);
+    T m = T(0);
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += stride) {
+        const F f = Xv[i];
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const T v = fabs(f[e]);
+            m = v > m ? v : m;
+        }
+    }
+    double md = (double)m;
+#pragma unroll
+    for (int mask = 32; mask >= 1; mask >>= 1) {
+        const double o = __shfl_xor(md, mask, 64);
+        md = o > md ? o : md;
+    }
+    if ((threadIdx.x & 63) == 0 && md > 0.0)
+        atomicMax((unsigned long long *)out, (unsigned long long)__double_as_longlong(md));
+}
+
+ftk_status launch_absmax(ftk_dtype dtype, const void *X, int64_t count, double *out, hipStream_t st)
+{
+    hipLaunchKernelGGL(reset_double_kernel, dim3(1), dim3(64), 0, st, out);
+    const int E = dtype == FTK_F32 ? 4 : 2;
+    const size_t esz = dtype == FTK_F32 ? 4 : 8;
+    int64_t nvec = ((uintptr_t)X % 16 == 0) ? count / E : 0;
+    if (nvec > 0) {
+        const int blocks = (int)(ceil_div(nvec, 256) < 2048 ? ceil_div(nvec, 256) : 2048);
+        if (dtype == FTK_F32)
+            hipLaunchKernelGGL((absmax_vec_kernel<float>), dim3(blocks), dim3(256), 0, st,
+                               (const float *)X, nvec, out);
+        else
+            hipLaunchKernelGGL((absmax_vec_kernel<double>), dim3(blocks), dim3(256), 0, st,
+                               (const double *)X, nvec, out);
+    }
+    const int64_t done = nvec * E;
+    if (done < count) {
+        const int64_t rest = count - done;
+        const int blocks = (int)(ceil_div(rest, 256) < 1024 ? ceil_div(rest, 256) : 1024);
+        const char *tail = (const char *)X + done * esz;
+        if (dtype == FTK_F32)
+            hipLaunchKernelGGL((absmax_kernel<float>), dim3(blocks), dim3(256), 0, st,
+                               (const float *)tail, rest, out);
+        else
+            hipLaunchKernelGGL((absmax_kernel<double>), dim3(blocks), dim3(256), 0, st,
+                               (const double *)tail, rest, out);
+    }
+    FTK_TRY_HIP(hipGetLastError());
+    return FTK_OK;
+}
+
+// ---- initial centroids: C[k] = X[idx[k]] ------------------------------------------------
+template <typename T>
+__global__ void gather_rows_kernel(const T *X, int D, const int64_t *idx, int K, T *C)
+{
+    const int k = blockIdx.x;
+    if (k >= K) return;
+    const T *src = X + idx[k] * D;
+    for (int d = threadIdx.x; d < D; d += blockDim.x) C[(int64_t)k * D + d] = src[d];
+}
+
+ftk_status launch_gather_rows(ftk_dtype dtype, const void *X, int D, const int64_t *idx_dev, int K,
+                              void *C, hipStream_t st)
+{
+    if (dtype == FTK_F32)
+        hipLaunchKernelGGL((gather_rows_kernel<float>), dim3(K), dim3(64), 0, st, (const float *)X, D,
+                           idx_dev, K, (float *)C);
+    else
+        hipLaunchKernelGGL((gather_rows_kernel<double>), dim3(K), dim3(64), 0, st, (const double *)X,
+                           D, idx_dev, K, (double *)C);
+    FTK_TRY_HIP(hipGetLastError());
+    return FTK_OK;
+}
+
+// ---- objective: sum of a vector in double, fixed order (block partials, then one block) ----
+constexpr int SUM_BLOCKS = 512;
+
+template <typename T>
+__global__ __launch_bounds__(256) void sum_partials_kernel(const T *v, int64_t n, double *partials)
+{
+    __shared__ double sh[256];
+    const int64_t per = (n + gridDim.x - 1) / gridDim.x;
+    const int64_t lo = per * blockIdx.x;
+    const int64_t hi = lo + per < n ? lo + per : n;
+    double s = 0.0;
+    for (int64_t i = lo + threadIdx.x; i < hi; i += 256) s += (double)v[i];
+    sh[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 128; w >= 1; w >>= 1) {
+        if ((int)threadIdx.x < w) sh[threadIdx.x] += sh[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) partials[blockIdx.x] = sh[0];
+}
+
+__global__ __launch_bounds__(256) void sum_final_kernel(const double *partials, int n, double *out)
+{
+    __shared__ double sh[256];
+    double s = 0.0;
+    for (int i = threadIdx.x; i < n; i += 256) s += partials[i];
+    sh[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 128; w >= 1; w >>= 1) {
+        if ((int)threadIdx.x < w) sh[threadIdx.x] += sh[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[0] = sh[0];
+}
+
+ftk_status launch_sum_to_double(ftk_dtype dtype, const void *v, int64_t n, double *partials,
+                                double *out, hipStream_t st)
+{
+    if (dtype == FTK_F32)
+        hipLaunchKernelGGL((sum_partials_kernel<float>), dim3(SUM_BLOCKS), dim3(256), 0, st,
+                           (const float *)v, n, partials);
+    else
+        hipLaunchKernelGGL((sum_partials_kernel<double>), dim3(SUM_BLOCKS), dim3(256), 0, st,
+                           (const double *)v, n, partials);
+    hipLaunchKernelGGL(sum_final_kernel, dim3(1), dim3(256), 0, st, partials, SUM_BLOCKS, out);
+    FTK_TRY_HIP(hipGetLastError());
+    return FTK_OK;
+}
+
+}  // namespace ftk

@@ -1,0 +1,145 @@
+"""GPU parity: the HIP path, called through the C-ABI binding, against the CPU oracle on the same
+seeded inputs.  Labels must be identical except inside the tie band (1e-5 relative for fp32,
+1e-12 for fp64, relative to the best distance); centroids within 1e-4 / 1e-10 relative."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import cpu as oracle
+from paper_2408_01391_amd import binding as ftk, synth
+from tests.gpu_util import (DEV, check_assign, check_centroids, gpu_assign, gpu_update, to_dev)
+
+pytestmark = pytest.mark.gpu
+
+SHAPES = [
+    (1, 1, 1), (5, 3, 2), (64, 4, 64), (100, 7, 5), (300, 8, 33), (1000, 16, 8), (257, 2, 600),
+    (777, 33, 130), (2048, 128, 256), (513, 200, 70), (100, 1, 300), (1500, 64, 129), (640, 24, 1025),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f64"])
+@pytest.mark.parametrize("N,D,K", SHAPES)
+def test_assign_matches_oracle_on_ragged_shapes(dtype, N, D, K):
+    X, C = synth.random_problem(N * 7 + D * 3 + K, N, D, K, dtype)
+    print("assign", dtype, N, D, K, flush=True)
+    labels, mind = gpu_assign(X, C)
+    check_assign(X, C, labels, mind)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f64"])
+def test_assign_exact_on_integers_with_duplicate_centroids(dtype):
+    X, C = synth.random_problem(5, 3000, 12, 40, dtype, integer=True)
+    C[17] = C[3]
+    C[39] = C[3]
+    C[8] = C[30]
+    labels, mind = gpu_assign(X, C)
+    lab_o, d1, _ = oracle.assign(X, C)
+    assert np.array_equal(labels, lab_o)          # every tie to the lowest index
+    assert not np.isin(labels, [17, 39, 30]).any()
+    assert np.allclose(mind, d1, rtol=1e-6, atol=1e-3)
+
+
+def test_assign_offset_data_needs_the_exact_tie_break():
+    """Large common offset: ||x||^2 is ~1e8 while cluster gaps are ~1; the expanded form alone
+    cannot order the two nearest centroids in fp32."""
+    rng = np.random.default_rng(3)
+    X = (rng.normal(size=(4000, 8)) + 3000.0).astype(np.float32)
+    C = X[rng.choice(4000, 50, replace=False)].copy()
+    labels, mind = gpu_assign(X, C)
+    check_assign(X, C, labels)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f64"])
+@pytest.mark.parametrize("N,D,K", [(1, 1, 1), (1000, 8, 16), (5000, 128, 256), (3001, 17, 700),
+                                   (4096, 512, 64), (20000, 32, 4096), (999, 3, 5)])
+def test_update_matches_oracle(dtype, N, D, K):
+    X, C = synth.random_problem(N + D + K, N, D, K, dtype)
+    rng = np.random.default_rng(N)
+    labels = rng.integers(0, max(1, K - 1), size=N).astype(np.int32)   # last cluster stays empty
+    print("update", dtype, N, D, K, flush=True)
+    C_g, counts_g = gpu_update(X, labels, C)
+    C_o, counts_o = oracle.update(X, labels, C)
+    assert np.array_equal(counts_g, counts_o)
+    check_centroids(C_g, C_o)
+    if K > 1:
+        assert np.array_equal(C_g[K - 1], C[K - 1])       # empty cluster keeps its centroid
+
+
+def test_update_is_bitwise_reproducible():
+    X, C = synth.random_problem(77, 50000, 24, 300, "f32")
+    labels = np.random.default_rng(0).integers(0, 300, size=50000).astype(np.int32)
+    a, _ = gpu_update(X, labels, C)
+    for _ in range(3):
+        b, _ = gpu_update(X, labels, C)
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
+def test_absmax():
+    x = np.random.default_rng(1).normal(size=100003).astype(np.float32)
+    x[4711] = -77.5
+    assert float(ftk.absmax(to_dev(x.reshape(1, -1))).cpu()[0]) == 77.5
+
+
+@pytest.mark.parametrize("name,N,iters", [("c1", 4096, 10), ("c2", 1 << 15, 6), ("c3", 1 << 13, 5),
+                                          ("c4", 1 << 12, 4), ("c5", 1 << 14, 4)])
+def test_teacher_forced_lloyd_iterations(name, N, iters):
+    """Per iteration: assign against the oracle's previous centroids, update from the oracle's
+    labels (a free-running comparison would amplify a single tie flip)."""
+    w = synth.WORKLOADS[name]
+    K = min(w.K, N // 4)
+    X, _ = synth.make_points(w, N)
+    C0 = X[synth.init_indices(w, N, K)].copy()
+    ref = oracle.fit(X, C0, iters, history=True)
+    Xd = to_dev(X)
+    C_prev = C0
+    in_band = 0
+    for t in range(iters):
+        print("teacher", name, "iter", t, flush=True)
+        labels, mind = ftk.kmeans_assign(Xd, to_dev(C_prev))
+        torch.cuda.synchronize()
+        nb, _ = check_assign(X, C_prev, labels.cpu().numpy(), mind.cpu().numpy())
+        in_band += nb
+        C_g, counts_g = gpu_update(X, ref["labels_hist"][t], C_prev)
+        check_centroids(C_g, ref["C_hist"][t])
+        C_prev = ref["C_hist"][t]
+    print(name, "labels inside the tie band:", in_band)
+
+
+def test_fit_free_running_matches_oracle_on_c1():
+    w = synth.WORKLOADS["c1"]
+    X, _ = synth.make_points(w)
+    C0 = X[synth.init_indices(w, w.N)].copy()
+    ref = oracle.fit(X, C0, w.iters)
+    out = ftk.kmeans_fit(to_dev(X), w.K, w.iters, C_init=to_dev(C0))
+    assert np.array_equal(out["labels"].cpu().numpy(), ref["labels"])
+    assert np.array_equal(out["counts"].cpu().numpy(), ref["counts"])
+    check_centroids(out["C"].cpu().numpy(), ref["C"])
+    assert np.allclose(out["inertia"], ref["inertia"], rtol=1e-4)
+    assert np.all(np.diff(out["inertia"]) <= 1e-6 * out["inertia"][:-1])
+
+
+def test_fit_seeded_init_uses_the_documented_index_choice():
+    X, _ = synth.random_problem(9, 5000, 6, 10, "f64")
+    idx_o = oracle.seeded_indices(2024, 5000, 10)
+    assert np.array_equal(ftk.seeded_indices(2024, 5000, 10), idx_o)
+    ref = oracle.fit(X, X[idx_o].copy(), 5)
+    out = ftk.kmeans_fit(to_dev(X), 10, 5, seed=2024)
+    assert np.array_equal(out["labels"].cpu().numpy(), ref["labels"])
+    check_centroids(out["C"].cpu().numpy(), ref["C"])
+
+
+def test_error_paths_return_codes_without_touching_the_gpu_state():
+    X = torch.zeros(16, 4, device=DEV)
+    C = torch.zeros(2, 4, device=DEV)
+    small = torch.empty(256, dtype=torch.uint8, device=DEV)
+    with pytest.raises(ftk.FtkError) as e:
+        ftk.kmeans_assign(X, C, workspace=small)
+    assert e.value.code == 3
+    with pytest.raises(ftk.FtkError) as e:
+        ftk.kmeans_fit(X, 32, 1, seed=1)            # K > N with seeded init
+    assert e.value.code == 1
+    with pytest.raises(ValueError):
+        ftk.kmeans_assign(X, torch.zeros(2, 5, device=DEV))
+    labels, _ = ftk.kmeans_assign(X, C)             # still usable afterwards
+    torch.cuda.synchronize()
+    assert labels.cpu().tolist() == [0] * 16
