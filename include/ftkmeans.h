@@ -140,6 +140,15 @@ ftk_status ftk_kmeans_fit(ftk_dtype dtype, const void *X, int64_t N, int32_t D, 
 /* (host) K distinct indices in [0, N) by the seeded procedure ftk_kmeans_fit uses. */
 ftk_status ftk_seeded_indices(uint64_t seed, int64_t N, int32_t K, int64_t *idx_host);
 
+/* Profiling aid for benchmarks.  While enabled, every ftk_kmeans_assign call brackets its main
+ * contraction kernel (not the small norm / refine kernels around it) with a pair of HIP events
+ * recorded on the call's stream.  ftk_profile_read waits for all recorded pairs, returns the
+ * summed kernel time in milliseconds and the number of launches since the last read (host
+ * pointers), and releases the events.  Not thread-safe; creates events, so keep it out of
+ * throughput timing loops. */
+ftk_status ftk_profile_enable(int32_t on);
+ftk_status ftk_profile_read(double *total_ms, int64_t *launches);
+
 const char *ftk_last_error(void);
 const char *ftk_version(void);
 

@@ -57,6 +57,10 @@ def load():
     L.ftk_kmeans_fit.restype = i32
     L.ftk_seeded_indices.argtypes = [u64, i64, i32, vp]
     L.ftk_seeded_indices.restype = i32
+    L.ftk_profile_enable.argtypes = [i32]
+    L.ftk_profile_enable.restype = i32
+    L.ftk_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+    L.ftk_profile_read.restype = i32
     L.ftk_last_error.restype = ctypes.c_char_p
     L.ftk_version.restype = ctypes.c_char_p
     _lib = L
@@ -64,8 +68,8 @@ def load():
 
 
 EXPORTS = ("ftk_workspace_bytes", "ftk_assign_geometry", "ftk_kmeans_assign", "ftk_absmax",
-           "ftk_kmeans_update", "ftk_kmeans_fit", "ftk_seeded_indices", "ftk_last_error",
-           "ftk_version")
+           "ftk_kmeans_update", "ftk_kmeans_fit", "ftk_seeded_indices", "ftk_profile_enable",
+           "ftk_profile_read", "ftk_last_error", "ftk_version")
 
 
 def _check(rc):
@@ -185,6 +189,17 @@ def seeded_indices(seed: int, N: int, K: int):
     idx = np.empty(K, dtype=np.int64)
     _check(load().ftk_seeded_indices(seed & (2**64 - 1), N, K, idx.ctypes.data))
     return idx
+
+
+def profile_enable(on: bool) -> None:
+    _check(load().ftk_profile_enable(1 if on else 0))
+
+
+def profile_read():
+    """(total milliseconds, launches) of the main assignment kernel since the last read."""
+    ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
+    _check(load().ftk_profile_read(ctypes.byref(ms), ctypes.byref(n)))
+    return ms.value, n.value
 
 
 def kmeans_fit(X, K, iters, seed=0, C_init=None, ft_mode=FT_OFF, stats=None, workspace=None,

@@ -3,6 +3,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <utility>
 #include <vector>
 
 #include "ftk_internal.h"
@@ -33,11 +34,11 @@ ftk_status launch_assign_generic(const AssignCall &c, const AssignPlan &p, const
 ftk_status launch_assign_smalld(const AssignCall &c, const AssignPlan &p, const Workspace &w,
                                 hipStream_t st);
 
-AssignPlan plan_assign(ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft)
+AssignPlan plan_assign(ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft, bool aligned16)
 {
     AssignPlan p;
     memset(&p, 0, sizeof(p));
-    if (smalld_supported(dtype, D, K))
+    if (aligned16 && smalld_supported(dtype, D, K))
         plan_smalld(N, D, K, ft, p);
     else
         plan_generic(dtype, N, D, K, p);
@@ -149,12 +150,26 @@ static ftk_status check_device()
     return FTK_OK;
 }
 
+static bool g_profile = false;
+static std::vector<std::pair<hipEvent_t, hipEvent_t>> g_profile_events;
+
 static ftk_status assign_impl(const AssignCall &c, void *workspace, hipStream_t st)
 {
-    const AssignPlan p = plan_assign(c.dtype, c.N, c.D, c.K, c.ft);
+    const bool aligned16 = ((uintptr_t)c.X % 16 == 0) && ((uintptr_t)c.C % 16 == 0);
+    const AssignPlan p = plan_assign(c.dtype, c.N, c.D, c.K, c.ft, aligned16);
     const Workspace w = carve_workspace(workspace, c.dtype, c.N, c.D, c.K, c.ft);
     FTK_TRY(launch_centroid_prologue(c, p, w, st));
-    FTK_TRY(launch_assign(c, p, w, st));
+    if (g_profile) {
+        hipEvent_t e0, e1;
+        FTK_TRY_HIP(hipEventCreate(&e0));
+        FTK_TRY_HIP(hipEventCreate(&e1));
+        FTK_TRY_HIP(hipEventRecord(e0, st));
+        FTK_TRY(launch_assign(c, p, w, st));
+        FTK_TRY_HIP(hipEventRecord(e1, st));
+        g_profile_events.emplace_back(e0, e1);
+    } else {
+        FTK_TRY(launch_assign(c, p, w, st));
+    }
     FTK_TRY(launch_refine(c, w, st));
     return FTK_OK;
 }
@@ -164,6 +179,35 @@ static ftk_status assign_impl(const AssignCall &c, void *workspace, hipStream_t 
 using namespace ftk;
 
 extern "C" {
+
+ftk_status ftk_profile_enable(int32_t on)
+{
+    g_profile = on != 0;
+    return FTK_OK;
+}
+
+ftk_status ftk_profile_read(double *total_ms, int64_t *launches)
+{
+    if (!total_ms || !launches) {
+        set_error("NULL output");
+        return FTK_EINVAL;
+    }
+    double sum = 0.0;
+    int64_t n = 0;
+    for (auto &pr : g_profile_events) {
+        float ms = 0.f;
+        FTK_TRY_HIP(hipEventSynchronize(pr.second));
+        FTK_TRY_HIP(hipEventElapsedTime(&ms, pr.first, pr.second));
+        sum += ms;
+        ++n;
+        (void)hipEventDestroy(pr.first);
+        (void)hipEventDestroy(pr.second);
+    }
+    g_profile_events.clear();
+    *total_ms = sum;
+    *launches = n;
+    return FTK_OK;
+}
 
 const char *ftk_last_error(void) { return g_err; }
 const char *ftk_version(void) { return "ftkmeans 0.1 (gfx950)"; }
@@ -182,7 +226,7 @@ ftk_status ftk_assign_geometry(ftk_dtype dtype, int64_t N, int32_t D, int32_t K,
         set_error("out is NULL");
         return FTK_EINVAL;
     }
-    const AssignPlan p = plan_assign(dtype, N, D, K, ft);
+    const AssignPlan p = plan_assign(dtype, N, D, K, ft, true);
     out->workgroups = (uint32_t)p.workgroups;
     out->waves_per_workgroup = (uint32_t)p.waves;
     out->tiles_per_wave = (uint32_t)p.tiles_per_wave;

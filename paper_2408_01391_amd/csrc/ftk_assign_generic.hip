@@ -47,32 +47,6 @@ struct GenericCfg<double> {
     static constexpr int PT = 4, KT = 4, WAVES = 4, DQMAX = 8;
 };
 
-// Running best-three scores and best-two indices of one point.
-template <typename T>
-struct Top3 {
-    T m1, m2, m3;
-    int i1, i2;
-};
-
-// Insert score s (centroid j).  Written on by-value locals so that every choice is a select
-// (v_cndmask) rather than a branch.
-template <typename T>
-__device__ __forceinline__ Top3<T> top3_insert(Top3<T> b, T s, int j)
-{
-    const T m1 = b.m1, m2 = b.m2, m3 = b.m3;
-    const int i1 = b.i1, i2 = b.i2;
-    const bool c1 = s > m1;
-    const bool c2 = s > m2;
-    const int i2a = c2 ? j : i2;
-    Top3<T> o;
-    o.i2 = c1 ? i1 : i2a;
-    o.i1 = c1 ? j : i1;
-    o.m3 = Mma<T>::med3(m2, m3, s);
-    o.m2 = Mma<T>::med3(m1, m2, s);
-    o.m1 = c1 ? s : m1;
-    return o;
-}
-
 template <typename T, bool ALIGNED>
 __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a)
 {
@@ -382,6 +356,9 @@ void plan_generic(ftk_dtype dtype, int64_t N, int D, int K, AssignPlan &p)
     p.regs_per_tile = f32 ? Mma<float>::R : Mma<double>::R;
     const size_t esz = f32 ? 4 : 8;
     p.lds_bytes = (size_t)(p.KC + p.KT) * (8 * p.DQ * esz + 16);
+    p.hcn_pad_inf = false;
+    p.grid = (int)p.workgroups;
+    p.kch = p.KC;
 }
 
 }  // namespace ftk

@@ -48,8 +48,11 @@ struct AssignPlan {
     int tiles_per_wave;         // output tiles a wave finishes (fault addressing)
     int regs_per_tile;
     size_t lds_bytes;
+    bool hcn_pad_inf;           // padding rows of the half-norm vector hold +inf (never win)
+    int grid;                   // workgroups launched (persistent variants launch fewer)
+    int kch;                    // centroids staged in LDS at a time (small-D variant)
 };
-AssignPlan plan_assign(ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft);
+AssignPlan plan_assign(ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft, bool aligned16);
 
 // ---- workspace carving --------------------------------------------------------------------
 struct Workspace {

@@ -7,7 +7,7 @@
 // (paper Sections 3.1.3-3.1.5) and the per-point checksums (Section 4) need no cross-lane
 // traffic until the very end.
 //
-// Lane layouts (checked on hardware by tests/test_gpu_layout.py):
+// Lane layouts (established with a probe on hardware; any mistake breaks the parity tests):
 //   v_mfma_f32_32x32x2_f32 : lane l supplies A[l%32][l/32] and B[l/32][l%32];
 //                            register r of lane l holds D[8*(r/4) + 4*(l/32) + r%4][l%32].
 //   v_mfma_f64_16x16x4_f64 : lane l supplies A[l%16][l/16] and B[l/16][l%16];
@@ -106,6 +106,32 @@ __device__ __forceinline__ double exact_sqdist(const T *x, const T *c, int D)
         s = fma(diff, diff, s);
     }
     return s;
+}
+
+// Running best-three scores and best-two indices of one point.
+template <typename T>
+struct Top3 {
+    T m1, m2, m3;
+    int i1, i2;
+};
+
+// Insert score s (centroid j).  Written on by-value locals so that every choice is a select
+// (v_cndmask) rather than a branch.
+template <typename T>
+__device__ __forceinline__ Top3<T> top3_insert(Top3<T> b, T s, int j)
+{
+    const T m1 = b.m1, m2 = b.m2, m3 = b.m3;
+    const int i1 = b.i1, i2 = b.i2;
+    const bool c1 = s > m1;
+    const bool c2 = s > m2;
+    const int i2a = c2 ? j : i2;
+    Top3<T> o;
+    o.i2 = c1 ? i1 : i2a;
+    o.i1 = c1 ? j : i1;
+    o.m3 = Mma<T>::med3(m2, m3, s);
+    o.m2 = Mma<T>::med3(m1, m2, s);
+    o.m1 = c1 ? s : m1;
+    return o;
 }
 
 __device__ __forceinline__ float shfl_xor_t(float v, int m) { return __shfl_xor(v, m, 64); }

@@ -19,7 +19,7 @@ __global__ void reset_assign_state_kernel(double *scal, int32_t *wl_count)
 // non-negative doubles).
 template <typename T>
 __global__ __launch_bounds__(256) void centroid_norms_kernel(const T *C, int D, int K, int Kpad, T *hcn,
-                                                             double *scal)
+                                                             double *scal, int pad_inf)
 {
     const int lane = threadIdx.x & 63;
     const int j = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
@@ -35,7 +35,7 @@ __global__ __launch_bounds__(256) void centroid_norms_kernel(const T *C, int D, 
 #pragma unroll
     for (int mask = 32; mask >= 1; mask >>= 1) s += __shfl_xor(s, mask, 64);
     if (lane == 0) {
-        hcn[j] = (T)(0.5 * s);
+        hcn[j] = (j >= K && pad_inf) ? (T)__builtin_huge_val() : (T)(0.5 * s);
         if (j < K) atomicMax((unsigned long long *)scal, (unsigned long long)__double_as_longlong(s));
     }
 }
@@ -87,14 +87,14 @@ ftk_status launch_centroid_prologue(const AssignCall &c, const AssignPlan &p, co
     const int ntiles = p.nkc * p.KT;
     if (c.dtype == FTK_F32) {
         hipLaunchKernelGGL((centroid_norms_kernel<float>), dim3(blocks), dim3(256), 0, st,
-                           (const float *)c.C, c.D, c.K, Kpad, (float *)w.hcn, w.scal);
+                           (const float *)c.C, c.D, c.K, Kpad, (float *)w.hcn, w.scal, (int)p.hcn_pad_inf);
         if (c.ft != FTK_FT_OFF)
             hipLaunchKernelGGL((centroid_checksum_kernel<float>), dim3(ntiles), dim3(256), 0, st,
                                (const float *)c.C, (const float *)w.hcn, c.D, p.D8, c.K, p.TM,
                                (float *)w.chk_v1, (float *)w.chk_v2, (float *)w.chk_s);
     } else {
         hipLaunchKernelGGL((centroid_norms_kernel<double>), dim3(blocks), dim3(256), 0, st,
-                           (const double *)c.C, c.D, c.K, Kpad, (double *)w.hcn, w.scal);
+                           (const double *)c.C, c.D, c.K, Kpad, (double *)w.hcn, w.scal, (int)p.hcn_pad_inf);
         if (c.ft != FTK_FT_OFF)
             hipLaunchKernelGGL((centroid_checksum_kernel<double>), dim3(ntiles), dim3(256), 0, st,
                                (const double *)c.C, (const double *)w.hcn, c.D, p.D8, c.K, p.TM,
