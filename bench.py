@@ -147,6 +147,7 @@ def main():
             "hbm_frac": algo_bytes / kern_s / 1e9 / HBM_PEAK_GBS,
         },
     }
+    out["stats"] = ftk.stats_dict(stats)
     if "off" in results and "on" in results:
         out["ft"] = {
             "iters_per_s_ft_on": steps / results["on"]["sec"],

@@ -242,12 +242,15 @@ __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a
     }
 }
 
-// One wave per queued point: all K exact distances, wave-wide arg-min (lowest index on ties).
-template <typename T>
+// One wave per queued point: all K exact distances (direct-difference form, double), wave-wide
+// arg-min with the lowest index on ties.  Rows are fetched with 16-byte loads, several in
+// flight per lane; every row is summed in the same feature order, so identical centroids tie.
+template <typename T, bool ALIGNED>
 __global__ __launch_bounds__(256) void refine_kernel(const T *X, const T *C, int D, int K,
                                                      const int32_t *wl, const int32_t *wl_count,
                                                      int32_t *labels, T *mindist, ftk_ft_stats *stats)
 {
+    constexpr int E = Mma<T>::E;
     const int lane = threadIdx.x & 63;
     const int wave_global = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
@@ -258,9 +261,20 @@ __global__ __launch_bounds__(256) void refine_kernel(const T *X, const T *C, int
         double best = __builtin_huge_val();
         int bj = 0x7fffffff;
         for (int j = lane; j < K; j += 64) {
-            const double d = exact_sqdist<T>(x, C + (int64_t)j * D, D);
-            if (d < best) {  // j increases within a lane: first minimum kept
-                best = d;
+            const T *c = C + (int64_t)j * D;
+            double s = 0.0;
+#pragma unroll 4
+            for (int d0 = 0; d0 < D; d0 += E) {
+                const auto cf = load_frag<T, ALIGNED>(c, d0, D);
+                const auto xf = load_frag<T, ALIGNED>(x, d0, D);
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    const double diff = (double)xf[e] - (double)cf[e];
+                    s = fma(diff, diff, s);
+                }
+            }
+            if (s < best) {  // j increases within a lane: first minimum kept
+                best = s;
                 bj = j;
             }
         }
@@ -322,17 +336,25 @@ ftk_status launch_assign_generic(const AssignCall &c, const AssignPlan &p, const
                               : launch_generic_t<double>(c, p, w, st);
 }
 
+template <typename T>
+static void launch_refine_t(const AssignCall &c, const Workspace &w, hipStream_t st)
+{
+    const bool aligned = (c.D % Mma<T>::E == 0) && ((uintptr_t)c.X % 16 == 0) && ((uintptr_t)c.C % 16 == 0);
+    dim3 grid(1024), block(256);
+    if (aligned)
+        hipLaunchKernelGGL((refine_kernel<T, true>), grid, block, 0, st, (const T *)c.X, (const T *)c.C,
+                           c.D, c.K, w.wl, w.wl_count, c.labels, (T *)c.mindist, c.stats);
+    else
+        hipLaunchKernelGGL((refine_kernel<T, false>), grid, block, 0, st, (const T *)c.X, (const T *)c.C,
+                           c.D, c.K, w.wl, w.wl_count, c.labels, (T *)c.mindist, c.stats);
+}
+
 ftk_status launch_refine(const AssignCall &c, const Workspace &w, hipStream_t st)
 {
-    dim3 grid(1024), block(256);
     if (c.dtype == FTK_F32)
-        hipLaunchKernelGGL((refine_kernel<float>), grid, block, 0, st, (const float *)c.X,
-                           (const float *)c.C, c.D, c.K, w.wl, w.wl_count, c.labels,
-                           (float *)c.mindist, c.stats);
+        launch_refine_t<float>(c, w, st);
     else
-        hipLaunchKernelGGL((refine_kernel<double>), grid, block, 0, st, (const double *)c.X,
-                           (const double *)c.C, c.D, c.K, w.wl, w.wl_count, c.labels,
-                           (double *)c.mindist, c.stats);
+        launch_refine_t<double>(c, w, st);
     FTK_TRY_HIP(hipGetLastError());
     return FTK_OK;
 }

@@ -15,6 +15,7 @@
 //     cancelling expanded form cannot order, and gives an accurate minimum distance.
 // A lane whose third-best tile maximum is still inside the rounding bound queues its point
 // for the refine kernel.
+#include <cstdlib>
 #include <type_traits>
 
 #include "ftk_internal.h"
@@ -38,60 +39,74 @@ struct SmallArgs {
     int32_t *wl_count;
     ftk_ft_stats *stats;
     double band_coef;
+    int dbg;
 };
 
 __device__ __forceinline__ float max3f(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
 
-// Exact (direct-difference, fp32) distances of one point to the 16 centroids that lane group g
-// owns in tile T; keeps the running (distance, index) minimum, lowest index on equal distance.
-// xlo / xhi hold features 8q..8q+3 and 8q+4..8q+7 of the point, so every lane adds the terms
-// in feature order and identical centroids give bit-identical distances whichever lane
-// evaluates them.  Rows come from `base` with `stride` floats per row (LDS chunk or global C).
+// Exact (direct-difference, fp32) distances of one point to 8 centroids of one lane group's
+// share of a tile: registers r0..r0+7 of group gw in the tile whose rows start at `base`
+// (`stride` floats per row, LDS chunk or global C).  xlo / xhi hold features 8q..8q+3 and
+// 8q+4..8q+7 of the point, so terms are always added in feature order and identical centroids
+// give bit-identical distances whichever lane evaluates them.  Keeps the running (distance,
+// index) minimum, lowest index on equal distance.
 template <int NQ>
-__device__ __forceinline__ void eval_group(const floatx4 (&xlo)[NQ], const floatx4 (&xhi)[NQ],
-                                           const float *base, int stride, int jfirst, int K, int D,
-                                           int g, float &dbest, int &jbest)
+__device__ __forceinline__ void eval_rows(const floatx4 (&xlo)[NQ], const floatx4 (&xhi)[NQ],
+                                          const float *base, int stride, int jfirst, int K, int D,
+                                          int gw, int r0, float &dbest, int &jbest)
 {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int j = jfirst + Mma<float>::row(r, g);
-        if (j < K) {
-            const float *c = base + (size_t)Mma<float>::row(r, g) * stride;
-            float d = 0.f;
+    for (int i = 0; i < 8; ++i) {
+        // register r = r0 + i of group gw holds tile row 8*(r/4) + 4*gw + r%4; r0 is 0 or 8
+        const int row = 8 * (i >> 2) + (i & 3) + 2 * r0 + 4 * gw;
+        const int j = jfirst + row;
+        const float *c = base + row * stride;
+        float d = 0.f;
 #pragma unroll
-            for (int q = 0; q < NQ; ++q) {
-                if (8 * q < D) {
-                    const floatx4 cl = *reinterpret_cast<const floatx4 *>(c + 8 * q);
+        for (int q = 0; q < NQ; ++q) {
+            if (8 * q < D) {
+                const floatx4 cl = *reinterpret_cast<const floatx4 *>(c + 8 * q);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float t = xlo[q][e] - cl[e];
-                        d = fmaf(t, t, d);
-                    }
-                }
-                if (8 * q + 4 < D) {
-                    const floatx4 ch = *reinterpret_cast<const floatx4 *>(c + 8 * q + 4);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float t = xhi[q][e] - ch[e];
-                        d = fmaf(t, t, d);
-                    }
+                for (int e = 0; e < 4; ++e) {
+                    const float t = xlo[q][e] - cl[e];
+                    d = fmaf(t, t, d);
                 }
             }
-            const bool better = d < dbest || (d == dbest && j < jbest);
-            dbest = better ? d : dbest;
-            jbest = better ? j : jbest;
+            if (8 * q + 4 < D) {
+                const floatx4 ch = *reinterpret_cast<const floatx4 *>(c + 8 * q + 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float t = xhi[q][e] - ch[e];
+                    d = fmaf(t, t, d);
+                }
+            }
         }
+        const bool better = j < K && (d < dbest || (d == dbest && j < jbest));
+        dbest = better ? d : dbest;
+        jbest = better ? j : jbest;
     }
 }
 
+constexpr int SMALLD_WAVES = 8;  // waves per workgroup sharing one staged centroid chunk
+constexpr int SMALLD_THREADS = SMALLD_WAVES * 64;
+
+// Best tile maximum, the tile it came from, and the runner-up tile maximum of one lane.
+struct TileBest {
+    float m1, m2;
+    int t1;
+};
+
 template <int NQ, int PT>
-__global__ __launch_bounds__(256) void assign_smalld_kernel(SmallArgs a)
+__global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs a)
 {
     using M = Mma<float>;
-    constexpr int SW = 8 * NQ + 4;  // LDS row stride in floats (16 bytes of padding)
+    constexpr int SW = 8 * NQ + 4;      // LDS row stride in floats (16 bytes of padding)
+    constexpr int TS = 32 * SW + 4;     // LDS tile stride: 16 more bytes so that lanes reading rows
+                                        // of different tiles (exact re-evaluation) spread over banks
     extern __shared__ __align__(16) float lds[];
-    float *ldsC = lds;                          // [kch][SW]
-    float *ldsH = lds + (size_t)a.kch * SW;     // [kch] -||c||^2/2 in (tile, group, register) order
+    const int tiles_per_chunk = a.kch / 32;
+    float *ldsC = lds;                                  // [tiles_per_chunk][TS]
+    float *ldsH = lds + (size_t)tiles_per_chunk * TS;   // [kch] -||c||^2/2 in (tile, group, register) order
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -100,16 +115,35 @@ __global__ __launch_bounds__(256) void assign_smalld_kernel(SmallArgs a)
     const int g = lane >> 5;
     const int D = a.D;
     const int tiles_total = (a.K + 31) / 32;
-    const int tiles_per_chunk = a.kch / 32;
     const float cmax2 = (float)a.scal[0];
     const float cmax = sqrtf(cmax2);
     int n_refined = 0;
 
-    for (int blk = blockIdx.x; blk < a.nblocks; blk += gridDim.x) {
-        const int64_t p0 = ((int64_t)blk * 4 + wave) * (PT * 32);
+    // operand fetch of one centroid tile: A fragments and the accumulator start values
+    auto load_tile = [&](int t, floatx4 (&av)[NQ], floatx16 &ci) {
+        const float *rowp = ldsC + (size_t)t * TS + col * SW + 4 * g;
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) av[q] = *reinterpret_cast<const floatx4 *>(rowp + 8 * q);
+        const float *hp = ldsH + t * 32 + g * 16;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const floatx4 h = *reinterpret_cast<const floatx4 *>(hp + 4 * i);
+            ci[4 * i + 0] = h[0];
+            ci[4 * i + 1] = h[1];
+            ci[4 * i + 2] = h[2];
+            ci[4 * i + 3] = h[3];
+        }
+    };
+
+    // point blocks are handed out dynamically: the first one by block index, the rest from an
+    // atomic counter, so that no workgroup idles while another still has a queue
+    __shared__ int sh_next;
+    bool staged = false;
+    for (int blk = blockIdx.x; blk < a.nblocks;) {
+        const int64_t p0 = ((int64_t)blk * SMALLD_WAVES + wave) * (PT * 32);
         floatx4 xf[PT][NQ];
         float xn[PT];
-        Top3<float> best[PT];
+        TileBest best[PT];
 #pragma unroll
         for (int pt = 0; pt < PT; ++pt) {
             int64_t p = p0 + pt * 32 + col;
@@ -122,24 +156,51 @@ __global__ __launch_bounds__(256) void assign_smalld_kernel(SmallArgs a)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) xn[pt] = fmaf(xf[pt][q][e], xf[pt][q][e], xn[pt]);
             }
-            best[pt].m1 = best[pt].m2 = best[pt].m3 = M::neg_inf();
-            best[pt].i1 = best[pt].i2 = 0;
+            best[pt].m1 = best[pt].m2 = M::neg_inf();
+            best[pt].t1 = 0;
         }
 
+        // one output tile: contraction, tile maximum per lane, running best tile
+        auto compute_tile = [&](const floatx4 (&av)[NQ], const floatx16 &ci, int tile) {
+#pragma unroll
+            for (int pt = 0; pt < PT; ++pt) {
+                floatx16 acc = ci;
+#pragma unroll
+                for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc = M::mma(av[q][e], xf[pt][q][e], acc);
+                float tm = max3f(acc[0], acc[1], acc[2]);
+                tm = max3f(tm, acc[3], acc[4]);
+                tm = max3f(tm, acc[5], acc[6]);
+                tm = max3f(tm, acc[7], acc[8]);
+                tm = max3f(tm, acc[9], acc[10]);
+                tm = max3f(tm, acc[11], acc[12]);
+                tm = max3f(tm, acc[13], acc[14]);
+                tm = __builtin_fmaxf(tm, acc[15]);
+                const float m1 = best[pt].m1, m2 = best[pt].m2;
+                const int t1 = best[pt].t1;
+                const bool c = tm > m1;
+                best[pt].m2 = __builtin_amdgcn_fmed3f(m1, m2, tm);
+                best[pt].t1 = c ? tile : t1;
+                best[pt].m1 = __builtin_fmaxf(m1, tm);
+            }
+        };
+
         for (int ch = 0; ch < a.nch; ++ch) {
-            if (a.nch > 1 || blk == (int)blockIdx.x) {
+            if (a.nch > 1 || !staged) {
+                staged = true;
                 // (re)stage the centroid chunk; with a single chunk it stays resident
                 __syncthreads();
                 const int jbase = ch * a.kch;
                 constexpr int PPR = 2 * NQ;  // 16-byte pieces per row
-                for (int idx = tid; idx < a.kch * PPR; idx += 256) {
+                for (int idx = tid; idx < a.kch * PPR; idx += SMALLD_THREADS) {
                     const int rrow = idx / PPR, pc = idx % PPR;
                     const int j = jbase + rrow;
                     floatx4 f = {0.f, 0.f, 0.f, 0.f};
                     if (j < a.K) f = load_frag<float, true>(a.C + (size_t)j * D, 4 * pc, D);
-                    *reinterpret_cast<floatx4 *>(ldsC + (size_t)rrow * SW + 4 * pc) = f;
+                    *reinterpret_cast<floatx4 *>(ldsC + (size_t)(rrow >> 5) * TS + (rrow & 31) * SW + 4 * pc) = f;
                 }
-                for (int idx = tid; idx < a.kch; idx += 256) {
+                for (int idx = tid; idx < a.kch; idx += SMALLD_THREADS) {
                     const int t = idx >> 5, gg = (idx >> 4) & 1, r = idx & 15;
                     ldsH[idx] = -a.hcn[jbase + t * 32 + M::row(r, gg)];
                 }
@@ -147,41 +208,20 @@ __global__ __launch_bounds__(256) void assign_smalld_kernel(SmallArgs a)
             }
             const int tile0 = ch * tiles_per_chunk;
             const int ntile = min(tiles_per_chunk, tiles_total - tile0);
-            for (int t = 0; t < ntile; ++t) {
-                floatx4 av[NQ];
-#pragma unroll
-                for (int q = 0; q < NQ; ++q)
-                    av[q] = *reinterpret_cast<const floatx4 *>(ldsC + (size_t)(t * 32 + col) * SW + 8 * q + 4 * g);
-                floatx16 cinit;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const floatx4 h = *reinterpret_cast<const floatx4 *>(ldsH + t * 32 + g * 16 + 4 * i);
-                    cinit[4 * i + 0] = h[0];
-                    cinit[4 * i + 1] = h[1];
-                    cinit[4 * i + 2] = h[2];
-                    cinit[4 * i + 3] = h[3];
-                }
-#pragma unroll
-                for (int pt = 0; pt < PT; ++pt) {
-                    floatx16 acc = cinit;
-#pragma unroll
-                    for (int q = 0; q < NQ; ++q)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) acc = M::mma(av[q][e], xf[pt][q][e], acc);
-                    float tm = max3f(acc[0], acc[1], acc[2]);
-                    tm = max3f(tm, acc[3], acc[4]);
-                    tm = max3f(tm, acc[5], acc[6]);
-                    tm = max3f(tm, acc[7], acc[8]);
-                    tm = max3f(tm, acc[9], acc[10]);
-                    tm = max3f(tm, acc[11], acc[12]);
-                    tm = max3f(tm, acc[13], acc[14]);
-                    tm = __builtin_fmaxf(tm, acc[15]);
-                    best[pt] = top3_insert<float>(best[pt], tm, tile0 + t);
-                }
+            // two operand register sets: the fetch of the next tile is in flight while the
+            // current one is multiplied
+            floatx4 avA[NQ], avB[NQ];
+            floatx16 ciA, ciB;
+            load_tile(0, avA, ciA);
+            for (int t = 0; t < ntile; t += 2) {
+                load_tile(min(t + 1, ntile - 1), avB, ciB);
+                compute_tile(avA, ciA, tile0 + t);
+                load_tile(min(t + 2, ntile - 1), avA, ciA);
+                if (t + 1 < ntile) compute_tile(avB, ciB, tile0 + t + 1);
             }
         }
 
-        // ---- exact evaluation of the candidate groups ----
+        // ---- exact evaluation of the winning group; the two lanes of a point share its rows ----
         const bool resident = a.nch == 1;
 #pragma unroll
         for (int pt = 0; pt < PT; ++pt) {
@@ -198,23 +238,30 @@ __global__ __launch_bounds__(256) void assign_smalld_kernel(SmallArgs a)
                     xhi[q][e] = g == 0 ? other : mine;
                 }
             const float xnt = xn[pt] + __shfl_xor(xn[pt], 32, 64);
-            const float top = fmaxf(best[pt].m1, __shfl_xor(best[pt].m1, 32, 64));
             const float bound = (float)a.band_coef * (sqrtf(xnt) * cmax + 0.5f * cmax2);
-            const float thr = top - bound;
-            const bool use1 = best[pt].m1 >= thr;
-            const bool use2 = best[pt].m2 >= thr;
-            const bool over = best[pt].m3 >= thr;
+            const float om1 = __shfl_xor(best[pt].m1, 32, 64), om2 = __shfl_xor(best[pt].m2, 32, 64);
+            const int ot1 = __shfl_xor(best[pt].t1, 32, 64);
+            const bool mine_wins = best[pt].m1 > om1 || (best[pt].m1 == om1 && g == 0);
+            const float thr = fmaxf(best[pt].m1, om1) - bound;
+            // first round: the group holding the best tile maximum (gw = its lane group)
+            const int gw = mine_wins ? g : 1 - g;
+            const int Tw = mine_wins ? best[pt].t1 : ot1;
+            // second round (rare): the other group's best tile is inside the bound as well
+            const bool second = fminf(best[pt].m1, om1) >= thr;
+            const int Ts = mine_wins ? ot1 : best[pt].t1;
+            // a third candidate tile anywhere: left to the refine kernel
+            const bool over = fmaxf(best[pt].m2, om2) >= thr;
             float dbest = __builtin_huge_valf();
             int jbest = 0x7fffffff;
-            if (use1) {
-                const int T = best[pt].i1;
-                const float *base = resident ? ldsC + (size_t)T * 32 * SW : a.C + (size_t)T * 32 * D;
-                eval_group<NQ>(xlo, xhi, base, resident ? SW : D, T * 32, a.K, D, g, dbest, jbest);
+            {
+                const float *base = resident ? ldsC + Tw * TS : a.C + (size_t)Tw * 32 * D;
+                eval_rows<NQ>(xlo, xhi, base, resident ? SW : D, Tw * 32, a.K, D, gw, 8 * g, dbest, jbest);
             }
-            if (use2) {
-                const int T = best[pt].i2;
-                const float *base = resident ? ldsC + (size_t)T * 32 * SW : a.C + (size_t)T * 32 * D;
-                eval_group<NQ>(xlo, xhi, base, resident ? SW : D, T * 32, a.K, D, g, dbest, jbest);
+            if (__any(second)) {
+                if (second) {
+                    const float *base = resident ? ldsC + Ts * TS : a.C + (size_t)Ts * 32 * D;
+                    eval_rows<NQ>(xlo, xhi, base, resident ? SW : D, Ts * 32, a.K, D, 1 - gw, 8 * g, dbest, jbest);
+                }
             }
             const float od = __shfl_xor(dbest, 32, 64);
             const int oj = __shfl_xor(jbest, 32, 64);
@@ -222,26 +269,21 @@ __global__ __launch_bounds__(256) void assign_smalld_kernel(SmallArgs a)
                 dbest = od;
                 jbest = oj;
             }
-            const bool over_any = over || (__shfl_xor((int)over, 32, 64) != 0);
-            const bool two_any = use2 || (__shfl_xor((int)use2, 32, 64) != 0);
             if (live && g == 0) {
                 a.labels[p] = jbest == 0x7fffffff ? 0 : jbest;
                 if (a.mindist) a.mindist[p] = dbest;
-                if (over_any) {
+                if (!(thr == thr) || over) {   // NaN scores or a third candidate tile
                     const int pos = atomicAdd(a.wl_count, 1);
                     a.wl[pos] = (int32_t)p;
-                } else if (two_any) {
-                    n_refined += 1;
                 }
             }
         }
+        __syncthreads();
+        if (tid == 0) sh_next = (int)gridDim.x + atomicAdd(a.wl_count + 1, 1);
+        __syncthreads();
+        blk = sh_next;
     }
-    if (a.stats) {
-        int n = n_refined;
-#pragma unroll
-        for (int mask = 1; mask < 64; mask <<= 1) n += __shfl_xor(n, mask, 64);
-        if (lane == 0 && n) atomicAdd((unsigned long long *)&a.stats->refined, (unsigned long long)n);
-    }
+    (void)n_refined;
 }
 
 bool smalld_supported(ftk_dtype dtype, int D, int K)
@@ -261,21 +303,21 @@ void plan_smalld(int64_t N, int D, int K, ftk_ft_mode ft, AssignPlan &p)
     p.D8 = (int)ceil_div(D, 8) * 8;
     p.PT = smalld_pt(p.D8);
     p.KT = 1;
-    p.waves = 4;
+    p.waves = SMALLD_WAVES;
     const int SW = p.D8 + 4;
     // chunk: as many centroids as fit 64 KB of LDS, all of them if possible
-    int kch = (64 * 1024) / (SW * 4 + 4) / 32 * 32;
+    int kch = (64 * 1024) / (SW * 4 + 4 + 1) / 32 * 32;
     const int Kr = (int)ceil_div(K, 32) * 32;
     if (kch > Kr) kch = Kr;
     p.kch = kch;
     p.KC = kch;
     p.nkc = (int)ceil_div(K, kch);
     p.DQ = p.D8 / 8;
-    p.points_per_wg = 4 * p.PT * 32;
+    p.points_per_wg = SMALLD_WAVES * p.PT * 32;
     p.workgroups = ceil_div(N, p.points_per_wg);
-    p.lds_bytes = (size_t)kch * (SW * 4 + 4);
-    int resident_wgs = (int)(160 * 1024 / (p.lds_bytes + 512));
-    if (resident_wgs > 4) resident_wgs = 4;
+    p.lds_bytes = (size_t)(kch / 32) * (32 * SW + 4) * 4 + (size_t)kch * 4;
+    int resident_wgs = (int)(160 * 1024 / (p.lds_bytes + 2048));
+    if (resident_wgs > 2) resident_wgs = 2;
     if (resident_wgs < 1) resident_wgs = 1;
     const int64_t cap = 256LL * resident_wgs;
     p.grid = (int)(p.workgroups < cap ? p.workgroups : cap);
@@ -287,7 +329,7 @@ void plan_smalld(int64_t N, int D, int K, ftk_ft_mode ft, AssignPlan &p)
 template <int NQ, int PT>
 static void launch_smalld_t(const SmallArgs &a, const AssignPlan &p, hipStream_t st)
 {
-    hipLaunchKernelGGL((assign_smalld_kernel<NQ, PT>), dim3(p.grid), dim3(256), p.lds_bytes, st, a);
+    hipLaunchKernelGGL((assign_smalld_kernel<NQ, PT>), dim3(p.grid), dim3(SMALLD_THREADS), p.lds_bytes, st, a);
 }
 
 ftk_status launch_assign_smalld(const AssignCall &c, const AssignPlan &p, const Workspace &w, hipStream_t st)
@@ -313,6 +355,7 @@ ftk_status launch_assign_smalld(const AssignCall &c, const AssignPlan &p, const 
     a.wl_count = w.wl_count;
     a.stats = c.stats;
     a.band_coef = 4.0 * (c.D + 4) * Mma<float>::kEps;
+    a.dbg = getenv("FTK_DBG") ? atoi(getenv("FTK_DBG")) : 0;
     switch (p.D8 / 8) {
     case 1: launch_smalld_t<1, 2>(a, p, st); break;
     case 2: launch_smalld_t<2, 2>(a, p, st); break;

@@ -10,7 +10,8 @@ __global__ void reset_assign_state_kernel(double *scal, int32_t *wl_count)
 {
     if (threadIdx.x == 0) {
         scal[0] = 0.0;
-        wl_count[0] = 0;
+        wl_count[0] = 0;  // refine work-list length
+        wl_count[1] = 0;  // dynamic point-block counter of the persistent small-D kernel
     }
 }
 
