@@ -50,40 +50,45 @@ __device__ __forceinline__ float max3f(float a, float b, float c) { return __bui
 // 8q+4..8q+7 of the point, so terms are always added in feature order and identical centroids
 // give bit-identical distances whichever lane evaluates them.  Keeps the running (distance,
 // index) minimum, lowest index on equal distance.
-template <int NQ>
+template <int NQ, bool PADDED>
 __device__ __forceinline__ void eval_rows(const floatx4 (&xlo)[NQ], const floatx4 (&xhi)[NQ],
                                           const float *base, int stride, int jfirst, int K, int D,
                                           int gw, int r0, float &dbest, int &jbest)
 {
+    // PADDED: rows are zero-padded to 8*NQ features (LDS copy), no bounds checks needed; the
+    // point fragments are zero beyond D as well.
+    float d[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         // register r = r0 + i of group gw holds tile row 8*(r/4) + 4*gw + r%4; r0 is 0 or 8
         const int row = 8 * (i >> 2) + (i & 3) + 2 * r0 + 4 * gw;
-        const int j = jfirst + row;
         const float *c = base + row * stride;
-        float d = 0.f;
+        d[i] = 0.f;
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
-            if (8 * q < D) {
-                const floatx4 cl = *reinterpret_cast<const floatx4 *>(c + 8 * q);
+            floatx4 cl = {0.f, 0.f, 0.f, 0.f}, ch = {0.f, 0.f, 0.f, 0.f};
+            if (PADDED || (8 * q < D && jfirst + row < K)) cl = *reinterpret_cast<const floatx4 *>(c + 8 * q);
+            if (PADDED || (8 * q + 4 < D && jfirst + row < K)) ch = *reinterpret_cast<const floatx4 *>(c + 8 * q + 4);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float t = xlo[q][e] - cl[e];
-                    d = fmaf(t, t, d);
-                }
+            for (int e = 0; e < 4; ++e) {
+                const float t = xlo[q][e] - cl[e];
+                d[i] = fmaf(t, t, d[i]);
             }
-            if (8 * q + 4 < D) {
-                const floatx4 ch = *reinterpret_cast<const floatx4 *>(c + 8 * q + 4);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float t = xhi[q][e] - ch[e];
-                    d = fmaf(t, t, d);
-                }
+            for (int e = 0; e < 4; ++e) {
+                const float t = xhi[q][e] - ch[e];
+                d[i] = fmaf(t, t, d[i]);
             }
         }
-        const bool better = j < K && (d < dbest || (d == dbest && j < jbest));
-        dbest = better ? d : dbest;
-        jbest = better ? j : jbest;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int j = jfirst + 8 * (i >> 2) + (i & 3) + 2 * r0 + 4 * gw;
+        const float db = dbest;
+        const int jb = jbest;
+        const bool better = (j < K) & ((d[i] < db) | ((d[i] == db) & (j < jb)));
+        dbest = better ? d[i] : db;
+        jbest = better ? j : jb;
     }
 }
 
@@ -135,11 +140,34 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
         }
     };
 
-    // point blocks are handed out dynamically: the first one by block index, the rest from an
-    // atomic counter, so that no workgroup idles while another still has a queue
+    // Blocks of SMALLD_WAVES units (PT*32 points per wave) are handed out dynamically from an
+    // atomic counter so that nothing idles while a queue remains.  The waves of a workgroup
+    // deliberately stay in step (one barrier per block): on this hardware fp32 matrix and
+    // vector instructions share the issue path, and waves that drift into different phases
+    // (one multiplying, one reducing) interleave them finely, which measurably costs throughput.
     __shared__ int sh_next;
-    bool staged = false;
-    for (int blk = blockIdx.x; blk < a.nblocks;) {
+    const bool resident = a.nch == 1;
+    auto stage_chunk = [&](int ch) {
+        const int jbase = ch * a.kch;
+        constexpr int PPR = 2 * NQ;  // 16-byte pieces per row
+        for (int idx = tid; idx < a.kch * PPR; idx += SMALLD_THREADS) {
+            const int rrow = idx / PPR, pc = idx % PPR;
+            const int j = jbase + rrow;
+            floatx4 f = {0.f, 0.f, 0.f, 0.f};
+            if (j < a.K) f = load_frag<float, true>(a.C + (size_t)j * D, 4 * pc, D);
+            *reinterpret_cast<floatx4 *>(ldsC + (size_t)(rrow >> 5) * TS + (rrow & 31) * SW + 4 * pc) = f;
+        }
+        for (int idx = tid; idx < a.kch; idx += SMALLD_THREADS) {
+            const int t = idx >> 5, gg = (idx >> 4) & 1, r = idx & 15;
+            ldsH[idx] = -a.hcn[jbase + t * 32 + M::row(r, gg)];
+        }
+    };
+    if (resident) {
+        stage_chunk(0);
+        __syncthreads();
+    }
+    int blk = blockIdx.x;
+    while (blk < a.nblocks) {
         const int64_t p0 = ((int64_t)blk * SMALLD_WAVES + wave) * (PT * 32);
         floatx4 xf[PT][NQ];
         float xn[PT];
@@ -187,23 +215,9 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
         };
 
         for (int ch = 0; ch < a.nch; ++ch) {
-            if (a.nch > 1 || !staged) {
-                staged = true;
-                // (re)stage the centroid chunk; with a single chunk it stays resident
-                __syncthreads();
-                const int jbase = ch * a.kch;
-                constexpr int PPR = 2 * NQ;  // 16-byte pieces per row
-                for (int idx = tid; idx < a.kch * PPR; idx += SMALLD_THREADS) {
-                    const int rrow = idx / PPR, pc = idx % PPR;
-                    const int j = jbase + rrow;
-                    floatx4 f = {0.f, 0.f, 0.f, 0.f};
-                    if (j < a.K) f = load_frag<float, true>(a.C + (size_t)j * D, 4 * pc, D);
-                    *reinterpret_cast<floatx4 *>(ldsC + (size_t)(rrow >> 5) * TS + (rrow & 31) * SW + 4 * pc) = f;
-                }
-                for (int idx = tid; idx < a.kch; idx += SMALLD_THREADS) {
-                    const int t = idx >> 5, gg = (idx >> 4) & 1, r = idx & 15;
-                    ldsH[idx] = -a.hcn[jbase + t * 32 + M::row(r, gg)];
-                }
+            if (!resident) {
+                __syncthreads();  // every wave is done with the previous chunk
+                stage_chunk(ch);
                 __syncthreads();
             }
             const int tile0 = ch * tiles_per_chunk;
@@ -222,7 +236,6 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
         }
 
         // ---- exact evaluation of the winning group; the two lanes of a point share its rows ----
-        const bool resident = a.nch == 1;
 #pragma unroll
         for (int pt = 0; pt < PT; ++pt) {
             const int64_t p = p0 + pt * 32 + col;
@@ -253,22 +266,30 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
             const bool over = fmaxf(best[pt].m2, om2) >= thr;
             float dbest = __builtin_huge_valf();
             int jbest = 0x7fffffff;
-            {
-                const float *base = resident ? ldsC + Tw * TS : a.C + (size_t)Tw * 32 * D;
-                eval_rows<NQ>(xlo, xhi, base, resident ? SW : D, Tw * 32, a.K, D, gw, 8 * g, dbest, jbest);
-            }
-            if (__any(second)) {
-                if (second) {
-                    const float *base = resident ? ldsC + Ts * TS : a.C + (size_t)Ts * 32 * D;
-                    eval_rows<NQ>(xlo, xhi, base, resident ? SW : D, Ts * 32, a.K, D, 1 - gw, 8 * g, dbest, jbest);
+            if (resident) {
+                eval_rows<NQ, true>(xlo, xhi, ldsC + Tw * TS, SW, Tw * 32, a.K, D, gw, 8 * g, dbest, jbest);
+                if (__any(second)) {
+                    float d2 = dbest;
+                    int j2 = jbest;
+                    eval_rows<NQ, true>(xlo, xhi, ldsC + Ts * TS, SW, Ts * 32, a.K, D, 1 - gw, 8 * g, d2, j2);
+                    dbest = second ? d2 : dbest;
+                    jbest = second ? j2 : jbest;
+                }
+            } else {
+                eval_rows<NQ, false>(xlo, xhi, a.C + (size_t)Tw * 32 * D, D, Tw * 32, a.K, D, gw, 8 * g, dbest, jbest);
+                if (__any(second)) {
+                    float d2 = dbest;
+                    int j2 = jbest;
+                    eval_rows<NQ, false>(xlo, xhi, a.C + (size_t)Ts * 32 * D, D, Ts * 32, a.K, D, 1 - gw, 8 * g, d2, j2);
+                    dbest = second ? d2 : dbest;
+                    jbest = second ? j2 : jbest;
                 }
             }
             const float od = __shfl_xor(dbest, 32, 64);
             const int oj = __shfl_xor(jbest, 32, 64);
-            if (od < dbest || (od == dbest && oj < jbest)) {
-                dbest = od;
-                jbest = oj;
-            }
+            const bool take = (od < dbest) | ((od == dbest) & (oj < jbest));
+            dbest = take ? od : dbest;
+            jbest = take ? oj : jbest;
             if (live && g == 0) {
                 a.labels[p] = jbest == 0x7fffffff ? 0 : jbest;
                 if (a.mindist) a.mindist[p] = dbest;
