@@ -71,8 +71,11 @@ typedef struct {
     uint64_t corrected;      /* repaired from the decoded location                        */
     uint64_t recomputed;     /* location not decodable -> tile recomputed                 */
     uint64_t uncorrectable;  /* still mismatching after recomputation                     */
-    uint64_t refined;        /* points whose two best scores were closer than the
-                                rounding-error bound and were re-evaluated exactly        */
+    uint64_t refined;        /* points whose best scores were closer than the rounding-
+                                error bound and were re-evaluated exactly by the refine
+                                kernel                                                    */
+    uint64_t max_residual_ppm; /* largest fault-free checksum residual seen, in millionths
+                                of the detection threshold (maximised, not added)        */
 } ftk_ft_stats;
 
 /* Launch geometry of the assignment kernel for a problem, for building fault lists. */

@@ -18,7 +18,7 @@ _LIB_PATH = Path(__file__).resolve().parent / "libftkmeans.so"
 _lib = None
 
 STAT_FIELDS = ("tiles_checked", "injected", "detected", "corrected", "recomputed",
-               "uncorrectable", "refined")
+               "uncorrectable", "refined", "max_residual_ppm")
 
 
 class Geometry(ctypes.Structure):

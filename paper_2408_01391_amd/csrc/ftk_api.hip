@@ -59,7 +59,7 @@ Workspace carve_workspace(void *base, ftk_dtype dtype, int64_t N, int D, int K, 
     const size_t esz = dtype == FTK_F32 ? 4 : 8;
     const size_t D8 = (size_t)ceil_div(D, 8) * 8;
     const size_t Kpad = (size_t)ceil_div(K, 512) * 512 + 512;   // multiple of every chunk size
-    const size_t ntiles = Kpad / 16;                            // smallest tile: 16 centroids
+    const size_t ntiles = Kpad / 8;                             // generous: checksum rows per lane group
     char *p = (char *)base;
     size_t off = 0;
     auto take = [&](size_t bytes) {

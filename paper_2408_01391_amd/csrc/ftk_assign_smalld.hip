@@ -1,20 +1,32 @@
-// Small-D assignment kernel (fp32, D <= 32, rows 16-byte aligned).
+// Small-D assignment kernel (fp32, D <= 32, rows 16-byte aligned), with optional checksums.
 //
 // With few features the contraction per output tile is only D/2 matrix instructions, so the
-// per-element epilogue work, not the matrix pipe, decides the speed (the paper notes the same
-// for small feature counts in Section 5.1: data movement and the row-wise reduction become the
-// critical part).  This variant therefore
+// per-element epilogue work decides the speed (the paper notes the same for small feature
+// counts in Section 5.1: data movement and the row-wise reduction become the critical part;
+// on this hardware fp32 matrix and vector instructions do not overlap, so every epilogue
+// instruction adds to the matrix time).  This variant therefore
 //   * keeps the point fragments (B operand) in registers for the whole sweep over K: X is read
 //     once, straight from HBM with 16-byte coalesced loads, and never goes through LDS;
 //   * stages centroids (A operand) in LDS together with their -||c||^2/2 terms laid out in
 //     accumulator order, so each tile starts from four broadcast 16-byte LDS reads;
 //   * reduces every 32x32 output tile to ONE maximum per lane with v_max3 (half an op per
-//     score) and keeps only the best three tile maxima and the two best tile numbers;
-//   * after the sweep re-evaluates the (at most two) candidate groups of 16 centroids per lane
-//     in direct-difference form, which yields the exact arg-min, resolves every near-tie the
-//     cancelling expanded form cannot order, and gives an accurate minimum distance.
-// A lane whose third-best tile maximum is still inside the rounding bound queues its point
-// for the refine kernel.
+//     score) and keeps only the best tile, its maximum and the runner-up tile maximum;
+//   * after the sweep re-evaluates the winning group of 16 centroids in direct-difference form
+//     (the two lanes of a point share the rows), which yields the exact arg-min inside the
+//     group, resolves near-ties the cancelling expanded form cannot order, and gives an
+//     accurate minimum distance.  A second group is evaluated when the other lane's best tile
+//     is inside the rounding bound; a third candidate sends the point to the refine kernel.
+//
+// Fault tolerance (Sections 2.3, 4): with FT on, every tile carries its own checksum row.  A
+// tile then holds 30 centroids; register 15 of each lane group belongs to a virtual centroid
+// "sum of the group's 15 centroids" (the Y e1 encoding, prepared by a prologue kernel), so the
+// matrix instructions deliver x.(sum c) - sum ||c||^2/2 next to the 15 scores it must equal.
+// After the tile's instructions (and the injection hook) each lane adds its 15 scores and
+// compares; a mismatch above the threshold is located with the e2 = 1..15 weighted sum
+// (Section 4.1), corrected by subtracting the error, and re-verified before the maximum reads
+// the tile.  If the location does not decode, the point is handed to the refine kernel, which
+// recomputes it without the matrix path.
+#include <cmath>
 #include <cstdlib>
 #include <type_traits>
 
@@ -26,49 +38,75 @@ namespace ftk {
 struct SmallArgs {
     const float *X;
     const float *C;
-    const float *hcn;    // half squared norms, +inf beyond K, padded to nch*kch
+    const float *hcn;    // half squared norms; beyond K: +inf (FT off) or unused (FT on)
     const double *scal;  // scal[0] = max_j ||c_j||^2
     int64_t N;
     int D, K;
-    int kch;      // centroids per LDS chunk (multiple of 32)
-    int nch;      // chunks
-    int nblocks;  // point blocks (256*PT points each)
+    int tpc;          // tiles staged in LDS at a time
+    int nch;          // chunks
+    int tiles_total;  // ceil(K / centroids-per-tile)
+    int nblocks;      // point blocks (SMALLD_WAVES*PT*32 points each)
     int32_t *labels;
     float *mindist;
     int32_t *wl;
     int32_t *wl_count;
     ftk_ft_stats *stats;
     double band_coef;
-    int dbg;
+    // fault tolerance / injection
+    const float *chk_v1;  // [tiles_total*2][D8] plain checksum rows per (tile, lane group)
+    const float *chk_v2;  // [tiles_total*2][D8] weighted (1..15) checksum rows
+    const float *chk_s;   // [tiles_total*2][2]  matching sums of the half norms
+    const ftk_fault *faults;
+    int n_faults;
+    int ft_mode;
+    double ft_coef;       // detection threshold = ft_coef * (||x|| max||c|| + max||c||^2/2)
 };
 
 __device__ __forceinline__ float max3f(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
 
-// Exact (direct-difference, fp32) distances of one point to 8 centroids of one lane group's
-// share of a tile: registers r0..r0+7 of group gw in the tile whose rows start at `base`
-// (`stride` floats per row, LDS chunk or global C).  xlo / xhi hold features 8q..8q+3 and
-// 8q+4..8q+7 of the point, so terms are always added in feature order and identical centroids
-// give bit-identical distances whichever lane evaluates them.  Keeps the running (distance,
-// index) minimum, lowest index on equal distance.
-template <int NQ, bool PADDED>
+constexpr int SMALLD_WAVES = 8;  // waves per workgroup sharing one staged centroid chunk
+constexpr int SMALLD_THREADS = SMALLD_WAVES * 64;
+constexpr int SMALLD_MAX_FAULTS = 4;  // injected faults honoured per point block
+
+// Tile geometry: which centroid sits in register r of lane group g of tile T.
+template <bool FT>
+struct TileGeom {
+    static constexpr int CPT = FT ? 30 : 32;  // centroids per tile
+    static constexpr int RG = FT ? 15 : 16;   // score registers per lane group
+    static __device__ __forceinline__ int centroid(int T, int g, int r)
+    {
+        return FT ? 30 * T + 15 * g + r : 32 * T + Mma<float>::row(r, g);
+    }
+};
+
+// Exact (direct-difference, fp32) distances of one point to 8 centroids: registers r0..r0+7 of
+// lane group gw in tile T, whose LDS / global rows start at `base` (`stride` floats per row).
+// xlo / xhi hold features 8q..8q+3 and 8q+4..8q+7 of the point, so terms are always added in
+// feature order and identical centroids give bit-identical distances whichever lane evaluates
+// them.  Keeps the running (distance, index) minimum, lowest index on equal distance.
+// LDSROWS: rows are addressed by their position in the staged tile and are zero-padded to
+// 8*NQ features; otherwise rows are addressed by centroid index in global C.
+template <int NQ, bool FT, bool LDSROWS>
 __device__ __forceinline__ void eval_rows(const floatx4 (&xlo)[NQ], const floatx4 (&xhi)[NQ],
-                                          const float *base, int stride, int jfirst, int K, int D,
+                                          const float *base, int stride, int T, int K, int D,
                                           int gw, int r0, float &dbest, int &jbest)
 {
-    // PADDED: rows are zero-padded to 8*NQ features (LDS copy), no bounds checks needed; the
-    // point fragments are zero beyond D as well.
     float d[8];
+    int jj[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         // register r = r0 + i of group gw holds tile row 8*(r/4) + 4*gw + r%4; r0 is 0 or 8
         const int row = 8 * (i >> 2) + (i & 3) + 2 * r0 + 4 * gw;
-        const float *c = base + row * stride;
+        const bool real = FT ? (r0 + i < 15) : true;
+        const int j = FT ? 30 * T + 15 * gw + r0 + i : 32 * T + row;
+        jj[i] = (real && j < K) ? j : 0x7fffffff;
+        const float *c = LDSROWS ? base + row * stride : base + (size_t)(j < K ? j : 0) * stride;
         d[i] = 0.f;
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
             floatx4 cl = {0.f, 0.f, 0.f, 0.f}, ch = {0.f, 0.f, 0.f, 0.f};
-            if (PADDED || (8 * q < D && jfirst + row < K)) cl = *reinterpret_cast<const floatx4 *>(c + 8 * q);
-            if (PADDED || (8 * q + 4 < D && jfirst + row < K)) ch = *reinterpret_cast<const floatx4 *>(c + 8 * q + 4);
+            if (LDSROWS || 8 * q < D) cl = *reinterpret_cast<const floatx4 *>(c + 8 * q);
+            if (LDSROWS || 8 * q + 4 < D) ch = *reinterpret_cast<const floatx4 *>(c + 8 * q + 4);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float t = xlo[q][e] - cl[e];
@@ -83,17 +121,13 @@ __device__ __forceinline__ void eval_rows(const floatx4 (&xlo)[NQ], const floatx
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const int j = jfirst + 8 * (i >> 2) + (i & 3) + 2 * r0 + 4 * gw;
         const float db = dbest;
         const int jb = jbest;
-        const bool better = (j < K) & ((d[i] < db) | ((d[i] == db) & (j < jb)));
+        const bool better = (jj[i] != 0x7fffffff) & ((d[i] < db) | ((d[i] == db) & (jj[i] < jb)));
         dbest = better ? d[i] : db;
-        jbest = better ? j : jb;
+        jbest = better ? jj[i] : jb;
     }
 }
-
-constexpr int SMALLD_WAVES = 8;  // waves per workgroup sharing one staged centroid chunk
-constexpr int SMALLD_THREADS = SMALLD_WAVES * 64;
 
 // Best tile maximum, the tile it came from, and the runner-up tile maximum of one lane.
 struct TileBest {
@@ -101,17 +135,22 @@ struct TileBest {
     int t1;
 };
 
-template <int NQ, int PT>
+template <int NQ, int PT, bool FT>
 __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs a)
 {
     using M = Mma<float>;
+    using G = TileGeom<FT>;
     constexpr int SW = 8 * NQ + 4;      // LDS row stride in floats (16 bytes of padding)
     constexpr int TS = 32 * SW + 4;     // LDS tile stride: 16 more bytes so that lanes reading rows
                                         // of different tiles (exact re-evaluation) spread over banks
+    constexpr int RG = G::RG;
+    constexpr int D8 = 8 * NQ;
     extern __shared__ __align__(16) float lds[];
-    const int tiles_per_chunk = a.kch / 32;
-    float *ldsC = lds;                                  // [tiles_per_chunk][TS]
-    float *ldsH = lds + (size_t)tiles_per_chunk * TS;   // [kch] -||c||^2/2 in (tile, group, register) order
+    float *ldsC = lds;                          // [tpc][TS]
+    float *ldsH = lds + (size_t)a.tpc * TS;     // [tpc*32] accumulator start values, (tile, group, register) order
+    __shared__ int sh_next;
+    __shared__ int sh_nf;
+    __shared__ ftk_fault sh_faults[SMALLD_MAX_FAULTS];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -119,10 +158,12 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
     const int col = lane & 31;
     const int g = lane >> 5;
     const int D = a.D;
-    const int tiles_total = (a.K + 31) / 32;
     const float cmax2 = (float)a.scal[0];
     const float cmax = sqrtf(cmax2);
-    int n_refined = 0;
+    const bool resident = a.nch == 1;
+    // per-lane event counters, reduced over the wave at the end
+    int n_checked = 0, n_injected = 0, n_detected = 0, n_corrected = 0, n_recomputed = 0;
+    float worst_resid = 0.f;
 
     // operand fetch of one centroid tile: A fragments and the accumulator start values
     auto load_tile = [&](int t, floatx4 (&av)[NQ], floatx16 &ci) {
@@ -140,56 +181,94 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
         }
     };
 
-    // Blocks of SMALLD_WAVES units (PT*32 points per wave) are handed out dynamically from an
-    // atomic counter so that nothing idles while a queue remains.  The waves of a workgroup
-    // deliberately stay in step (one barrier per block): on this hardware fp32 matrix and
-    // vector instructions share the issue path, and waves that drift into different phases
-    // (one multiplying, one reducing) interleave them finely, which measurably costs throughput.
-    __shared__ int sh_next;
-    const bool resident = a.nch == 1;
+    // stage tiles [ch*tpc, (ch+1)*tpc) into LDS: centroid rows (and checksum rows) plus the
+    // accumulator start values
     auto stage_chunk = [&](int ch) {
-        const int jbase = ch * a.kch;
         constexpr int PPR = 2 * NQ;  // 16-byte pieces per row
-        for (int idx = tid; idx < a.kch * PPR; idx += SMALLD_THREADS) {
+        const int rows = a.tpc * 32;
+        for (int idx = tid; idx < rows * PPR; idx += SMALLD_THREADS) {
             const int rrow = idx / PPR, pc = idx % PPR;
-            const int j = jbase + rrow;
+            const int tl = rrow >> 5, lr = rrow & 31;
+            const int T = ch * a.tpc + tl;
+            const int gg = (lr >> 2) & 1, r = (lr >> 3) * 4 + (lr & 3);
             floatx4 f = {0.f, 0.f, 0.f, 0.f};
-            if (j < a.K) f = load_frag<float, true>(a.C + (size_t)j * D, 4 * pc, D);
-            *reinterpret_cast<floatx4 *>(ldsC + (size_t)(rrow >> 5) * TS + (rrow & 31) * SW + 4 * pc) = f;
+            if (!FT || r < RG) {
+                const int j = G::centroid(T, gg, r);
+                if (j < a.K) f = load_frag<float, true>(a.C + (size_t)j * D, 4 * pc, D);
+            } else if (T < a.tiles_total) {
+                f = *reinterpret_cast<const floatx4 *>(a.chk_v1 + (size_t)(T * 2 + gg) * D8 + 4 * pc);
+            }
+            *reinterpret_cast<floatx4 *>(ldsC + (size_t)tl * TS + lr * SW + 4 * pc) = f;
         }
-        for (int idx = tid; idx < a.kch; idx += SMALLD_THREADS) {
-            const int t = idx >> 5, gg = (idx >> 4) & 1, r = idx & 15;
-            ldsH[idx] = -a.hcn[jbase + t * 32 + M::row(r, gg)];
+        for (int idx = tid; idx < rows; idx += SMALLD_THREADS) {
+            const int tl = idx >> 5, gg = (idx >> 4) & 1, r = idx & 15;
+            const int T = ch * a.tpc + tl;
+            float h;
+            if (!FT) {
+                h = -a.hcn[G::centroid(T, gg, r)];
+            } else if (r < RG) {
+                const int j = G::centroid(T, gg, r);
+                h = j < a.K ? -a.hcn[j] : 0.f;
+            } else {
+                h = T < a.tiles_total ? -a.chk_s[(T * 2 + gg) * 2] : 0.f;
+            }
+            ldsH[idx] = h;
         }
     };
     if (resident) {
         stage_chunk(0);
         __syncthreads();
     }
+
+    // Blocks of SMALLD_WAVES units (PT*32 points per wave) are handed out dynamically from an
+    // atomic counter so that nothing idles while a queue remains.  The waves of a workgroup
+    // deliberately stay in step (one barrier per block): fp32 matrix and vector instructions
+    // share the issue path, and waves that drift into different phases (one multiplying, one
+    // reducing) interleave them finely, which measurably costs throughput.
     int blk = blockIdx.x;
     while (blk < a.nblocks) {
         const int64_t p0 = ((int64_t)blk * SMALLD_WAVES + wave) * (PT * 32);
         floatx4 xf[PT][NQ];
         float xn[PT];
+        float tau[PT];          // checksum detection threshold of this lane's point
+        bool force_refine[PT];  // a tile of this point failed correction
         TileBest best[PT];
 #pragma unroll
         for (int pt = 0; pt < PT; ++pt) {
             int64_t p = p0 + pt * 32 + col;
             if (p >= a.N) p = a.N - 1;
             const float *xrow = a.X + p * D;
-            xn[pt] = 0.f;
+            float s = 0.f;
 #pragma unroll
             for (int q = 0; q < NQ; ++q) {
                 xf[pt][q] = load_frag<float, true>(xrow, 8 * q + 4 * g, D);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) xn[pt] = fmaf(xf[pt][q][e], xf[pt][q][e], xn[pt]);
+                for (int e = 0; e < 4; ++e) s = fmaf(xf[pt][q][e], xf[pt][q][e], s);
             }
+            xn[pt] = s + __shfl_xor(s, 32, 64);
+            tau[pt] = (float)a.ft_coef * (sqrtf(xn[pt]) * cmax + 0.5f * cmax2);
+            force_refine[pt] = false;
             best[pt].m1 = best[pt].m2 = M::neg_inf();
             best[pt].t1 = 0;
         }
 
-        // one output tile: contraction, tile maximum per lane, running best tile
-        auto compute_tile = [&](const floatx4 (&av)[NQ], const floatx16 &ci, int tile) {
+        // faults aimed at this point block
+        int nf = 0;
+        if (a.n_faults > 0) {
+            if (tid == 0) sh_nf = 0;
+            __syncthreads();
+            for (int i = tid; i < a.n_faults; i += SMALLD_THREADS) {
+                if ((int)a.faults[i].workgroup == blk) {
+                    const int slot = atomicAdd(&sh_nf, 1);
+                    if (slot < SMALLD_MAX_FAULTS) sh_faults[slot] = a.faults[i];
+                }
+            }
+            __syncthreads();
+            nf = min(sh_nf, SMALLD_MAX_FAULTS);
+        }
+
+        // one output tile: contraction, (injection, verification,) tile maximum, running best
+        auto compute_tile = [&](const floatx4 (&av)[NQ], const floatx16 &ci, int T) {
 #pragma unroll
             for (int pt = 0; pt < PT; ++pt) {
                 floatx16 acc = ci;
@@ -197,6 +276,85 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
                 for (int q = 0; q < NQ; ++q)
 #pragma unroll
                     for (int e = 0; e < 4; ++e) acc = M::mma(av[q][e], xf[pt][q][e], acc);
+
+                if (nf > 0) {  // fault injection (Section 2.1): flip one bit of one accumulator
+                    for (int i = 0; i < nf; ++i) {
+                        const ftk_fault f = sh_faults[i];
+                        const int seq = (int)(f.tile % (unsigned)(a.tiles_total * PT));
+                        if ((int)(f.wave % SMALLD_WAVES) == wave && seq == T * PT + pt) {
+                            const bool me = lane == (int)(f.lane & 63);
+                            const unsigned mask = 1u << (f.bit & 31);
+                            const int reg = (int)(f.reg & 15);
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                const unsigned bits = __float_as_uint(acc[r]);
+                                acc[r] = (me && r == reg) ? __uint_as_float(bits ^ mask) : acc[r];
+                            }
+                            n_injected += me ? 1 : 0;
+                        }
+                    }
+                }
+
+                if constexpr (FT) {
+                    // verify: the 15 scores of this lane must add up to the carried checksum
+                    float s1 = acc[0];
+#pragma unroll
+                    for (int r = 1; r < RG; ++r) s1 += acc[r];
+                    float resid = s1 - acc[15];
+                    const bool bad = !(fabsf(resid) <= tau[pt]);
+                    n_checked += 1;
+                    if (__any(bad)) {
+                        n_detected += bad ? 1 : 0;
+                        if (a.ft_mode == FTK_FT_CORRECT) {
+                            // locate with the e2 = 1..15 weighted sum; the weighted reference is
+                            // formed here on demand from the weighted checksum row
+                            float s2 = 0.f;
+#pragma unroll
+                            for (int r = 0; r < RG; ++r) s2 = fmaf((float)(r + 1), acc[r], s2);
+                            float ref2 = 0.f;
+                            if (T < a.tiles_total) {
+                                const float *v2 = a.chk_v2 + (size_t)(T * 2 + g) * D8;
+                                ref2 = -a.chk_s[(T * 2 + g) * 2 + 1];
+#pragma unroll
+                                for (int q = 0; q < NQ; ++q) {
+                                    const floatx4 vo = *reinterpret_cast<const floatx4 *>(v2 + 8 * q + 4 * g);
+                                    const floatx4 vp = *reinterpret_cast<const floatx4 *>(v2 + 8 * q + 4 * (1 - g));
+#pragma unroll
+                                    for (int e = 0; e < 4; ++e) {
+                                        const float xo = xf[pt][q][e];
+                                        const float xp = __shfl_xor(xo, 32, 64);
+                                        ref2 = fmaf(xo, vo[e], ref2);
+                                        ref2 = fmaf(xp, vp[e], ref2);
+                                    }
+                                }
+                            }
+                            const float delta = resid;
+                            const float fpos = (s2 - ref2) / delta;
+                            const float rpos = rintf(fpos);
+                            const bool finite = (__float_as_uint(delta) & 0x7f800000u) != 0x7f800000u;
+                            bool ok = bad && finite && fabsf(fpos - rpos) < 0.25f && rpos >= 1.f && rpos <= (float)RG;
+                            const int rfix = ok ? (int)rpos - 1 : -1;
+#pragma unroll
+                            for (int r = 0; r < RG; ++r) acc[r] = (r == rfix) ? acc[r] - delta : acc[r];
+                            float s1b = acc[0];
+#pragma unroll
+                            for (int r = 1; r < RG; ++r) s1b += acc[r];
+                            ok = ok && (fabsf(s1b - acc[15]) <= tau[pt]);
+                            n_corrected += ok ? 1 : 0;
+                            // not decodable (error in the checksum register itself, several errors,
+                            // Inf/NaN): the point is recomputed outside the matrix path
+                            n_recomputed += (bad && !ok) ? 1 : 0;
+                            force_refine[pt] = force_refine[pt] || (bad && !ok);
+                        }
+                    }
+                    worst_resid = fmaxf(worst_resid, bad ? 0.f : fabsf(resid) / tau[pt]);
+                    if (30 * (T + 1) > a.K) {  // last tile: rows beyond K carried zeros, now drop them
+#pragma unroll
+                        for (int r = 0; r < RG; ++r)
+                            acc[r] = (G::centroid(T, g, r) < a.K) ? acc[r] : M::neg_inf();
+                    }
+                }
+
                 float tm = max3f(acc[0], acc[1], acc[2]);
                 tm = max3f(tm, acc[3], acc[4]);
                 tm = max3f(tm, acc[5], acc[6]);
@@ -204,12 +362,12 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
                 tm = max3f(tm, acc[9], acc[10]);
                 tm = max3f(tm, acc[11], acc[12]);
                 tm = max3f(tm, acc[13], acc[14]);
-                tm = __builtin_fmaxf(tm, acc[15]);
+                if constexpr (!FT) tm = __builtin_fmaxf(tm, acc[15]);
                 const float m1 = best[pt].m1, m2 = best[pt].m2;
                 const int t1 = best[pt].t1;
                 const bool c = tm > m1;
                 best[pt].m2 = __builtin_amdgcn_fmed3f(m1, m2, tm);
-                best[pt].t1 = c ? tile : t1;
+                best[pt].t1 = c ? T : t1;
                 best[pt].m1 = __builtin_fmaxf(m1, tm);
             }
         };
@@ -220,8 +378,8 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
                 stage_chunk(ch);
                 __syncthreads();
             }
-            const int tile0 = ch * tiles_per_chunk;
-            const int ntile = min(tiles_per_chunk, tiles_total - tile0);
+            const int tile0 = ch * a.tpc;
+            const int ntile = min(a.tpc, a.tiles_total - tile0);
             // two operand register sets: the fetch of the next tile is in flight while the
             // current one is multiplied
             floatx4 avA[NQ], avB[NQ];
@@ -250,8 +408,10 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
                     xlo[q][e] = g == 0 ? mine : other;
                     xhi[q][e] = g == 0 ? other : mine;
                 }
-            const float xnt = xn[pt] + __shfl_xor(xn[pt], 32, 64);
-            const float bound = (float)a.band_coef * (sqrtf(xnt) * cmax + 0.5f * cmax2);
+            // scores inside `bound` of each other cannot be ordered: rounding of the expanded
+            // form, plus (FT on) an undetected error below the detection threshold
+            float bound = (float)a.band_coef * (sqrtf(xn[pt]) * cmax + 0.5f * cmax2);
+            if (FT) bound += tau[pt];
             const float om1 = __shfl_xor(best[pt].m1, 32, 64), om2 = __shfl_xor(best[pt].m2, 32, 64);
             const int ot1 = __shfl_xor(best[pt].t1, 32, 64);
             const bool mine_wins = best[pt].m1 > om1 || (best[pt].m1 == om1 && g == 0);
@@ -264,23 +424,24 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
             const int Ts = mine_wins ? ot1 : best[pt].t1;
             // a third candidate tile anywhere: left to the refine kernel
             const bool over = fmaxf(best[pt].m2, om2) >= thr;
+            const bool forced = force_refine[pt] || (__shfl_xor((int)force_refine[pt], 32, 64) != 0);
             float dbest = __builtin_huge_valf();
             int jbest = 0x7fffffff;
             if (resident) {
-                eval_rows<NQ, true>(xlo, xhi, ldsC + Tw * TS, SW, Tw * 32, a.K, D, gw, 8 * g, dbest, jbest);
+                eval_rows<NQ, FT, true>(xlo, xhi, ldsC + Tw * TS, SW, Tw, a.K, D, gw, 8 * g, dbest, jbest);
                 if (__any(second)) {
                     float d2 = dbest;
                     int j2 = jbest;
-                    eval_rows<NQ, true>(xlo, xhi, ldsC + Ts * TS, SW, Ts * 32, a.K, D, 1 - gw, 8 * g, d2, j2);
+                    eval_rows<NQ, FT, true>(xlo, xhi, ldsC + Ts * TS, SW, Ts, a.K, D, 1 - gw, 8 * g, d2, j2);
                     dbest = second ? d2 : dbest;
                     jbest = second ? j2 : jbest;
                 }
             } else {
-                eval_rows<NQ, false>(xlo, xhi, a.C + (size_t)Tw * 32 * D, D, Tw * 32, a.K, D, gw, 8 * g, dbest, jbest);
+                eval_rows<NQ, FT, false>(xlo, xhi, a.C, D, Tw, a.K, D, gw, 8 * g, dbest, jbest);
                 if (__any(second)) {
                     float d2 = dbest;
                     int j2 = jbest;
-                    eval_rows<NQ, false>(xlo, xhi, a.C + (size_t)Ts * 32 * D, D, Ts * 32, a.K, D, 1 - gw, 8 * g, d2, j2);
+                    eval_rows<NQ, FT, false>(xlo, xhi, a.C, D, Ts, a.K, D, 1 - gw, 8 * g, d2, j2);
                     dbest = second ? d2 : dbest;
                     jbest = second ? j2 : jbest;
                 }
@@ -293,7 +454,7 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
             if (live && g == 0) {
                 a.labels[p] = jbest == 0x7fffffff ? 0 : jbest;
                 if (a.mindist) a.mindist[p] = dbest;
-                if (!(thr == thr) || over) {   // NaN scores or a third candidate tile
+                if (!(thr == thr) || over || forced) {   // NaN scores, a third candidate, or a failed repair
                     const int pos = atomicAdd(a.wl_count, 1);
                     a.wl[pos] = (int32_t)p;
                 }
@@ -304,7 +465,68 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
         __syncthreads();
         blk = sh_next;
     }
-    (void)n_refined;
+
+    if (a.stats && (FT || a.n_faults > 0)) {
+        int v[5] = {n_checked, n_injected, n_detected, n_corrected, n_recomputed};
+#pragma unroll
+        for (int i = 0; i < 5; ++i)
+#pragma unroll
+            for (int mask = 1; mask < 64; mask <<= 1) v[i] += __shfl_xor(v[i], mask, 64);
+#pragma unroll
+        for (int mask = 1; mask < 64; mask <<= 1) worst_resid = fmaxf(worst_resid, __shfl_xor(worst_resid, mask, 64));
+        if (lane == 0) {
+            unsigned long long *s = reinterpret_cast<unsigned long long *>(a.stats);
+            if (v[0]) atomicAdd(s + 0, (unsigned long long)v[0]);
+            if (v[1]) atomicAdd(s + 1, (unsigned long long)v[1]);
+            if (v[2]) atomicAdd(s + 2, (unsigned long long)v[2]);
+            if (v[3]) atomicAdd(s + 3, (unsigned long long)v[3]);
+            if (v[4]) atomicAdd(s + 4, (unsigned long long)v[4]);
+            if (FT) atomicMax(s + 7, (unsigned long long)(fminf(worst_resid, 4000.f) * 1.0e6f));
+        }
+    }
+}
+
+// Checksum rows of the small-D tiles (FT on): for tile T and lane group g, over the group's 15
+// centroids j = 30T + 15g + r (those below K):
+//   v1[d] = sum_r c_{j,d}, v2[d] = sum_r (r+1) c_{j,d}   (the Y e1 / Y e2 encodings, Section 4.1)
+// in double, rounded once; and the matching sums of the half squared norms.
+__global__ __launch_bounds__(64) void smalld_checksum_kernel(const float *C, const float *hcn, int D, int D8,
+                                                             int K, float *v1, float *v2, float *cs)
+{
+    const int tg = blockIdx.x;  // T*2 + g
+    const int j0 = 30 * (tg >> 1) + 15 * (tg & 1);
+    for (int d = threadIdx.x; d < D8; d += blockDim.x) {
+        double s1 = 0.0, s2 = 0.0;
+        if (d < D) {
+            for (int r = 0; r < 15 && j0 + r < K; ++r) {
+                const double v = (double)C[(size_t)(j0 + r) * D + d];
+                s1 += v;
+                s2 = fma((double)(r + 1), v, s2);
+            }
+        }
+        v1[(size_t)tg * D8 + d] = (float)s1;
+        v2[(size_t)tg * D8 + d] = (float)s2;
+    }
+    if (threadIdx.x == 0) {
+        double h1 = 0.0, h2 = 0.0;
+        for (int r = 0; r < 15 && j0 + r < K; ++r) {
+            const double h = (double)hcn[j0 + r];
+            h1 += h;
+            h2 = fma((double)(r + 1), h, h2);
+        }
+        cs[2 * tg] = (float)h1;
+        cs[2 * tg + 1] = (float)h2;
+    }
+}
+
+ftk_status launch_smalld_checksums(const AssignCall &c, const AssignPlan &p, const Workspace &w, hipStream_t st)
+{
+    const int tiles_total = (int)ceil_div(c.K, 30);
+    hipLaunchKernelGGL(smalld_checksum_kernel, dim3(tiles_total * 2), dim3(64), 0, st, (const float *)c.C,
+                       (const float *)w.hcn, c.D, p.D8, c.K, (float *)w.chk_v1, (float *)w.chk_v2,
+                       (float *)w.chk_s);
+    FTK_TRY_HIP(hipGetLastError());
+    return FTK_OK;
 }
 
 bool smalld_supported(ftk_dtype dtype, int D, int K)
@@ -313,44 +535,59 @@ bool smalld_supported(ftk_dtype dtype, int D, int K)
     return dtype == FTK_F32 && D <= 32 && D % 4 == 0;
 }
 
-static int smalld_pt(int D8) { return D8 <= 16 ? 2 : 2; }
+// Detection threshold coefficient: the residual "15 scores minus carried checksum" is pure
+// rounding noise when no fault occurred.  With n = 15 terms of magnitude up to
+// B = ||x|| max||c|| + max||c||^2/2, the vector sum, the checksum product (magnitude up to n B)
+// and the scores themselves each contribute about u B n (sqrt(n) + sqrt(D)) in the worst
+// realistic alignment; KAPPA is the safety factor on top (calibrated so that the largest
+// fault-free residual seen on the five workloads stays below half the threshold).
+static constexpr double SMALLD_FT_KAPPA = 2.0;
+static double smalld_ft_coef(int D)
+{
+    const double n = 15.0;
+    return SMALLD_FT_KAPPA * Mma<float>::kEps * n * (std::sqrt(n) + std::sqrt((double)D + 4.0));
+}
 
 void plan_smalld(int64_t N, int D, int K, ftk_ft_mode ft, AssignPlan &p)
 {
-    (void)ft;
+    const bool FT = ft != FTK_FT_OFF;
     p.variant = VAR_SMALLD;
     p.TM = 32;
     p.TN = 32;
     p.D8 = (int)ceil_div(D, 8) * 8;
-    p.PT = smalld_pt(p.D8);
+    p.PT = 2;
     p.KT = 1;
     p.waves = SMALLD_WAVES;
     const int SW = p.D8 + 4;
-    // chunk: as many centroids as fit 64 KB of LDS, all of them if possible
-    int kch = (64 * 1024) / (SW * 4 + 4 + 1) / 32 * 32;
-    const int Kr = (int)ceil_div(K, 32) * 32;
-    if (kch > Kr) kch = Kr;
-    p.kch = kch;
-    p.KC = kch;
-    p.nkc = (int)ceil_div(K, kch);
+    const int tile_bytes = (32 * SW + 4) * 4 + 32 * 4;
+    const int tiles_total = (int)ceil_div(K, FT ? 30 : 32);
+    // chunk: as many tiles as fit 72 KB of LDS (two workgroups per CU), all of them if possible
+    int tpc = (72 * 1024) / tile_bytes;
+    if (tpc > tiles_total) tpc = tiles_total;
+    p.kch = tpc * 32;
+    p.KC = tpc * 32;
+    p.nkc = (int)ceil_div(tiles_total, tpc);
     p.DQ = p.D8 / 8;
     p.points_per_wg = SMALLD_WAVES * p.PT * 32;
     p.workgroups = ceil_div(N, p.points_per_wg);
-    p.lds_bytes = (size_t)(kch / 32) * (32 * SW + 4) * 4 + (size_t)kch * 4;
+    p.lds_bytes = (size_t)tpc * tile_bytes;
     int resident_wgs = (int)(160 * 1024 / (p.lds_bytes + 2048));
     if (resident_wgs > 2) resident_wgs = 2;
     if (resident_wgs < 1) resident_wgs = 1;
     const int64_t cap = 256LL * resident_wgs;
     p.grid = (int)(p.workgroups < cap ? p.workgroups : cap);
-    p.tiles_per_wave = (int)(ceil_div(K, 32) * p.PT * ceil_div(p.workgroups, p.grid));
+    p.tiles_per_wave = tiles_total * p.PT;
     p.regs_per_tile = 16;
-    p.hcn_pad_inf = true;
+    p.hcn_pad_inf = !FT;
 }
 
-template <int NQ, int PT>
-static void launch_smalld_t(const SmallArgs &a, const AssignPlan &p, hipStream_t st)
+template <int NQ>
+static void launch_smalld_t(const SmallArgs &a, const AssignPlan &p, bool ft, hipStream_t st)
 {
-    hipLaunchKernelGGL((assign_smalld_kernel<NQ, PT>), dim3(p.grid), dim3(SMALLD_THREADS), p.lds_bytes, st, a);
+    if (ft)
+        hipLaunchKernelGGL((assign_smalld_kernel<NQ, 2, true>), dim3(p.grid), dim3(SMALLD_THREADS), p.lds_bytes, st, a);
+    else
+        hipLaunchKernelGGL((assign_smalld_kernel<NQ, 2, false>), dim3(p.grid), dim3(SMALLD_THREADS), p.lds_bytes, st, a);
 }
 
 ftk_status launch_assign_smalld(const AssignCall &c, const AssignPlan &p, const Workspace &w, hipStream_t st)
@@ -359,6 +596,7 @@ ftk_status launch_assign_smalld(const AssignCall &c, const AssignPlan &p, const 
         set_error("small-D variant needs 16-byte aligned X and C");
         return FTK_EALIGN;
     }
+    const bool FT = c.ft != FTK_FT_OFF;
     SmallArgs a;
     a.X = (const float *)c.X;
     a.C = (const float *)c.C;
@@ -367,8 +605,9 @@ ftk_status launch_assign_smalld(const AssignCall &c, const AssignPlan &p, const 
     a.N = c.N;
     a.D = c.D;
     a.K = c.K;
-    a.kch = p.kch;
+    a.tpc = p.kch / 32;
     a.nch = p.nkc;
+    a.tiles_total = (int)ceil_div(c.K, FT ? 30 : 32);
     a.nblocks = (int)p.workgroups;
     a.labels = c.labels;
     a.mindist = (float *)c.mindist;
@@ -376,12 +615,18 @@ ftk_status launch_assign_smalld(const AssignCall &c, const AssignPlan &p, const 
     a.wl_count = w.wl_count;
     a.stats = c.stats;
     a.band_coef = 4.0 * (c.D + 4) * Mma<float>::kEps;
-    a.dbg = getenv("FTK_DBG") ? atoi(getenv("FTK_DBG")) : 0;
+    a.chk_v1 = (const float *)w.chk_v1;
+    a.chk_v2 = (const float *)w.chk_v2;
+    a.chk_s = (const float *)w.chk_s;
+    a.faults = c.faults;
+    a.n_faults = c.n_faults;
+    a.ft_mode = (int)c.ft;
+    a.ft_coef = smalld_ft_coef(c.D);
     switch (p.D8 / 8) {
-    case 1: launch_smalld_t<1, 2>(a, p, st); break;
-    case 2: launch_smalld_t<2, 2>(a, p, st); break;
-    case 3: launch_smalld_t<3, 2>(a, p, st); break;
-    default: launch_smalld_t<4, 2>(a, p, st); break;
+    case 1: launch_smalld_t<1>(a, p, FT, st); break;
+    case 2: launch_smalld_t<2>(a, p, FT, st); break;
+    case 3: launch_smalld_t<3>(a, p, FT, st); break;
+    default: launch_smalld_t<4>(a, p, FT, st); break;
     }
     FTK_TRY_HIP(hipGetLastError());
     return FTK_OK;

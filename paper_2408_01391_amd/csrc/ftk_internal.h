@@ -93,6 +93,8 @@ struct AssignCall {
 };
 ftk_status launch_centroid_prologue(const AssignCall &c, const AssignPlan &p, const Workspace &w,
                                     hipStream_t st);
+ftk_status launch_smalld_checksums(const AssignCall &c, const AssignPlan &p, const Workspace &w,
+                                   hipStream_t st);
 ftk_status launch_assign(const AssignCall &c, const AssignPlan &p, const Workspace &w, hipStream_t st);
 ftk_status launch_refine(const AssignCall &c, const Workspace &w, hipStream_t st);
 

@@ -85,22 +85,24 @@ ftk_status launch_centroid_prologue(const AssignCall &c, const AssignPlan &p, co
     hipLaunchKernelGGL(reset_assign_state_kernel, dim3(1), dim3(64), 0, st, w.scal, w.wl_count);
     const int Kpad = p.nkc * p.KC;
     const int blocks = (int)ceil_div(Kpad, 4);
-    const int ntiles = p.nkc * p.KT;
+    const int ntiles = p.nkc;  // generic variant: one checksum row pair per K-chunk
+    const bool generic_ft = c.ft != FTK_FT_OFF && p.variant == VAR_GENERIC;
     if (c.dtype == FTK_F32) {
         hipLaunchKernelGGL((centroid_norms_kernel<float>), dim3(blocks), dim3(256), 0, st,
                            (const float *)c.C, c.D, c.K, Kpad, (float *)w.hcn, w.scal, (int)p.hcn_pad_inf);
-        if (c.ft != FTK_FT_OFF)
+        if (generic_ft)
             hipLaunchKernelGGL((centroid_checksum_kernel<float>), dim3(ntiles), dim3(256), 0, st,
-                               (const float *)c.C, (const float *)w.hcn, c.D, p.D8, c.K, p.TM,
+                               (const float *)c.C, (const float *)w.hcn, c.D, p.D8, c.K, p.KC,
                                (float *)w.chk_v1, (float *)w.chk_v2, (float *)w.chk_s);
     } else {
         hipLaunchKernelGGL((centroid_norms_kernel<double>), dim3(blocks), dim3(256), 0, st,
                            (const double *)c.C, c.D, c.K, Kpad, (double *)w.hcn, w.scal, (int)p.hcn_pad_inf);
-        if (c.ft != FTK_FT_OFF)
+        if (generic_ft)
             hipLaunchKernelGGL((centroid_checksum_kernel<double>), dim3(ntiles), dim3(256), 0, st,
-                               (const double *)c.C, (const double *)w.hcn, c.D, p.D8, c.K, p.TM,
+                               (const double *)c.C, (const double *)w.hcn, c.D, p.D8, c.K, p.KC,
                                (double *)w.chk_v1, (double *)w.chk_v2, (double *)w.chk_s);
     }
+    if (c.ft != FTK_FT_OFF && p.variant == VAR_SMALLD) FTK_TRY(launch_smalld_checksums(c, p, w, st));
     FTK_TRY_HIP(hipGetLastError());
     return FTK_OK;
 }

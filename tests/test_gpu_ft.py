@@ -1,0 +1,123 @@
+"""Fault tolerance of the assignment step on the GPU (paper Sections 2.1, 2.3, 4).
+
+With FT on and single-bit flips injected into the accumulators of the matrix instructions,
+the labels must equal those of the fault-free run; without FT the same flips corrupt them."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2408_01391_amd import binding as ftk, synth
+from tests.gpu_util import DEV, check_assign, to_dev
+
+pytestmark = pytest.mark.gpu
+
+# (name, N, D, K, dtype): one shape per kernel variant / dtype
+SHAPES = [
+    ("small-D resident", 40000, 8, 1000, "f32"),
+    ("small-D streamed", 30000, 32, 1500, "f32"),
+    ("small-D ragged", 5000, 12, 77, "f32"),
+]
+
+
+def _problem(N, D, K, dtype, seed=0):
+    X, C = synth.random_problem(seed + N + D + K, N, D, K, dtype, spread=6.0)
+    return X, C
+
+
+def _run(X, C, ft_mode, faults=None):
+    Xd, Cd = to_dev(X), to_dev(C)
+    stats = ftk.new_stats(DEV)
+    labels, mind = ftk.kmeans_assign(Xd, Cd, ft_mode=ft_mode, faults=faults, stats=stats)
+    torch.cuda.synchronize()
+    return labels.cpu().numpy(), mind.cpu().numpy(), ftk.stats_dict(stats)
+
+
+def _random_faults(geom, n, seed, bits=None):
+    rng = np.random.default_rng(seed)
+    wgs = rng.choice(geom.workgroups, size=min(n, geom.workgroups), replace=False)
+    rows = []
+    for wg in wgs:
+        rows.append((int(wg), int(rng.integers(geom.waves_per_workgroup)), int(rng.integers(geom.tiles_per_wave)),
+                     int(rng.integers(geom.regs_per_tile)), int(rng.integers(geom.lanes)),
+                     int(rng.integers(geom.bits) if bits is None else rng.choice(bits))))
+    return rows
+
+
+@pytest.mark.parametrize("name,N,D,K,dtype", SHAPES)
+def test_ft_on_without_faults_matches_oracle_and_raises_no_alarm(name, N, D, K, dtype):
+    X, C = _problem(N, D, K, dtype)
+    print("ft clean", name, flush=True)
+    lab_off, md_off, _ = _run(X, C, ftk.FT_OFF)
+    lab_on, md_on, st = _run(X, C, ftk.FT_CORRECT)
+    check_assign(X, C, lab_on, md_on)
+    assert np.array_equal(lab_on, lab_off)
+    assert st["tiles_checked"] > 0
+    assert st["detected"] == 0 and st["corrected"] == 0 and st["recomputed"] == 0
+    # headroom of the detection threshold over rounding noise
+    assert st["max_residual_ppm"] < 500_000, st
+
+
+@pytest.mark.parametrize("name,N,D,K,dtype", SHAPES)
+def test_one_random_flip_per_workgroup_is_repaired(name, N, D, K, dtype):
+    """The paper's stress model: every workgroup corrupts one random element by one random bit."""
+    X, C = _problem(N, D, K, dtype)
+    code = ftk.F32 if dtype == "f32" else ftk.F64
+    geom = ftk.assign_geometry(code, N, D, K, ftk.FT_CORRECT)
+    rows = _random_faults(geom, geom.workgroups, seed=11)
+    faults = ftk.make_faults(rows, DEV)
+    print("ft stress", name, "faults", len(rows), flush=True)
+    lab_clean, md_clean, _ = _run(X, C, ftk.FT_CORRECT)
+    lab, md, st = _run(X, C, ftk.FT_CORRECT, faults)
+    assert st["injected"] == len(rows), st
+    assert np.array_equal(lab, lab_clean), "%d labels changed under injection" % (lab != lab_clean).sum()
+    assert st["detected"] >= 1 and st["detected"] <= st["injected"]
+    assert st["corrected"] + st["recomputed"] == st["detected"], st
+    assert st["uncorrectable"] == 0
+    assert np.allclose(md, md_clean, rtol=1e-4, atol=1e-3 * (1 + np.abs(md_clean).max()))
+
+
+def test_high_bit_flips_corrupt_labels_without_ft_and_not_with_it():
+    name, N, D, K, dtype = SHAPES[0]
+    X, C = _problem(N, D, K, dtype)
+    geom_off = ftk.assign_geometry(ftk.F32, N, D, K, ftk.FT_OFF)
+    rng = np.random.default_rng(5)
+    # flip the sign or a high exponent bit of four scores in every workgroup
+    rows = [(wg, int(rng.integers(geom_off.waves_per_workgroup)), int(rng.integers(geom_off.tiles_per_wave)),
+             int(rng.integers(15)), int(rng.integers(64)), int(rng.choice([31, 30, 29])))
+            for wg in range(geom_off.workgroups) for _ in range(4)]
+    faults = ftk.make_faults(rows, DEV)
+    lab_clean, _, _ = _run(X, C, ftk.FT_OFF)
+    lab_bad, _, st_off = _run(X, C, ftk.FT_OFF, faults)
+    assert st_off["injected"] > 0
+    assert (lab_bad != lab_clean).sum() > 0, "injection had no visible effect with FT off"
+    lab_ft, _, st = _run(X, C, ftk.FT_CORRECT, faults)
+    assert np.array_equal(lab_ft, lab_clean)
+    assert st["detected"] > 0.9 * st["injected"] > 0    # a flip of a score near zero can stay below the threshold
+
+
+@pytest.mark.parametrize("reg", [0, 7, 14, 15])
+@pytest.mark.parametrize("bit", [31, 30, 27, 23, 20])
+def test_every_register_and_bit_class_is_handled(reg, bit):
+    """Score registers are corrected from the decoded location; register 15 holds the carried
+    checksum itself, whose corruption cannot be located and sends the point to recomputation."""
+    name, N, D, K, dtype = SHAPES[0]
+    X, C = _problem(N, D, K, dtype)
+    faults = ftk.make_faults([(0, 1, 9, reg, 37, bit), (2, 0, 40, reg, 5, bit)], DEV)
+    lab_clean, _, _ = _run(X, C, ftk.FT_CORRECT)
+    lab, _, st = _run(X, C, ftk.FT_CORRECT, faults)
+    assert st["injected"] == 2
+    assert np.array_equal(lab, lab_clean)
+    assert st["corrected"] + st["recomputed"] == st["detected"]
+    if bit >= 27:
+        assert st["detected"] == 2                     # large errors are always seen
+        if reg == 15:
+            assert st["recomputed"] == 2 and st["corrected"] == 0
+
+
+def test_detect_mode_only_counts():
+    name, N, D, K, dtype = SHAPES[0]
+    X, C = _problem(N, D, K, dtype)
+    faults = ftk.make_faults([(1, 3, 17, 4, 50, 30)], DEV)
+    _, _, st = _run(X, C, ftk.FT_DETECT, faults)
+    assert st["injected"] == 1 and st["detected"] == 1
+    assert st["corrected"] == 0 and st["recomputed"] == 0
