@@ -212,11 +212,9 @@ __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a
         int label = i1;
         T dist = xn[pt] - (T)2 * m1;
         dist = dist > T(0) ? dist : T(0);
+        worklist_push(live && amb3 && g == 0, (int32_t)p, a.wl, a.wl_count);
         if (live && amb3) {
-            if (g == 0) {
-                const int pos = atomicAdd(a.wl_count, 1);
-                a.wl[pos] = (int32_t)p;
-            }
+            // three or more candidates: settled by the refine kernel
         } else if (live && amb2) {
             // two candidates: lane groups 0/1 each evaluate one of them exactly
             const int ja = min(i1, i2), jb = max(i1, i2);

@@ -60,6 +60,7 @@ struct SmallArgs {
     int n_faults;
     int ft_mode;
     double ft_coef;       // detection threshold = ft_coef * (||x|| max||c|| + max||c||^2/2)
+    int dbg;
 };
 
 __device__ __forceinline__ float max3f(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
@@ -231,6 +232,7 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
         floatx4 xf[PT][NQ];
         float xn[PT];
         float tau[PT];          // checksum detection threshold of this lane's point
+        float inv_tau[PT];
         bool force_refine[PT];  // a tile of this point failed correction
         TileBest best[PT];
 #pragma unroll
@@ -247,6 +249,7 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
             }
             xn[pt] = s + __shfl_xor(s, 32, 64);
             tau[pt] = (float)a.ft_coef * (sqrtf(xn[pt]) * cmax + 0.5f * cmax2);
+            inv_tau[pt] = 1.0f / tau[pt];
             force_refine[pt] = false;
             best[pt].m1 = best[pt].m2 = M::neg_inf();
             best[pt].t1 = 0;
@@ -268,16 +271,24 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
         }
 
         // one output tile: contraction, (injection, verification,) tile maximum, running best
-        auto compute_tile = [&](const floatx4 (&av)[NQ], const floatx16 &ci, int T) {
+        auto compute_tile = [&](auto inj_tag, const floatx4 (&av)[NQ], const floatx16 &ci, int T) {
+            constexpr bool INJ = decltype(inj_tag)::value;
+            // all matrix instructions of the tile first: the PT accumulator chains are independent
+            // and interleave on the matrix pipe; verification and reduction follow per point tile
+            floatx16 accs[PT];
+#pragma unroll
+            for (int pt = 0; pt < PT; ++pt) accs[pt] = ci;
+#pragma unroll
+            for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int pt = 0; pt < PT; ++pt) accs[pt] = M::mma(av[q][e], xf[pt][q][e], accs[pt]);
 #pragma unroll
             for (int pt = 0; pt < PT; ++pt) {
-                floatx16 acc = ci;
-#pragma unroll
-                for (int q = 0; q < NQ; ++q)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) acc = M::mma(av[q][e], xf[pt][q][e], acc);
+                floatx16 acc = accs[pt];
 
-                if (nf > 0) {  // fault injection (Section 2.1): flip one bit of one accumulator
+                if constexpr (INJ) {  // fault injection (Section 2.1): flip one bit of one accumulator
                     for (int i = 0; i < nf; ++i) {
                         const ftk_fault f = sh_faults[i];
                         const int seq = (int)(f.tile % (unsigned)(a.tiles_total * PT));
@@ -295,15 +306,14 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
                     }
                 }
 
-                if constexpr (FT) {
+                if (FT && !(a.dbg & 1)) {
                     // verify: the 15 scores of this lane must add up to the carried checksum
                     float s1 = acc[0];
 #pragma unroll
                     for (int r = 1; r < RG; ++r) s1 += acc[r];
                     float resid = s1 - acc[15];
                     const bool bad = !(fabsf(resid) <= tau[pt]);
-                    n_checked += 1;
-                    if (__any(bad)) {
+                    if (__builtin_expect(__any(bad), 0)) {
                         n_detected += bad ? 1 : 0;
                         if (a.ft_mode == FTK_FT_CORRECT) {
                             // locate with the e2 = 1..15 weighted sum; the weighted reference is
@@ -347,8 +357,8 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
                             force_refine[pt] = force_refine[pt] || (bad && !ok);
                         }
                     }
-                    worst_resid = fmaxf(worst_resid, bad ? 0.f : fabsf(resid) / tau[pt]);
-                    if (30 * (T + 1) > a.K) {  // last tile: rows beyond K carried zeros, now drop them
+                    worst_resid = fmaxf(worst_resid, bad ? 0.f : fabsf(resid) * inv_tau[pt]);
+                    if (__builtin_expect(30 * (T + 1) > a.K, 0)) {  // last tile: rows beyond K carried zeros, now drop them
 #pragma unroll
                         for (int r = 0; r < RG; ++r)
                             acc[r] = (G::centroid(T, g, r) < a.K) ? acc[r] : M::neg_inf();
@@ -381,16 +391,23 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
             const int tile0 = ch * a.tpc;
             const int ntile = min(a.tpc, a.tiles_total - tile0);
             // two operand register sets: the fetch of the next tile is in flight while the
-            // current one is multiplied
-            floatx4 avA[NQ], avB[NQ];
-            floatx16 ciA, ciB;
-            load_tile(0, avA, ciA);
-            for (int t = 0; t < ntile; t += 2) {
-                load_tile(min(t + 1, ntile - 1), avB, ciB);
-                compute_tile(avA, ciA, tile0 + t);
-                load_tile(min(t + 2, ntile - 1), avA, ciA);
-                if (t + 1 < ntile) compute_tile(avB, ciB, tile0 + t + 1);
-            }
+            // current one is multiplied; the injection hook is compiled in only when faults are
+            // listed for this block, so the common sweep has no per-tile branch for it
+            auto sweep = [&](auto inj_tag) {
+                floatx4 avA[NQ], avB[NQ];
+                floatx16 ciA, ciB;
+                load_tile(0, avA, ciA);
+                for (int t = 0; t < ntile; t += 2) {
+                    load_tile(min(t + 1, ntile - 1), avB, ciB);
+                    compute_tile(inj_tag, avA, ciA, tile0 + t);
+                    load_tile(min(t + 2, ntile - 1), avA, ciA);
+                    if (t + 1 < ntile) compute_tile(inj_tag, avB, ciB, tile0 + t + 1);
+                }
+            };
+            if (nf > 0)
+                sweep(std::true_type{});
+            else
+                sweep(std::false_type{});
         }
 
         // ---- exact evaluation of the winning group; the two lanes of a point share its rows ----
@@ -411,7 +428,7 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
             // scores inside `bound` of each other cannot be ordered: rounding of the expanded
             // form, plus (FT on) an undetected error below the detection threshold
             float bound = (float)a.band_coef * (sqrtf(xn[pt]) * cmax + 0.5f * cmax2);
-            if (FT) bound += tau[pt];
+            if (FT && !(a.dbg & 2)) bound += tau[pt];
             const float om1 = __shfl_xor(best[pt].m1, 32, 64), om2 = __shfl_xor(best[pt].m2, 32, 64);
             const int ot1 = __shfl_xor(best[pt].t1, 32, 64);
             const bool mine_wins = best[pt].m1 > om1 || (best[pt].m1 == om1 && g == 0);
@@ -454,12 +471,11 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
             if (live && g == 0) {
                 a.labels[p] = jbest == 0x7fffffff ? 0 : jbest;
                 if (a.mindist) a.mindist[p] = dbest;
-                if (!(thr == thr) || over || forced) {   // NaN scores, a third candidate, or a failed repair
-                    const int pos = atomicAdd(a.wl_count, 1);
-                    a.wl[pos] = (int32_t)p;
-                }
             }
+            // NaN scores, a third candidate, or a failed repair: exact recomputation
+            worklist_push(live && g == 0 && (!(thr == thr) || over || forced), (int32_t)p, a.wl, a.wl_count);
         }
+        if (FT) n_checked += a.tiles_total * PT;
         __syncthreads();
         if (tid == 0) sh_next = (int)gridDim.x + atomicAdd(a.wl_count + 1, 1);
         __syncthreads();
@@ -541,7 +557,7 @@ bool smalld_supported(ftk_dtype dtype, int D, int K)
 // and the scores themselves each contribute about u B n (sqrt(n) + sqrt(D)) in the worst
 // realistic alignment; KAPPA is the safety factor on top (calibrated so that the largest
 // fault-free residual seen on the five workloads stays below half the threshold).
-static constexpr double SMALLD_FT_KAPPA = 2.0;
+static constexpr double SMALLD_FT_KAPPA = 1.0;
 static double smalld_ft_coef(int D)
 {
     const double n = 15.0;
@@ -622,6 +638,7 @@ ftk_status launch_assign_smalld(const AssignCall &c, const AssignPlan &p, const 
     a.n_faults = c.n_faults;
     a.ft_mode = (int)c.ft;
     a.ft_coef = smalld_ft_coef(c.D);
+    a.dbg = getenv("FTK_DBG") ? atoi(getenv("FTK_DBG")) : 0;
     switch (p.D8 / 8) {
     case 1: launch_smalld_t<1>(a, p, FT, st); break;
     case 2: launch_smalld_t<2>(a, p, FT, st); break;

@@ -134,6 +134,19 @@ __device__ __forceinline__ Top3<T> top3_insert(Top3<T> b, T s, int j)
     return o;
 }
 
+// Append this lane's point to the refine work-list if `need`; one atomic per wave.
+__device__ __forceinline__ void worklist_push(bool need, int32_t point, int32_t *wl, int32_t *wl_count)
+{
+    const unsigned long long m = __ballot(need);
+    if (m == 0ull) return;
+    const int lane = (int)(threadIdx.x & 63);
+    const int leader = __ffsll((long long)m) - 1;
+    int base = 0;
+    if (lane == leader) base = atomicAdd(wl_count, (int)__popcll(m));
+    base = __shfl(base, leader, 64);
+    if (need) wl[base + (int)__popcll(m & ((1ull << lane) - 1ull))] = point;
+}
+
 __device__ __forceinline__ float shfl_xor_t(float v, int m) { return __shfl_xor(v, m, 64); }
 __device__ __forceinline__ double shfl_xor_t(double v, int m) { return __shfl_xor(v, m, 64); }
 __device__ __forceinline__ int shfl_xor_t(int v, int m) { return __shfl_xor(v, m, 64); }
