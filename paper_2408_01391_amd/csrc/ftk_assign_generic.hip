@@ -13,6 +13,7 @@
 // best indices; a point whose runner-up lies within a rigorous rounding bound of the winner
 // is settled by evaluating the two candidates in direct-difference form in double, and a
 // point with three or more candidates inside the bound is queued for the refine kernel.
+#include <cmath>
 #include <type_traits>
 
 #include "ftk_internal.h"
@@ -34,7 +35,19 @@ struct GenericArgs {
     int32_t *wl_count;
     ftk_ft_stats *stats;
     double band_coef;  // ambiguity band = band_coef * (||x|| * max||c|| + max||c||^2 / 2)
+    // fault tolerance / injection
+    const T *chk_v1;   // [nkc][D8] per-chunk plain checksum row  (sum of the chunk's centroids)
+    const T *chk_v2;   // [nkc][D8] per-chunk weighted checksum row (weights 1..KC)
+    const T *chk_s;    // [nkc][2]  matching sums of the half squared norms
+    const ftk_fault *faults;
+    int n_faults;
+    int ft_mode;
+    double ft_coef;    // detection threshold = ft_coef * (||x|| * max||c|| + max||c||^2 / 2)
 };
+
+constexpr int GENERIC_MAX_FAULTS = 4;
+
+constexpr double GENERIC_FT_KAPPA = 1.0;
 
 template <typename T>
 struct GenericCfg;
@@ -47,7 +60,7 @@ struct GenericCfg<double> {
     static constexpr int PT = 4, KT = 4, WAVES = 4, DQMAX = 8;
 };
 
-template <typename T, bool ALIGNED>
+template <typename T, bool ALIGNED, bool FT>
 __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a)
 {
     using M = Mma<T>;
@@ -58,6 +71,8 @@ __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a
     constexpr int PT = Cfg::PT, KT = Cfg::KT, KC = KT * TM;
 
     extern __shared__ __align__(16) unsigned char lds_raw[];
+    __shared__ int sh_nf;
+    __shared__ ftk_fault sh_faults[GENERIC_MAX_FAULTS];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -80,11 +95,32 @@ __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a
 
     Top3<T> best[PT];
     T xn[PT];
+    bool force_refine[PT];  // a chunk of this point failed checksum correction
 #pragma unroll
     for (int pt = 0; pt < PT; ++pt) {
         best[pt].m1 = best[pt].m2 = best[pt].m3 = M::neg_inf();
         best[pt].i1 = best[pt].i2 = 0;
         xn[pt] = T(0);
+        force_refine[pt] = false;
+    }
+    const T cmax2 = (T)a.scal[0];
+    const T cmax = sqrt(cmax2);
+    int n_checked = 0, n_injected = 0, n_detected = 0, n_corrected = 0, n_recomputed = 0;
+    float worst_resid = 0.f;
+
+    // faults aimed at this workgroup
+    int nf = 0;
+    if (a.n_faults > 0) {
+        if (tid == 0) sh_nf = 0;
+        __syncthreads();
+        for (int i = tid; i < a.n_faults; i += 256) {
+            if (a.faults[i].workgroup == blockIdx.x) {
+                const int slot = atomicAdd(&sh_nf, 1);
+                if (slot < GENERIC_MAX_FAULTS) sh_faults[slot] = a.faults[i];
+            }
+        }
+        __syncthreads();
+        nf = min(sh_nf, GENERIC_MAX_FAULTS);
     }
 
     // quad 0 of this wave's points; afterwards every quad is prefetched one step ahead and the
@@ -105,6 +141,9 @@ __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a
                 for (int pt = 0; pt < PT; ++pt) acc[pt][t][r] = -h;
             }
         }
+        T ref1[PT];  // x . (sum of the chunk's centroids), this lane's share of the features
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt) ref1[pt] = T(0);
 
         for (int dc = 0; dc < ndc; ++dc) {
             const int q0 = dc * a.DQ;
@@ -126,6 +165,11 @@ __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a
                     }
                     *reinterpret_cast<frag_t *>(lds_raw + rrow * SB + pc * 16) = f;
                 }
+                if (FT) {  // row KC: this stage's slice of the chunk's checksum row
+                    for (int pc = tid; pc < ppr; pc += 256)
+                        *reinterpret_cast<frag_t *>(lds_raw + KC * SB + pc * 16) =
+                            *reinterpret_cast<const frag_t *>(a.chk_v1 + (size_t)kc * a.D8 + q0 * 8 + pc * E);
+                }
             }
             __syncthreads();
 
@@ -144,6 +188,15 @@ __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a
 #pragma unroll
                         for (int e = 0; e < E; ++e) xn[pt] = fma(xcur[pt][e], xcur[pt][e], xn[pt]);
                 }
+                if (FT) {
+                    // operand checksum on the vector ALU (Section 4.2): x . v1 over this lane's features
+                    const frag_t v = *reinterpret_cast<const frag_t *>(
+                        lds_raw + KC * SB + q * (8 * (int)sizeof(T)) + g * 16);
+#pragma unroll
+                    for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+                        for (int e = 0; e < E; ++e) ref1[pt] = fma(xcur[pt][e], v[e], ref1[pt]);
+                }
 #pragma unroll
                 for (int t = 0; t < KT; ++t) {
                     const frag_t av = *reinterpret_cast<const frag_t *>(
@@ -156,6 +209,108 @@ __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a
                 }
 #pragma unroll
                 for (int pt = 0; pt < PT; ++pt) xcur[pt] = xnext[pt];
+            }
+        }
+
+        if (nf > 0) {  // fault injection (Section 2.1): flip one bit of one accumulator element
+            using bits_t = typename std::conditional<sizeof(T) == 4, unsigned, unsigned long long>::type;
+            for (int i = 0; i < nf; ++i) {
+                const ftk_fault f = sh_faults[i];
+                const int seq = (int)(f.tile % (unsigned)(a.nkc * PT * KT));
+                if ((int)(f.wave % Cfg::WAVES) != wave || seq / (PT * KT) != kc) continue;
+                const int fpt = (seq / KT) % PT, ft = seq % KT, fr = (int)(f.reg % R);
+                const bool me = lane == (int)(f.lane & 63);
+                const bits_t mask = (bits_t)1 << (f.bit % (8 * sizeof(T)));
+#pragma unroll
+                for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+                    for (int t = 0; t < KT; ++t)
+#pragma unroll
+                        for (int r = 0; r < R; ++r) {
+                            bits_t b;
+                            T v = acc[pt][t][r];
+                            __builtin_memcpy(&b, &v, sizeof(T));
+                            b ^= mask;
+                            T flipped;
+                            __builtin_memcpy(&flipped, &b, sizeof(T));
+                            acc[pt][t][r] = (me && pt == fpt && t == ft && r == fr) ? flipped : v;
+                        }
+                n_injected += me ? 1 : 0;
+            }
+        }
+
+        if constexpr (FT) {
+            // Verify the chunk before the arg-max reads it: for every point the KC scores must add
+            // up to x . v1 - sum ||c||^2/2 (carried through the same feature loop).  A mismatch is
+            // located with the weighted sum (weights 1..KC, Section 4.1) and corrected in place.
+            const T s1ref = a.chk_s[2 * kc];
+#pragma unroll
+            for (int pt = 0; pt < PT; ++pt) {
+                T s1 = T(0);
+#pragma unroll
+                for (int t = 0; t < KT; ++t)
+#pragma unroll
+                    for (int r = 0; r < R; ++r) s1 += acc[pt][t][r];
+                T rf = ref1[pt];
+                T xnp = xn[pt];
+#pragma unroll
+                for (int mask = TN; mask < 64; mask <<= 1) {
+                    s1 += shfl_xor_t(s1, mask);
+                    rf += shfl_xor_t(rf, mask);
+                    xnp += shfl_xor_t(xnp, mask);
+                }
+                // xn is complete after the first chunk; later chunks reuse the same lanes' sums
+                const T tau = (T)a.ft_coef * (sqrt(xnp) * cmax + (T)0.5 * cmax2);
+                const T resid = s1 - (rf - s1ref);
+                const bool bad = !(fabs(resid) <= tau);
+                n_checked += (g == 0) ? 1 : 0;
+                if (__builtin_expect(__any(bad), 0)) {
+                    n_detected += (bad && g == 0) ? 1 : 0;
+                    if (a.ft_mode == FTK_FT_CORRECT) {
+                        T s2 = T(0);
+#pragma unroll
+                        for (int t = 0; t < KT; ++t)
+#pragma unroll
+                            for (int r = 0; r < R; ++r)
+                                s2 = fma((T)(t * TM + M::row(r, g) + 1), acc[pt][t][r], s2);
+                        // weighted reference on demand: x . v2 over this lane's features
+                        T r2 = T(0);
+                        for (int qq = 0; qq < nq; ++qq) {
+                            const frag_t xv = load_frag<T, ALIGNED>(xrow[pt], qq * 8 + E * g, D);
+                            const frag_t vv = *reinterpret_cast<const frag_t *>(a.chk_v2 + (size_t)kc * a.D8 + qq * 8 + E * g);
+#pragma unroll
+                            for (int e = 0; e < E; ++e) r2 = fma(xv[e], vv[e], r2);
+                        }
+#pragma unroll
+                        for (int mask = TN; mask < 64; mask <<= 1) {
+                            s2 += shfl_xor_t(s2, mask);
+                            r2 += shfl_xor_t(r2, mask);
+                        }
+                        r2 -= a.chk_s[2 * kc + 1];
+                        const T fpos = (s2 - r2) / resid;
+                        const T rpos = rint(fpos);
+                        const bool finite = fabs(resid) < M::huge();
+                        bool ok = bad && finite && fabs(fpos - rpos) < (T)0.25 && rpos >= (T)1 && rpos <= (T)KC;
+                        const int wfix = ok ? (int)rpos : -1;
+#pragma unroll
+                        for (int t = 0; t < KT; ++t)
+#pragma unroll
+                            for (int r = 0; r < R; ++r)
+                                acc[pt][t][r] = (t * TM + M::row(r, g) + 1 == wfix) ? acc[pt][t][r] - resid : acc[pt][t][r];
+                        T s1b = T(0);
+#pragma unroll
+                        for (int t = 0; t < KT; ++t)
+#pragma unroll
+                            for (int r = 0; r < R; ++r) s1b += acc[pt][t][r];
+#pragma unroll
+                        for (int mask = TN; mask < 64; mask <<= 1) s1b += shfl_xor_t(s1b, mask);
+                        ok = ok && (fabs(s1b - (rf - s1ref)) <= tau);
+                        n_corrected += (ok && g == 0) ? 1 : 0;
+                        n_recomputed += (bad && !ok && g == 0) ? 1 : 0;
+                        force_refine[pt] = force_refine[pt] || (bad && !ok);
+                    }
+                }
+                worst_resid = fmaxf(worst_resid, bad ? 0.f : (float)(fabs(resid) / tau));
             }
         }
 
@@ -184,8 +339,6 @@ __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a
     }
 
     // combine the lane groups that share a point
-    const T cmax2 = (T)a.scal[0];
-    const T cmax = sqrt(cmax2);
     uint64_t n_refined = 0;
 #pragma unroll
     for (int pt = 0; pt < PT; ++pt) {
@@ -206,9 +359,11 @@ __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a
         // indices are made symmetric by ordering the pair.
         const int64_t p = p0 + pt * TN + col;
         const bool live = p < a.N;
-        const T bound = (T)a.band_coef * (sqrt(xn[pt]) * cmax + (T)0.5 * cmax2);
+        // scores inside `bound` of each other cannot be ordered: rounding of the expanded form,
+        // plus (FT on) an undetected error below the detection threshold
+        const T bound = (T)(a.band_coef + (FT ? a.ft_coef : 0.0)) * (sqrt(xn[pt]) * cmax + (T)0.5 * cmax2);
         const bool amb2 = (m1 - m2) <= bound;
-        const bool amb3 = (m1 - m3) <= bound;
+        const bool amb3 = ((m1 - m3) <= bound) || force_refine[pt];
         int label = i1;
         T dist = xn[pt] - (T)2 * m1;
         dist = dist > T(0) ? dist : T(0);
@@ -230,6 +385,21 @@ __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a
         if (live && g == 0) {
             a.labels[p] = label;
             if (a.mindist) a.mindist[p] = dist;
+        }
+    }
+    if (a.stats && (FT || a.n_faults > 0)) {
+        int v[5] = {n_checked, n_injected, n_detected, n_corrected, n_recomputed};
+#pragma unroll
+        for (int i = 0; i < 5; ++i)
+#pragma unroll
+            for (int mask = 1; mask < 64; mask <<= 1) v[i] += __shfl_xor(v[i], mask, 64);
+#pragma unroll
+        for (int mask = 1; mask < 64; mask <<= 1) worst_resid = fmaxf(worst_resid, __shfl_xor(worst_resid, mask, 64));
+        if (lane == 0) {
+            unsigned long long *sp = reinterpret_cast<unsigned long long *>(a.stats);
+            for (int i = 0; i < 5; ++i)
+                if (v[i]) atomicAdd(sp + i, (unsigned long long)v[i]);
+            if (FT) atomicMax(sp + 7, (unsigned long long)(fminf(worst_resid, 4000.f) * 1.0e6f));
         }
     }
     if (a.stats) {
@@ -317,12 +487,30 @@ static ftk_status launch_generic_t(const AssignCall &c, const AssignPlan &p, con
     // |fl(s) - s| <= gamma * (|x|.|c| + |c|^2/2) with gamma = (D+4) * 2u (matrix-core products and
     // accumulation each rounded once, factor two of slack); two scores -> twice that.
     a.band_coef = 4.0 * (c.D + 4) * Mma<T>::kEps;
+    a.chk_v1 = (const T *)w.chk_v1;
+    a.chk_v2 = (const T *)w.chk_v2;
+    a.chk_s = (const T *)w.chk_s;
+    a.faults = c.faults;
+    a.n_faults = c.n_faults;
+    a.ft_mode = (int)c.ft;
+    // Residual "KC scores minus carried checksum" of a fault-free chunk is rounding noise: about
+    // u B n (sqrt(n) + sqrt(D)) for n = KC terms of magnitude up to B (vector sum, checksum
+    // product of magnitude n B, and the scores themselves); factor GENERIC_FT_KAPPA on top.
+    {
+        const double n = (double)p.KC;
+        a.ft_coef = GENERIC_FT_KAPPA * Mma<T>::kEps * n * (std::sqrt(n) + std::sqrt((double)c.D + 4.0));
+    }
     const bool aligned = (c.D % Mma<T>::E == 0) && ((uintptr_t)c.X % 16 == 0) && ((uintptr_t)c.C % 16 == 0);
+    const bool ft = c.ft != FTK_FT_OFF;
     dim3 grid((unsigned)p.workgroups), block(256);
-    if (aligned)
-        hipLaunchKernelGGL((assign_generic_kernel<T, true>), grid, block, p.lds_bytes, st, a);
+    if (aligned && ft)
+        hipLaunchKernelGGL((assign_generic_kernel<T, true, true>), grid, block, p.lds_bytes, st, a);
+    else if (aligned)
+        hipLaunchKernelGGL((assign_generic_kernel<T, true, false>), grid, block, p.lds_bytes, st, a);
+    else if (ft)
+        hipLaunchKernelGGL((assign_generic_kernel<T, false, true>), grid, block, p.lds_bytes, st, a);
     else
-        hipLaunchKernelGGL((assign_generic_kernel<T, false>), grid, block, p.lds_bytes, st, a);
+        hipLaunchKernelGGL((assign_generic_kernel<T, false, false>), grid, block, p.lds_bytes, st, a);
     FTK_TRY_HIP(hipGetLastError());
     return FTK_OK;
 }

@@ -49,6 +49,7 @@ struct Mma<float> {
         return __builtin_amdgcn_fmed3f(a, b, c);
     }
     static __device__ __forceinline__ float neg_inf() { return -__builtin_huge_valf(); }
+    static __device__ __forceinline__ float huge() { return __builtin_huge_valf(); }
 };
 
 template <>
@@ -72,6 +73,7 @@ struct Mma<double> {
         return fmax(b, fmin(a, c));
     }
     static __device__ __forceinline__ double neg_inf() { return -__builtin_huge_val(); }
+    static __device__ __forceinline__ double huge() { return __builtin_huge_val(); }
 };
 
 // E consecutive elements of a row starting at feature d0, zero beyond D.

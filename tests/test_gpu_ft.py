@@ -16,6 +16,10 @@ SHAPES = [
     ("small-D resident", 40000, 8, 1000, "f32"),
     ("small-D streamed", 30000, 32, 1500, "f32"),
     ("small-D ragged", 5000, 12, 77, "f32"),
+    ("generic f32", 6000, 128, 256, "f32"),
+    ("generic f32 unaligned", 2000, 33, 130, "f32"),
+    ("generic f64", 3000, 64, 100, "f64"),
+    ("generic f64 large D", 1500, 512, 64, "f64"),
 ]
 
 
