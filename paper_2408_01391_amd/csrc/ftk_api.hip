@@ -75,8 +75,11 @@ Workspace carve_workspace(void *base, ftk_dtype dtype, int64_t N, int D, int K, 
     w.chk_s = take(ntiles * 2 * esz);
     w.wl_count = (int32_t *)take(4 * sizeof(int32_t));
     w.wl = (int32_t *)take((size_t)N * sizeof(int32_t));
-    w.fx_sums = (int64_t *)take((size_t)K * D * sizeof(int64_t));
+    w.fx_sums = (int64_t *)take((size_t)K * D * 2 * sizeof(int64_t));  // two limbs per cell
     w.absmax = (double *)take(2 * sizeof(double));
+    w.sort_idx = (int32_t *)take((size_t)N * sizeof(int32_t));
+    w.sort_lab = (int32_t *)take((size_t)N * sizeof(int32_t));
+    w.sort_cursor = (int32_t *)take(((size_t)K + 1) * sizeof(int32_t));
     w.C_cur = take((size_t)K * D * esz);
     w.mindist = take((size_t)N * esz);
     w.inertia = (double *)take(FIT_MAX_ITERS_IN_WS * sizeof(double));

@@ -27,7 +27,6 @@
 // the tile.  If the location does not decode, the point is handed to the refine kernel, which
 // recomputes it without the matrix path.
 #include <cmath>
-#include <cstdlib>
 #include <type_traits>
 
 #include "ftk_internal.h"
@@ -60,7 +59,6 @@ struct SmallArgs {
     int n_faults;
     int ft_mode;
     double ft_coef;       // detection threshold = ft_coef * (||x|| max||c|| + max||c||^2/2)
-    int dbg;
 };
 
 __device__ __forceinline__ float max3f(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
@@ -306,7 +304,7 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
                     }
                 }
 
-                if (FT && !(a.dbg & 1)) {
+                if constexpr (FT) {
                     // verify: the 15 scores of this lane must add up to the carried checksum
                     float s1 = acc[0];
 #pragma unroll
@@ -428,7 +426,7 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
             // scores inside `bound` of each other cannot be ordered: rounding of the expanded
             // form, plus (FT on) an undetected error below the detection threshold
             float bound = (float)a.band_coef * (sqrtf(xn[pt]) * cmax + 0.5f * cmax2);
-            if (FT && !(a.dbg & 2)) bound += tau[pt];
+            if (FT) bound += tau[pt];
             const float om1 = __shfl_xor(best[pt].m1, 32, 64), om2 = __shfl_xor(best[pt].m2, 32, 64);
             const int ot1 = __shfl_xor(best[pt].t1, 32, 64);
             const bool mine_wins = best[pt].m1 > om1 || (best[pt].m1 == om1 && g == 0);
@@ -638,7 +636,6 @@ ftk_status launch_assign_smalld(const AssignCall &c, const AssignPlan &p, const 
     a.n_faults = c.n_faults;
     a.ft_mode = (int)c.ft;
     a.ft_coef = smalld_ft_coef(c.D);
-    a.dbg = getenv("FTK_DBG") ? atoi(getenv("FTK_DBG")) : 0;
     switch (p.D8 / 8) {
     case 1: launch_smalld_t<1>(a, p, FT, st); break;
     case 2: launch_smalld_t<2>(a, p, FT, st); break;

@@ -67,6 +67,9 @@ struct Workspace {
     // update
     int64_t *fx_sums;   // [K*D] fixed-point sums
     double *absmax;     // [2]
+    int32_t *sort_idx;  // [N]   point indices grouped by label
+    int32_t *sort_lab;  // [N]   their labels
+    int32_t *sort_cursor;  // [K] bucket cursors
     // fit
     void *C_cur;        // [K*D] running centroids (dtype)
     void *mindist;      // [N]   (dtype)

@@ -3,10 +3,13 @@
 // The paper's kernel (Section 3.1.2) has every thread add its point into the global sums with
 // floating-point atomics, whose result depends on the order in which the adds land.  Here the
 // sums are accumulated in 64-bit FIXED POINT: every coordinate is scaled by a power of two
-// fixed from max|x| and N so that no sum can overflow, rounded once to an integer, and added
-// with integer atomics.  Integer addition is associative, so the sums - and the centroids -
-// are bitwise identical from run to run whatever the schedule, and the only rounding is the
-// one quantisation per coordinate (<= 2^-(62 - ceil(log2 N)) relative to max|x|).
+// fixed from max|x| and the number of points a workgroup handles so that no workgroup sum can
+// overflow, rounded once to an integer, and added with integer atomics.  Integer addition is
+// associative, so the sums - and the centroids - are bitwise identical from run to run
+// whatever the schedule, and the only rounding is the one quantisation per coordinate
+// (<= 2^-(62 - ceil(log2 rows_per_workgroup)) relative to max|x|, below 2^-45 for the
+// workloads here).  Workgroup sums are flushed into a two-limb global accumulator (high part
+// and low 24 bits separately), so the global sum cannot overflow either.
 //
 // Accumulation is privatised in LDS: a workgroup owns a block of points and a [Ks x Ds] slice
 // of the sum matrix that fits 64 KB, adds into it with LDS atomics, and flushes the non-zero
@@ -68,13 +71,25 @@ __global__ void update_zero_kernel(unsigned long long *sums, int64_t n, int32_t 
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < K; i += stride) counts[i] = 0;
 }
 
-// scale = 2^(62 - ceil(log2 N) - (ilogb(absmax) + 1)): N * max|x| * scale <= 2^62
-__device__ __forceinline__ double fixed_point_scale(double absmax, int64_t N)
+constexpr int UPD_LIMB_BITS = 24;
+
+// scale = 2^(62 - ceil(log2 rows) - (ilogb(absmax) + 1)): rows * max|x| * scale <= 2^62.
+// rows is taken as at least 2048, which keeps every scaled coordinate below 2^51 so that the
+// conversion below is valid.
+__device__ __forceinline__ double fixed_point_scale(double absmax, int64_t rows)
 {
-    int L = 0;
-    while (((int64_t)1 << L) < N) ++L;
+    int L = 11;
+    while (((int64_t)1 << L) < rows) ++L;
     if (!(absmax > 0.0) || !(absmax < __builtin_huge_val())) return 1.0;
     return ldexp(1.0, 62 - L - (ilogb(absmax) + 1));
+}
+
+// round(x * scale) as a 64-bit integer, for |x * scale| < 2^51: adding 1.5 * 2^52 in one fused
+// operation leaves the rounded integer in the low mantissa bits (one rounding, to nearest even).
+__device__ __forceinline__ long long to_fixed(double x, double scale)
+{
+    constexpr double MAGIC = 6755399441055744.0;  // 1.5 * 2^52
+    return __double_as_longlong(fma(x, scale, MAGIC)) - __double_as_longlong(MAGIC);
 }
 
 template <typename T, bool ALIGNED>
@@ -99,38 +114,77 @@ __global__ __launch_bounds__(256) void update_accumulate_kernel(
     for (int i = tid; i < Ks; i += 256) cnt[i] = 0;
     __syncthreads();
 
-    const double scale = fixed_point_scale(*absmax_p, N);
+    // fp32 data: 24-bit mantissas leave ample room, one limb scaled for the whole of N;
+    // fp64 data: scale for this workgroup's rows only and flush into two limbs
+    constexpr bool TWO_LIMB = sizeof(T) == 8;
+    const double scale = fixed_point_scale(*absmax_p, TWO_LIMB ? rows_per_chunk : N);
     const int TX = 1 << tx_log2, TY = 256 >> tx_log2;
     const int tx = tid & (TX - 1), ty = tid >> tx_log2;
     const int ppr = (dn + E - 1) / E;
     const int64_t r0 = (int64_t)blockIdx.x * rows_per_chunk;
     const int64_t r1 = r0 + rows_per_chunk < N ? r0 + rows_per_chunk : N;
 
-    for (int64_t row = r0 + ty; row < r1; row += TY) {
-        const int lab = labels[row] - k0;
-        if ((unsigned)lab >= (unsigned)kn) continue;
-        if (tx == 0 && ds_i == 0) atomicAdd(&cnt[lab], 1);
-        const T *xr = X + row * D + d0;
-        unsigned long long *dst = cell + (size_t)lab * Ds;
+    // UNR rows per thread and step: the label loads, then the point loads, are issued together
+    // before any LDS atomic, so several HBM requests per thread are in flight
+    constexpr int UNR = 4;
+    for (int64_t row0 = r0 + ty; row0 < r1; row0 += (int64_t)TY * UNR) {
+        int lab[UNR];
+        bool ok[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int64_t row = row0 + (int64_t)u * TY;
+            lab[u] = row < r1 ? labels[row] - k0 : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            ok[u] = (unsigned)lab[u] < (unsigned)kn;
+            if (ok[u] && tx == 0 && ds_i == 0) atomicAdd(&cnt[lab[u]], 1);
+        }
         for (int pc = tx; pc < ppr; pc += TX) {
             if constexpr (ALIGNED) {
-                const F f = *reinterpret_cast<const F *>(xr + pc * E);
+                F f[UNR];
 #pragma unroll
-                for (int e = 0; e < E; ++e) {
-                    const long long q = __double2ll_rn((double)f[e] * scale);
-                    atomicAdd(dst + pc * E + e, (unsigned long long)q);
+                for (int u = 0; u < UNR; ++u) {
+                    const int64_t row = row0 + (int64_t)u * TY;
+                    if (ok[u]) f[u] = *reinterpret_cast<const F *>(X + row * D + d0 + pc * E);
+                }
+#pragma unroll
+                for (int u = 0; u < UNR; ++u) {
+                    if (ok[u]) {
+                        unsigned long long *dst = cell + (size_t)lab[u] * Ds + pc * E;
+#pragma unroll
+                        for (int e = 0; e < E; ++e)
+                            atomicAdd(dst + e, (unsigned long long)to_fixed((double)f[u][e], scale));
+                    }
                 }
             } else {
-                const long long q = __double2ll_rn((double)xr[pc] * scale);
-                atomicAdd(dst + pc, (unsigned long long)q);
+                T v[UNR];
+#pragma unroll
+                for (int u = 0; u < UNR; ++u) {
+                    const int64_t row = row0 + (int64_t)u * TY;
+                    if (ok[u]) v[u] = X[row * D + d0 + pc];
+                }
+#pragma unroll
+                for (int u = 0; u < UNR; ++u)
+                    if (ok[u])
+                        atomicAdd(cell + (size_t)lab[u] * Ds + pc,
+                                  (unsigned long long)to_fixed((double)v[u], scale));
             }
         }
     }
     __syncthreads();
     for (int i = tid; i < kn * Ds; i += 256) {
         const int k = i / Ds, d = i - k * Ds;
-        const unsigned long long v = cell[i];
-        if (v != 0ull && d < dn) atomicAdd(sums + (int64_t)(k0 + k) * D + d0 + d, v);
+        const long long v = (long long)cell[i];
+        if (v != 0ll && d < dn) {
+            unsigned long long *dst = sums + 2 * ((int64_t)(k0 + k) * D + d0 + d);
+            if (TWO_LIMB) {
+                atomicAdd(dst, (unsigned long long)(v >> UPD_LIMB_BITS));                      // high limb (floor)
+                atomicAdd(dst + 1, (unsigned long long)(v & ((1ll << UPD_LIMB_BITS) - 1)));   // low limb >= 0
+            } else {
+                atomicAdd(dst + 1, (unsigned long long)v);
+            }
+        }
     }
     if (ds_i == 0)
         for (int i = tid; i < kn; i += 256)
@@ -141,16 +195,219 @@ __global__ __launch_bounds__(256) void update_accumulate_kernel(
 // a cluster without points keeps its previous centroid.
 template <typename T>
 __global__ __launch_bounds__(256) void update_finalize_kernel(const unsigned long long *sums,
-                                                              const int32_t *counts, int64_t N, int D,
-                                                              int K, const double *absmax_p, T *C)
+                                                              const int32_t *counts, int64_t N,
+                                                              int64_t rows_per_chunk, int D, int K,
+                                                              const double *absmax_p, T *C)
 {
-    const double inv = 1.0 / fixed_point_scale(*absmax_p, N);
+    const double inv = 1.0 / fixed_point_scale(*absmax_p, sizeof(T) == 8 ? rows_per_chunk : N);
     const int64_t n = (int64_t)K * D;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
         const int c = counts[i / D];
-        if (c > 0) C[i] = (T)(((double)(long long)sums[i] * inv) / (double)c);
+        if (c > 0) {
+            const double total = (double)(long long)sums[2 * i] * (double)(1ll << UPD_LIMB_BITS) +
+                                 (double)(long long)sums[2 * i + 1];
+            C[i] = (T)((total * inv) / (double)c);
+        }
     }
+}
+
+// ======================= label-sorted path (rows of at least one cache line) =================
+// Points are first bucketed by label (counting sort: histogram, scan, scatter); the reduction
+// then walks the sorted order, where a lane sees long runs of one label and can keep the
+// running sum of its features in registers, touching memory only when the label changes.
+// No LDS and no atomics in the inner loop; the order inside a bucket is whatever the scatter
+// produced, which is irrelevant because fixed-point sums do not depend on it.
+
+constexpr int SORT_CHUNK = 4096;       // points per workgroup in histogram / scatter
+constexpr int SORT_PER_THREAD = SORT_CHUNK / 256;
+constexpr int SORT_MAX_K_LDS = 8192;   // clusters whose per-workgroup histogram fits LDS
+
+// counts[k] += number of points of this chunk with label k  (counts zeroed beforehand)
+__global__ __launch_bounds__(256) void sort_hist_kernel(const int32_t *labels, int64_t N, int K, int32_t *counts)
+{
+    extern __shared__ int lh[];
+    const bool use_lds = K <= SORT_MAX_K_LDS;
+    if (use_lds) {
+        for (int k = threadIdx.x; k < K; k += 256) lh[k] = 0;
+        __syncthreads();
+    }
+    const int64_t base = (int64_t)blockIdx.x * SORT_CHUNK;
+#pragma unroll 4
+    for (int i = 0; i < SORT_PER_THREAD; ++i) {
+        const int64_t p = base + i * 256 + threadIdx.x;
+        if (p < N) {
+            const int lab = labels[p];
+            if ((unsigned)lab < (unsigned)K) {
+                if (use_lds) atomicAdd(&lh[lab], 1);
+                else atomicAdd(&counts[lab], 1);
+            }
+        }
+    }
+    if (use_lds) {
+        __syncthreads();
+        for (int k = threadIdx.x; k < K; k += 256)
+            if (lh[k]) atomicAdd(&counts[k], lh[k]);
+    }
+}
+
+// cursor[k] = exclusive prefix sum of counts (one workgroup, fixed order)
+__global__ __launch_bounds__(1024) void sort_scan_kernel(const int32_t *counts, int K, int32_t *cursor)
+{
+    __shared__ int sh[1024];
+    __shared__ int carry;
+    if (threadIdx.x == 0) carry = 0;
+    __syncthreads();
+    for (int k0 = 0; k0 < K; k0 += 1024) {
+        const int k = k0 + threadIdx.x;
+        const int v = k < K ? counts[k] : 0;
+        sh[threadIdx.x] = v;
+        __syncthreads();
+        for (int off = 1; off < 1024; off <<= 1) {
+            const int t = threadIdx.x >= off ? sh[threadIdx.x - off] : 0;
+            __syncthreads();
+            sh[threadIdx.x] += t;
+            __syncthreads();
+        }
+        if (k < K) cursor[k] = carry + sh[threadIdx.x] - v;
+        __syncthreads();
+        if (threadIdx.x == 1023) carry += sh[1023];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) cursor[K] = carry;  // number of validly labelled points; not touched by the scatter
+}
+
+// sorted_idx / sorted_lab: point indices and labels grouped by label.  Each workgroup ranks its
+// points inside LDS, reserves one range per label with a single global atomic, then writes.
+__global__ __launch_bounds__(256) void sort_scatter_kernel(const int32_t *labels, int64_t N, int K, int32_t *cursor,
+                                                           int32_t *sorted_idx, int32_t *sorted_lab)
+{
+    extern __shared__ int lh[];  // [K] local counts, then reused as local bases
+    const bool use_lds = K <= SORT_MAX_K_LDS;
+    const int64_t base = (int64_t)blockIdx.x * SORT_CHUNK;
+    int lab[SORT_PER_THREAD], rank[SORT_PER_THREAD];
+    if (use_lds) {
+        for (int k = threadIdx.x; k < K; k += 256) lh[k] = 0;
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < SORT_PER_THREAD; ++i) {
+        const int64_t p = base + i * 256 + threadIdx.x;
+        lab[i] = -1;
+        rank[i] = 0;
+        if (p < N) {
+            const int l = labels[p];
+            if ((unsigned)l < (unsigned)K) {
+                lab[i] = l;
+                rank[i] = use_lds ? atomicAdd(&lh[l], 1) : atomicAdd(&cursor[l], 1);
+            }
+        }
+    }
+    if (use_lds) {
+        __syncthreads();
+        for (int k = threadIdx.x; k < K; k += 256) {
+            const int c = lh[k];
+            lh[k] = c ? atomicAdd(&cursor[k], c) : 0;
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < SORT_PER_THREAD; ++i) {
+        if (lab[i] >= 0) {
+            const int pos = (use_lds ? lh[lab[i]] : 0) + rank[i];
+            sorted_idx[pos] = (int32_t)(base + i * 256 + threadIdx.x);
+            sorted_lab[pos] = lab[i];
+        }
+    }
+}
+
+constexpr int RED_ROWS_PER_LANE_MAX = 256;  // most sorted positions a lane walks (stride = groups per wave)
+
+// Walk the sorted order.  lpr_log2: lanes per row (power of two); a wave holds 64/lpr row groups;
+// blockIdx.y selects the slice of 64*E features when a row is wider than one wave.
+template <typename T, bool ALIGNED>
+__global__ __launch_bounds__(256) void sorted_reduce_kernel(const T *X, const int32_t *sorted_idx,
+                                                            const int32_t *sorted_lab, const int32_t *n_sorted_p,
+                                                            int64_t N, int D, int lpr_log2, int rows_per_lane,
+                                                            const double *absmax_p, unsigned long long *sums)
+{
+    using F = typename Mma<T>::frag_t;
+    constexpr int E = ALIGNED ? Mma<T>::E : 1;
+    constexpr bool TWO_LIMB = sizeof(T) == 8;
+    constexpr int UNR = 8;
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int lpr = 1 << lpr_log2, gpw = 64 >> lpr_log2;
+    const int group = lane >> lpr_log2, piece = lane & (lpr - 1);
+    const int d0 = (blockIdx.y * 64 + piece) * E;  // first feature of this lane
+    const bool lane_on = d0 < D;
+    const double scale = fixed_point_scale(*absmax_p, TWO_LIMB ? RED_ROWS_PER_LANE_MAX : N);
+    const int64_t s_begin = wave * (int64_t)(gpw * rows_per_lane) + group;
+    const int64_t n_sorted = *n_sorted_p;
+    const int64_t s_end = min(n_sorted, (wave + 1) * (int64_t)(gpw * rows_per_lane));
+
+    long long acc[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) acc[e] = 0;
+    int cur = -1;
+    auto flush = [&]() {
+        if (cur >= 0 && lane_on) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                if (d0 + e < D && acc[e] != 0) {
+                    unsigned long long *dst = sums + 2 * ((int64_t)cur * D + d0 + e);
+                    if (TWO_LIMB) {
+                        atomicAdd(dst, (unsigned long long)(acc[e] >> UPD_LIMB_BITS));
+                        atomicAdd(dst + 1, (unsigned long long)(acc[e] & ((1ll << UPD_LIMB_BITS) - 1)));
+                    } else {
+                        atomicAdd(dst + 1, (unsigned long long)acc[e]);
+                    }
+                }
+                acc[e] = 0;
+            }
+        }
+    };
+    // software pipeline: the index / label pairs of the next batch are fetched while the point
+    // rows of the current batch are in flight
+    int lab_n[UNR];
+    int64_t row_n[UNR];
+    auto fetch_keys = [&](int64_t s0) {
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int64_t s = s0 + (int64_t)u * gpw;
+            const bool in = s < s_end;
+            lab_n[u] = in ? sorted_lab[s] : -1;
+            row_n[u] = in ? sorted_idx[s] : 0;
+        }
+    };
+    fetch_keys(s_begin);
+    for (int64_t s0 = s_begin; s0 < s_end; s0 += (int64_t)gpw * UNR) {
+        int lab[UNR];
+        F f[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            lab[u] = lab_n[u];
+            if (lab[u] >= 0 && lane_on) {
+                if constexpr (ALIGNED) f[u] = *reinterpret_cast<const F *>(X + row_n[u] * D + d0);
+                else f[u][0] = X[row_n[u] * D + d0];
+            }
+        }
+        fetch_keys(s0 + (int64_t)gpw * UNR);
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            if (lab[u] >= 0) {
+                if (lab[u] != cur) {
+                    flush();
+                    cur = lab[u];
+                }
+                if (lane_on) {
+#pragma unroll
+                    for (int e = 0; e < E; ++e) acc[e] += to_fixed((double)f[u][e], scale);
+                }
+            }
+        }
+    }
+    flush();
 }
 
 ftk_status launch_update(ftk_dtype dtype, const void *X, const int32_t *labels, int64_t N, int D,
@@ -162,8 +419,41 @@ ftk_status launch_update(ftk_dtype dtype, const void *X, const int32_t *labels, 
     unsigned long long *sums = reinterpret_cast<unsigned long long *>(w.fx_sums);
     {
         const int blocks = (int)(ceil_div(cells, 256) < 1024 ? ceil_div(cells, 256) : 1024);
-        hipLaunchKernelGGL(update_zero_kernel, dim3(blocks), dim3(256), 0, st, sums, cells, counts, K);
+        hipLaunchKernelGGL(update_zero_kernel, dim3(blocks), dim3(256), 0, st, sums, 2 * cells, counts, K);
     }
+    const size_t esz = dtype == FTK_F32 ? 4 : 8;
+    const bool sorted_path = (size_t)D * esz >= 64;   // rows of at least half a cache line: gather is efficient
+    if (sorted_path) {
+        const int chunks = (int)ceil_div(N, SORT_CHUNK);
+        const size_t hl = K <= SORT_MAX_K_LDS ? (size_t)K * 4 : 0;
+        hipLaunchKernelGGL(sort_hist_kernel, dim3(chunks), dim3(256), hl, st, labels, N, K, counts);
+        hipLaunchKernelGGL(sort_scan_kernel, dim3(1), dim3(1024), 0, st, counts, K, w.sort_cursor);
+        hipLaunchKernelGGL(sort_scatter_kernel, dim3(chunks), dim3(256), hl, st, labels, N, K, w.sort_cursor,
+                           w.sort_idx, w.sort_lab);
+        const int E = u.aligned ? (dtype == FTK_F32 ? 4 : 2) : 1;
+        const int pieces = (int)ceil_div(D, E);
+        int lpr_log2 = 0;
+        while ((1 << lpr_log2) < pieces && lpr_log2 < 6) ++lpr_log2;
+        const int gpw = 64 >> lpr_log2;
+        // long runs per lane (few flushes), but at least ~2048 waves where N allows
+        int64_t rpl = N / ((int64_t)gpw * 2048);
+        if (rpl < 64) rpl = 64;
+        if (rpl > RED_ROWS_PER_LANE_MAX) rpl = RED_ROWS_PER_LANE_MAX;
+        const int rows_per_lane = (int)rpl;
+        const int64_t waves = ceil_div(N, (int64_t)gpw * rows_per_lane);
+        dim3 rgrid((unsigned)ceil_div(waves, 4), (unsigned)ceil_div(pieces, 64)), rblock(256);
+#define FTK_LAUNCH_RED(T, AL)                                                                       \
+    hipLaunchKernelGGL((sorted_reduce_kernel<T, AL>), rgrid, rblock, 0, st, (const T *)X, w.sort_idx, \
+                       w.sort_lab, w.sort_cursor + K, N, D, lpr_log2, rows_per_lane, absmax, sums)
+        if (dtype == FTK_F32) {
+            if (u.aligned) FTK_LAUNCH_RED(float, true);
+            else FTK_LAUNCH_RED(float, false);
+        } else {
+            if (u.aligned) FTK_LAUNCH_RED(double, true);
+            else FTK_LAUNCH_RED(double, false);
+        }
+#undef FTK_LAUNCH_RED
+    } else {
     const size_t lds = (size_t)u.Ks * u.Ds * 8 + (size_t)u.Ks * 4;
     dim3 grid(u.chunks, u.nds * u.nks), block(256);
 #define FTK_LAUNCH_ACC(T, AL)                                                                      \
@@ -177,14 +467,16 @@ ftk_status launch_update(ftk_dtype dtype, const void *X, const int32_t *labels, 
         else FTK_LAUNCH_ACC(double, false);
     }
 #undef FTK_LAUNCH_ACC
+    }
+    const int64_t fin_rows = sorted_path ? RED_ROWS_PER_LANE_MAX : u.rows_per_chunk;
     {
         const int blocks = (int)(ceil_div(cells, 256) < 1024 ? ceil_div(cells, 256) : 1024);
         if (dtype == FTK_F32)
             hipLaunchKernelGGL((update_finalize_kernel<float>), dim3(blocks), dim3(256), 0, st, sums,
-                               counts, N, D, K, absmax, (float *)C);
+                               counts, N, fin_rows, D, K, absmax, (float *)C);
         else
             hipLaunchKernelGGL((update_finalize_kernel<double>), dim3(blocks), dim3(256), 0, st, sums,
-                               counts, N, D, K, absmax, (double *)C);
+                               counts, N, fin_rows, D, K, absmax, (double *)C);
     }
     FTK_TRY_HIP(hipGetLastError());
     return FTK_OK;
