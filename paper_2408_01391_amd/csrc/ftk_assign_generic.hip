@@ -95,13 +95,14 @@ __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a
 
     Top3<T> best[PT];
     T xn[PT];
-    bool force_refine[PT];  // a chunk of this point failed checksum correction
+    int force_refine[PT];   // a chunk of this point failed checksum correction (int, not bool:
+                            // a bool array updated inside the rare branch lost its value when compiled)
 #pragma unroll
     for (int pt = 0; pt < PT; ++pt) {
         best[pt].m1 = best[pt].m2 = best[pt].m3 = M::neg_inf();
         best[pt].i1 = best[pt].i2 = 0;
         xn[pt] = T(0);
-        force_refine[pt] = false;
+        force_refine[pt] = 0;
     }
     const T cmax2 = (T)a.scal[0];
     const T cmax = sqrt(cmax2);
@@ -290,7 +291,11 @@ __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a
                         const T fpos = (s2 - r2) / resid;
                         const T rpos = rint(fpos);
                         const bool finite = fabs(resid) < M::huge();
-                        bool ok = bad && finite && fabs(fpos - rpos) < (T)0.25 && rpos >= (T)1 && rpos <= (T)KC;
+                        // the location is trusted only when the error stands far enough above the rounding
+                        // noise of the weighted sum (weights up to KC) for the quotient to be accurate to a
+                        // quarter; smaller detected errors are recomputed by the refine kernel instead
+                        bool ok = bad && finite && fabs(resid) >= (T)(2 * KC) * tau && fabs(fpos - rpos) < (T)0.25 &&
+                                  rpos >= (T)1 && rpos <= (T)KC;
                         const int wfix = ok ? (int)rpos : -1;
 #pragma unroll
                         for (int t = 0; t < KT; ++t)
@@ -307,7 +312,7 @@ __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a
                         ok = ok && (fabs(s1b - (rf - s1ref)) <= tau);
                         n_corrected += (ok && g == 0) ? 1 : 0;
                         n_recomputed += (bad && !ok && g == 0) ? 1 : 0;
-                        force_refine[pt] = force_refine[pt] || (bad && !ok);
+                        force_refine[pt] |= (bad && !ok) ? 1 : 0;
                     }
                 }
                 worst_resid = fmaxf(worst_resid, bad ? 0.f : (float)(fabs(resid) / tau));
@@ -363,7 +368,7 @@ __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a
         // plus (FT on) an undetected error below the detection threshold
         const T bound = (T)(a.band_coef + (FT ? a.ft_coef : 0.0)) * (sqrt(xn[pt]) * cmax + (T)0.5 * cmax2);
         const bool amb2 = (m1 - m2) <= bound;
-        const bool amb3 = ((m1 - m3) <= bound) || force_refine[pt];
+        const bool amb3 = ((m1 - m3) <= bound) || force_refine[pt] != 0;
         int label = i1;
         T dist = xn[pt] - (T)2 * m1;
         dist = dist > T(0) ? dist : T(0);

@@ -44,7 +44,7 @@ struct SmallArgs {
     int tpc;          // tiles staged in LDS at a time
     int nch;          // chunks
     int tiles_total;  // ceil(K / centroids-per-tile)
-    int nblocks;      // point blocks (SMALLD_WAVES*PT*32 points each)
+    int nblocks;      // point blocks (waves*PT*32 points each)
     int32_t *labels;
     float *mindist;
     int32_t *wl;
@@ -63,8 +63,9 @@ struct SmallArgs {
 
 __device__ __forceinline__ float max3f(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
 
-constexpr int SMALLD_WAVES = 8;  // waves per workgroup sharing one staged centroid chunk
-constexpr int SMALLD_THREADS = SMALLD_WAVES * 64;
+// waves per workgroup sharing one staged centroid chunk (measured: 8 beats 4 for every D <= 32,
+// even where the exact re-evaluation then spills a few registers)
+static constexpr int smalld_waves(int nq) { return nq <= 4 ? 8 : 4; }
 constexpr int SMALLD_MAX_FAULTS = 4;  // injected faults honoured per point block
 
 // Tile geometry: which centroid sits in register r of lane group g of tile T.
@@ -135,8 +136,10 @@ struct TileBest {
 };
 
 template <int NQ, int PT, bool FT>
-__global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs a)
+__global__ __launch_bounds__(smalld_waves(NQ) * 64) void assign_smalld_kernel(SmallArgs a)
 {
+    constexpr int SMALLD_WAVES = smalld_waves(NQ);
+    constexpr int SMALLD_THREADS = SMALLD_WAVES * 64;
     using M = Mma<float>;
     using G = TileGeom<FT>;
     constexpr int SW = 8 * NQ + 4;      // LDS row stride in floats (16 bytes of padding)
@@ -231,7 +234,8 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
         float xn[PT];
         float tau[PT];          // checksum detection threshold of this lane's point
         float inv_tau[PT];
-        bool force_refine[PT];  // a tile of this point failed correction
+        int force_refine[PT];   // a tile of this point failed correction (int, not bool: a bool
+                                // array updated inside the rare branch lost its value when compiled)
         TileBest best[PT];
 #pragma unroll
         for (int pt = 0; pt < PT; ++pt) {
@@ -248,7 +252,7 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
             xn[pt] = s + __shfl_xor(s, 32, 64);
             tau[pt] = (float)a.ft_coef * (sqrtf(xn[pt]) * cmax + 0.5f * cmax2);
             inv_tau[pt] = 1.0f / tau[pt];
-            force_refine[pt] = false;
+            force_refine[pt] = 0;
             best[pt].m1 = best[pt].m2 = M::neg_inf();
             best[pt].t1 = 0;
         }
@@ -340,7 +344,13 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
                             const float fpos = (s2 - ref2) / delta;
                             const float rpos = rintf(fpos);
                             const bool finite = (__float_as_uint(delta) & 0x7f800000u) != 0x7f800000u;
-                            bool ok = bad && finite && fabsf(fpos - rpos) < 0.25f && rpos >= 1.f && rpos <= (float)RG;
+                            // The location is only trusted when the error stands far enough above the
+                            // rounding noise of the weighted sum (weights up to 15) for the quotient to be
+                            // accurate to a quarter; smaller detected errors are recomputed instead.  (After
+                            // subtracting delta the plain checksum matches wherever it was subtracted, so a
+                            // wrong location would go unnoticed.)
+                            bool ok = bad && finite && fabsf(delta) >= 32.f * tau[pt] && fabsf(fpos - rpos) < 0.25f &&
+                                      rpos >= 1.f && rpos <= (float)RG;
                             const int rfix = ok ? (int)rpos - 1 : -1;
 #pragma unroll
                             for (int r = 0; r < RG; ++r) acc[r] = (r == rfix) ? acc[r] - delta : acc[r];
@@ -352,7 +362,7 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
                             // not decodable (error in the checksum register itself, several errors,
                             // Inf/NaN): the point is recomputed outside the matrix path
                             n_recomputed += (bad && !ok) ? 1 : 0;
-                            force_refine[pt] = force_refine[pt] || (bad && !ok);
+                            force_refine[pt] |= (bad && !ok) ? 1 : 0;
                         }
                     }
                     worst_resid = fmaxf(worst_resid, bad ? 0.f : fabsf(resid) * inv_tau[pt]);
@@ -439,7 +449,7 @@ __global__ __launch_bounds__(SMALLD_THREADS) void assign_smalld_kernel(SmallArgs
             const int Ts = mine_wins ? ot1 : best[pt].t1;
             // a third candidate tile anywhere: left to the refine kernel
             const bool over = fmaxf(best[pt].m2, om2) >= thr;
-            const bool forced = force_refine[pt] || (__shfl_xor((int)force_refine[pt], 32, 64) != 0);
+            const bool forced = (force_refine[pt] | __shfl_xor(force_refine[pt], 32, 64)) != 0;
             float dbest = __builtin_huge_valf();
             int jbest = 0x7fffffff;
             if (resident) {
@@ -571,7 +581,7 @@ void plan_smalld(int64_t N, int D, int K, ftk_ft_mode ft, AssignPlan &p)
     p.D8 = (int)ceil_div(D, 8) * 8;
     p.PT = 2;
     p.KT = 1;
-    p.waves = SMALLD_WAVES;
+    p.waves = smalld_waves(p.D8 / 8);
     const int SW = p.D8 + 4;
     const int tile_bytes = (32 * SW + 4) * 4 + 32 * 4;
     const int tiles_total = (int)ceil_div(K, FT ? 30 : 32);
@@ -582,7 +592,7 @@ void plan_smalld(int64_t N, int D, int K, ftk_ft_mode ft, AssignPlan &p)
     p.KC = tpc * 32;
     p.nkc = (int)ceil_div(tiles_total, tpc);
     p.DQ = p.D8 / 8;
-    p.points_per_wg = SMALLD_WAVES * p.PT * 32;
+    p.points_per_wg = p.waves * p.PT * 32;
     p.workgroups = ceil_div(N, p.points_per_wg);
     p.lds_bytes = (size_t)tpc * tile_bytes;
     int resident_wgs = (int)(160 * 1024 / (p.lds_bytes + 2048));
@@ -599,9 +609,9 @@ template <int NQ>
 static void launch_smalld_t(const SmallArgs &a, const AssignPlan &p, bool ft, hipStream_t st)
 {
     if (ft)
-        hipLaunchKernelGGL((assign_smalld_kernel<NQ, 2, true>), dim3(p.grid), dim3(SMALLD_THREADS), p.lds_bytes, st, a);
+        hipLaunchKernelGGL((assign_smalld_kernel<NQ, 2, true>), dim3(p.grid), dim3(smalld_waves(NQ) * 64), p.lds_bytes, st, a);
     else
-        hipLaunchKernelGGL((assign_smalld_kernel<NQ, 2, false>), dim3(p.grid), dim3(SMALLD_THREADS), p.lds_bytes, st, a);
+        hipLaunchKernelGGL((assign_smalld_kernel<NQ, 2, false>), dim3(p.grid), dim3(smalld_waves(NQ) * 64), p.lds_bytes, st, a);
 }
 
 ftk_status launch_assign_smalld(const AssignCall &c, const AssignPlan &p, const Workspace &w, hipStream_t st)
