@@ -23,6 +23,10 @@ if ROOT not in sys.path:
 
 PEAK = {"f32": 157.3, "f64": 78.6}          # dense MFMA TFLOP/s, MI355X datasheet
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the assignment kernel (FT off), from two rocprofv3 --pmc runs
+# (FETCH_SIZE, WRITE_SIZE) scaled by the readings of a device copy of X in the same run;
+# the summaries and commands are in profiles/<workload>_assign_update.txt
+MEASURED_TRAFFIC_BYTES = {"c2": 43.0e6, "c3": 296.5e6, "c4": 5889.9e6, "c5": 3753.3e6}
 
 
 def parse():
@@ -153,7 +157,7 @@ def main():
             "peak": PEAK[w.dtype],
             "unit": "TFLOP/s",
             "frac": tflops / PEAK[w.dtype],
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
             "flops_per_launch": flops,
             "kernel_ms": primary["kernel_ms"],
             "hbm_gbs_algorithmic": algo_bytes / kern_s / 1e9,

@@ -422,7 +422,9 @@ ftk_status launch_update(ftk_dtype dtype, const void *X, const int32_t *labels, 
         hipLaunchKernelGGL(update_zero_kernel, dim3(blocks), dim3(256), 0, st, sums, 2 * cells, counts, K);
     }
     const size_t esz = dtype == FTK_F32 ? 4 : 8;
-    const bool sorted_path = (size_t)D * esz >= 64;   // rows of at least half a cache line: gather is efficient
+    // rows of at least half a cache line gather efficiently; small problems are launch bound and
+    // take the three-kernel LDS path instead of the six-kernel sorted one
+    const bool sorted_path = (size_t)D * esz >= 64 && N >= 65536;
     if (sorted_path) {
         const int chunks = (int)ceil_div(N, SORT_CHUNK);
         const size_t hl = K <= SORT_MAX_K_LDS ? (size_t)K * 4 : 0;
