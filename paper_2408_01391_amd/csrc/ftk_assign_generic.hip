@@ -28,7 +28,7 @@ struct GenericArgs {
     const T *hcn;        // half squared norms, padded with zeros to nkc*KC entries
     const double *scal;  // scal[0] = max_j ||c_j||^2
     int64_t N;
-    int D, K, D8, DQ, nkc;
+    int D, K, D8, nkc;
     int32_t *labels;
     T *mindist;  // may be null
     int32_t *wl;
@@ -53,11 +53,11 @@ template <typename T>
 struct GenericCfg;
 template <>
 struct GenericCfg<float> {
-    static constexpr int PT = 2, KT = 4, WAVES = 4, DQMAX = 8;
+    static constexpr int PT = 2, KT = 4, WAVES = 4, DQ = 2;
 };
 template <>
 struct GenericCfg<double> {
-    static constexpr int PT = 4, KT = 4, WAVES = 4, DQMAX = 8;
+    static constexpr int PT = 4, KT = 4, WAVES = 4, DQ = 2;
 };
 
 template <typename T, bool ALIGNED, bool FT>
@@ -80,8 +80,6 @@ __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a
     const int col = lane % TN;
     const int g = lane / TN;
     const int D = a.D;
-    const int SB = 8 * a.DQ * (int)sizeof(T) + 16;  // LDS row stride in bytes
-    const int ndc = (a.D8 / 8 + a.DQ - 1) / a.DQ;   // D-stages per K-chunk
     const int nq = a.D8 / 8;                        // quads in total
 
     const int64_t p0 = ((int64_t)blockIdx.x * Cfg::WAVES + wave) * (PT * TN);
@@ -93,14 +91,20 @@ __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a
         xrow[pt] = a.X + p * D;
     }
 
-    Top3<T> best[PT];
+    // Epilogue state per point tile: best tile maximum, runner-up maximum over the OTHER tiles and
+    // the best tile's number; the best tile's accumulators are parked in a per-lane LDS slot and the
+    // arg-max inside it is taken once, at the end.  About one vector op per score for the maximum
+    // instead of a full compare/select chain per score - fp32 matrix and vector work do not overlap
+    // here - and the slot costs no registers.
+    T bm1[PT], bm2[PT];
+    int bt[PT];  // -1: no tile has produced a comparable score yet
     T xn[PT];
     int force_refine[PT];   // a chunk of this point failed checksum correction (int, not bool:
                             // a bool array updated inside the rare branch lost its value when compiled)
 #pragma unroll
     for (int pt = 0; pt < PT; ++pt) {
-        best[pt].m1 = best[pt].m2 = best[pt].m3 = M::neg_inf();
-        best[pt].i1 = best[pt].i2 = 0;
+        bm1[pt] = bm2[pt] = M::neg_inf();
+        bt[pt] = -1;
         xn[pt] = T(0);
         force_refine[pt] = 0;
     }
@@ -124,22 +128,79 @@ __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a
         nf = min(sh_nf, GENERIC_MAX_FAULTS);
     }
 
+    // Centroid stages (DQ quads of one K-chunk, plus the chunk's checksum-row slice when FT is on)
+    // go through two LDS buffers: the global loads of stage s+1 are issued before the matrix work
+    // of stage s and land in LDS after it, so one barrier per stage is enough and the load latency
+    // is covered by the matrix instructions.  The chunk's half-norms ride along with its first stage.
+    constexpr int DQ = Cfg::DQ;
+    constexpr int PPR = DQ * 8 / E;                      // 16-byte pieces per staged row
+    constexpr int SB = DQ * 8 * (int)sizeof(T) + 16;     // row stride in bytes (bank spread)
+    constexpr int STAGE_BYTES = (KC + 1) * SB;
+    constexpr int NP = KC * PPR / 256;                   // pieces per thread per stage
+    static_assert(KC * PPR % 256 == 0, "stage must divide evenly over the workgroup");
+    static_assert(KC / E <= 64 && PPR <= 64, "extra pieces: half-norms on wave 0, checksum row on wave 1");
+    unsigned char *const lds_hcn = lds_raw + 2 * STAGE_BYTES;
+    // per-lane parking slots for the accumulators of the best tile so far ([pt][piece][thread])
+    constexpr int BV = R / E;
+    unsigned char *const lds_best = lds_hcn + 2 * KC * (int)sizeof(T);
+    const int ndc = (nq + DQ - 1) / DQ;  // stages per K-chunk
+
+    frag_t pf[NP], pfx;
+    auto fetch = [&](int kc, int dc) {
+        const int q0 = dc * DQ;
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const int idx = tid + 256 * i;
+            const int rrow = idx / PPR, pc = idx % PPR;
+            const int j = kc * KC + rrow;
+            const int d0 = q0 * 8 + pc * E;
+            pf[i] = frag_keep<T>(load_frag_clamped<T, ALIGNED>(a.C + (int64_t)min(j, a.K - 1) * D, d0, D),
+                                 d0, D, j < a.K);
+        }
+#pragma unroll
+        for (int e = 0; e < E; ++e) pfx[e] = T(0);
+        if (dc == 0 && tid < KC / E)  // half-norms of the chunk (padded with zeros to nkc*KC entries)
+            pfx = *reinterpret_cast<const frag_t *>(a.hcn + (size_t)kc * KC + tid * E);
+        if (FT && tid >= 64 && tid < 64 + PPR && (q0 * 8 + (tid - 64) * E) < a.D8)
+            pfx = *reinterpret_cast<const frag_t *>(a.chk_v1 + (size_t)kc * a.D8 + q0 * 8 + (tid - 64) * E);
+    };
+    auto commit = [&](int kc, int dc, int buf) {
+        unsigned char *const base = lds_raw + buf * STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const int idx = tid + 256 * i;
+            *reinterpret_cast<frag_t *>(base + (idx / PPR) * SB + (idx % PPR) * 16) = pf[i];
+        }
+        if (dc == 0 && tid < KC / E)
+            *reinterpret_cast<frag_t *>(lds_hcn + ((kc & 1) * KC + tid * E) * (int)sizeof(T)) = pfx;
+        if (FT && tid >= 64 && tid < 64 + PPR)
+            *reinterpret_cast<frag_t *>(base + KC * SB + (tid - 64) * 16) = pfx;
+    };
+
     // quad 0 of this wave's points; afterwards every quad is prefetched one step ahead and the
     // prefetch wraps to quad 0 at the end of a K-chunk
     frag_t xcur[PT];
 #pragma unroll
-    for (int pt = 0; pt < PT; ++pt) xcur[pt] = load_frag<T, ALIGNED>(xrow[pt], E * g, D);
+    for (int pt = 0; pt < PT; ++pt) xcur[pt] = load_frag_clamped<T, ALIGNED>(xrow[pt], E * g, D);
+
+    fetch(0, 0);
+    commit(0, 0, 0);
+    __syncthreads();
+    int buf = 0;
 
     for (int kc = 0; kc < a.nkc; ++kc) {
         const int jbase = kc * KC;
         acc_t acc[PT][KT];
+        {
+            const T *const hl = reinterpret_cast<const T *>(lds_hcn) + (kc & 1) * KC;
 #pragma unroll
-        for (int t = 0; t < KT; ++t) {
+            for (int t = 0; t < KT; ++t) {
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const T h = a.hcn[jbase + t * TM + M::row(r, g)];
+                for (int r = 0; r < R; ++r) {
+                    const T h = hl[t * TM + M::row(r, g)];
 #pragma unroll
-                for (int pt = 0; pt < PT; ++pt) acc[pt][t][r] = -h;
+                    for (int pt = 0; pt < PT; ++pt) acc[pt][t][r] = -h;
+                }
             }
         }
         T ref1[PT];  // x . (sum of the chunk's centroids), this lane's share of the features
@@ -147,70 +208,65 @@ __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a
         for (int pt = 0; pt < PT; ++pt) ref1[pt] = T(0);
 
         for (int dc = 0; dc < ndc; ++dc) {
-            const int q0 = dc * a.DQ;
-            const int dq = min(a.DQ, nq - q0);
-            __syncthreads();  // readers of the previous stage are done
-            // stage C[jbase .. jbase+KC) x [8*q0 .. 8*(q0+dq)) into LDS, zero beyond K / D
-            {
-                const int ppr = dq * 8 / E;  // 16-byte pieces per row
-                for (int idx = tid; idx < KC * ppr; idx += 256) {
-                    const int rrow = idx / ppr;
-                    const int pc = idx - rrow * ppr;
-                    const int j = jbase + rrow;
-                    frag_t f;
-                    if (j < a.K) {
-                        f = load_frag<T, ALIGNED>(a.C + (int64_t)j * D, q0 * 8 + pc * E, D);
-                    } else {
+            const int q0 = dc * DQ;
+            // next stage in sweep order (none after the last stage of the last chunk)
+            const bool chunk_end = dc + 1 == ndc;
+            const int kc_n = chunk_end ? kc + 1 : kc;
+            const int dc_n = chunk_end ? 0 : dc + 1;
+            const bool more = kc_n < a.nkc;
+            if (more) fetch(kc_n, dc_n);
+            const unsigned char *const sbuf = lds_raw + buf * STAGE_BYTES;
 #pragma unroll
-                        for (int e = 0; e < E; ++e) f[e] = T(0);
+            for (int q = 0; q < DQ; ++q) {
+                if (q0 + q < nq) {
+                    // prefetch the next quad of this wave's points (wraps to quad 0 at the end).
+                    // Features beyond D hold copies of valid ones: the staged centroid rows are zero
+                    // there, so they add nothing to the scores; the norm masks them explicitly.
+                    int qn = q0 + q + 1;
+                    if (qn >= nq) qn = 0;
+                    frag_t xnext[PT];
+#pragma unroll
+                    for (int pt = 0; pt < PT; ++pt)
+                        xnext[pt] = load_frag_clamped<T, ALIGNED>(xrow[pt], qn * 8 + E * g, D);
+
+                    if (kc == 0) {
+                        const int d0 = (q0 + q) * 8 + E * g;
+#pragma unroll
+                        for (int pt = 0; pt < PT; ++pt) {
+                            const frag_t xm = frag_keep<T>(xcur[pt], d0, D, true);
+#pragma unroll
+                            for (int e = 0; e < E; ++e) xn[pt] = fma(xm[e], xm[e], xn[pt]);
+                        }
                     }
-                    *reinterpret_cast<frag_t *>(lds_raw + rrow * SB + pc * 16) = f;
-                }
-                if (FT) {  // row KC: this stage's slice of the chunk's checksum row
-                    for (int pc = tid; pc < ppr; pc += 256)
-                        *reinterpret_cast<frag_t *>(lds_raw + KC * SB + pc * 16) =
-                            *reinterpret_cast<const frag_t *>(a.chk_v1 + (size_t)kc * a.D8 + q0 * 8 + pc * E);
-                }
-            }
-            __syncthreads();
-
-            for (int q = 0; q < dq; ++q) {
-                // prefetch the next quad of this wave's points (wraps to quad 0 at the end)
-                int qn = q0 + q + 1;
-                if (qn >= nq) qn = 0;
-                frag_t xnext[PT];
+                    if (FT) {
+                        // operand checksum on the vector ALU (Section 4.2): x . v1 over this lane's features
+                        const frag_t v = *reinterpret_cast<const frag_t *>(
+                            sbuf + KC * SB + q * (8 * (int)sizeof(T)) + g * 16);
 #pragma unroll
-                for (int pt = 0; pt < PT; ++pt)
-                    xnext[pt] = load_frag<T, ALIGNED>(xrow[pt], qn * 8 + E * g, D);
-
-                if (kc == 0) {
+                        for (int pt = 0; pt < PT; ++pt)
 #pragma unroll
-                    for (int pt = 0; pt < PT; ++pt)
+                            for (int e = 0; e < E; ++e) ref1[pt] = fma(xcur[pt][e], v[e], ref1[pt]);
+                    }
+                    frag_t av[KT];
 #pragma unroll
-                        for (int e = 0; e < E; ++e) xn[pt] = fma(xcur[pt][e], xcur[pt][e], xn[pt]);
-                }
-                if (FT) {
-                    // operand checksum on the vector ALU (Section 4.2): x . v1 over this lane's features
-                    const frag_t v = *reinterpret_cast<const frag_t *>(
-                        lds_raw + KC * SB + q * (8 * (int)sizeof(T)) + g * 16);
-#pragma unroll
-                    for (int pt = 0; pt < PT; ++pt)
-#pragma unroll
-                        for (int e = 0; e < E; ++e) ref1[pt] = fma(xcur[pt][e], v[e], ref1[pt]);
-                }
-#pragma unroll
-                for (int t = 0; t < KT; ++t) {
-                    const frag_t av = *reinterpret_cast<const frag_t *>(
-                        lds_raw + (t * TM + lane % TM) * SB + q * (8 * (int)sizeof(T)) + g * 16);
+                    for (int t = 0; t < KT; ++t)
+                        av[t] = *reinterpret_cast<const frag_t *>(
+                            sbuf + (t * TM + lane % TM) * SB + q * (8 * (int)sizeof(T)) + g * 16);
+                    // KT*PT independent accumulator chains interleave on the matrix pipe
 #pragma unroll
                     for (int e = 0; e < E; ++e)
 #pragma unroll
-                        for (int pt = 0; pt < PT; ++pt)
-                            acc[pt][t] = M::mma(av[e], xcur[pt][e], acc[pt][t]);
-                }
+                        for (int t = 0; t < KT; ++t)
 #pragma unroll
-                for (int pt = 0; pt < PT; ++pt) xcur[pt] = xnext[pt];
+                            for (int pt = 0; pt < PT; ++pt)
+                                acc[pt][t] = M::mma(av[t][e], xcur[pt][e], acc[pt][t]);
+#pragma unroll
+                    for (int pt = 0; pt < PT; ++pt) xcur[pt] = xnext[pt];
+                }
             }
+            if (more) commit(kc_n, dc_n, buf ^ 1);
+            __syncthreads();
+            buf ^= 1;
         }
 
         if (nf > 0) {  // fault injection (Section 2.1): flip one bit of one accumulator element
@@ -319,20 +375,35 @@ __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a
             }
         }
 
-        // fused epilogue: running top-3 over this chunk's scores (rows beyond K only exist in the
-        // last chunk; the two variants keep the common path free of the bounds select)
+        // fused epilogue (rows beyond K only exist in the last chunk; the two variants keep the
+        // common path free of the bounds select)
         auto epilogue = [&](auto tail_tag) {
             constexpr bool TAIL = decltype(tail_tag)::value;
 #pragma unroll
             for (int pt = 0; pt < PT; ++pt) {
 #pragma unroll
                 for (int t = 0; t < KT; ++t) {
+                    if constexpr (TAIL) {
 #pragma unroll
-                    for (int r = 0; r < R; ++r) {
-                        const int j = jbase + t * TM + M::row(r, g);
-                        T s = acc[pt][t][r];
-                        if constexpr (TAIL) s = (j < a.K) ? s : M::neg_inf();
-                        best[pt] = top3_insert<T>(best[pt], s, j);
+                        for (int r = 0; r < R; ++r)
+                            acc[pt][t][r] = (jbase + t * TM + M::row(r, g) < a.K) ? acc[pt][t][r] : M::neg_inf();
+                    }
+                    T tm = acc[pt][t][0];
+#pragma unroll
+                    for (int r = 1; r < R; ++r) tm = fmax(tm, acc[pt][t][r]);
+                    const T o1 = bm1[pt], o2 = bm2[pt];
+                    const bool c = tm > o1;
+                    bm2[pt] = M::med3(o1, o2, tm);
+                    bm1[pt] = fmax(o1, tm);
+                    bt[pt] = c ? kc * KT + t : bt[pt];
+                    if (c) {  // rare after the first few tiles: park the tile in this lane's LDS slot
+#pragma unroll
+                        for (int i = 0; i < BV; ++i) {
+                            frag_t w;
+#pragma unroll
+                            for (int e = 0; e < E; ++e) w[e] = acc[pt][t][i * E + e];
+                            *reinterpret_cast<frag_t *>(lds_best + ((pt * BV + i) * 256 + tid) * 16) = w;
+                        }
                     }
                 }
             }
@@ -347,18 +418,31 @@ __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a
     uint64_t n_refined = 0;
 #pragma unroll
     for (int pt = 0; pt < PT; ++pt) {
+        // arg-max inside the saved best tile, then the runner-up of the other tiles as an
+        // anonymous third entry (index -1: its centroid is not known)
+        Top3<T> best;
+        best.m1 = best.m2 = best.m3 = M::neg_inf();
+        best.i1 = best.i2 = -1;
+#pragma unroll
+        for (int i = 0; i < BV; ++i) {
+            const frag_t w = *reinterpret_cast<const frag_t *>(lds_best + ((pt * BV + i) * 256 + tid) * 16);
+#pragma unroll
+            for (int e = 0; e < E; ++e)
+                best = top3_insert<T>(best, bt[pt] >= 0 ? w[e] : M::neg_inf(), bt[pt] * TM + M::row(i * E + e, g));
+        }
+        best = top3_insert<T>(best, bm2[pt], -1);
 #pragma unroll
         for (int mask = TN; mask < 64; mask <<= 1) {
-            const T b1 = shfl_xor_t(best[pt].m1, mask), b2 = shfl_xor_t(best[pt].m2, mask),
-                    b3 = shfl_xor_t(best[pt].m3, mask);
-            const int j1 = shfl_xor_t(best[pt].i1, mask), j2 = shfl_xor_t(best[pt].i2, mask);
-            best[pt] = top3_insert<T>(best[pt], b1, j1);
-            best[pt] = top3_insert<T>(best[pt], b2, j2);
-            best[pt].m3 = M::med3(best[pt].m2, best[pt].m3, b3);  // b3 <= b2 can never pass m2
+            const T b1 = shfl_xor_t(best.m1, mask), b2 = shfl_xor_t(best.m2, mask),
+                    b3 = shfl_xor_t(best.m3, mask);
+            const int j1 = shfl_xor_t(best.i1, mask), j2 = shfl_xor_t(best.i2, mask);
+            best = top3_insert<T>(best, b1, j1);
+            best = top3_insert<T>(best, b2, j2);
+            best.m3 = M::med3(best.m2, best.m3, b3);  // b3 <= b2 can never pass m2
             xn[pt] += shfl_xor_t(xn[pt], mask);
         }
-        const T m1 = best[pt].m1, m2 = best[pt].m2, m3 = best[pt].m3;
-        const int i1 = best[pt].i1, i2 = best[pt].i2;
+        const T m1 = best.m1, m2 = best.m2, m3 = best.m3;
+        const int i1 = best.i1 < 0 ? 0 : best.i1, i2 = best.i2;
         // After the exchange both partners hold the same multiset of values but may order
         // equal scores differently; everything below only depends on values, and candidate
         // indices are made symmetric by ordering the pair.
@@ -368,7 +452,8 @@ __global__ __launch_bounds__(256, 2) void assign_generic_kernel(GenericArgs<T> a
         // plus (FT on) an undetected error below the detection threshold
         const T bound = (T)(a.band_coef + (FT ? a.ft_coef : 0.0)) * (sqrt(xn[pt]) * cmax + (T)0.5 * cmax2);
         const bool amb2 = (m1 - m2) <= bound;
-        const bool amb3 = ((m1 - m3) <= bound) || force_refine[pt] != 0;
+        // a runner-up whose centroid is unknown cannot be settled in place: leave it to the refine kernel
+        const bool amb3 = ((m1 - m3) <= bound) || force_refine[pt] != 0 || (amb2 && i2 < 0);
         int label = i1;
         T dist = xn[pt] - (T)2 * m1;
         dist = dist > T(0) ? dist : T(0);
@@ -482,7 +567,6 @@ static ftk_status launch_generic_t(const AssignCall &c, const AssignPlan &p, con
     a.D = c.D;
     a.K = c.K;
     a.D8 = p.D8;
-    a.DQ = p.DQ;
     a.nkc = p.nkc;
     a.labels = c.labels;
     a.mindist = (T *)c.mindist;
@@ -562,13 +646,15 @@ void plan_generic(ftk_dtype dtype, int64_t N, int D, int K, AssignPlan &p)
     p.KC = p.KT * p.TM;
     p.nkc = (int)ceil_div(K, p.KC);
     p.D8 = (int)ceil_div(D, 8) * 8;
-    p.DQ = (int)((p.D8 / 8 < 8) ? p.D8 / 8 : 8);
+    p.DQ = f32 ? GenericCfg<float>::DQ : GenericCfg<double>::DQ;
     p.points_per_wg = p.waves * p.PT * p.TN;
     p.workgroups = ceil_div(N, p.points_per_wg);
     p.tiles_per_wave = p.nkc * p.PT * p.KT;
     p.regs_per_tile = f32 ? Mma<float>::R : Mma<double>::R;
     const size_t esz = f32 ? 4 : 8;
-    p.lds_bytes = (size_t)(p.KC + p.KT) * (8 * p.DQ * esz + 16);
+    // two stage buffers of KC+1 rows, two half-norm buffers, the best-tile slots of 256 lanes
+    p.lds_bytes = 2 * (size_t)(p.KC + 1) * (8 * p.DQ * esz + 16) + 2 * (size_t)p.KC * esz +
+                  (size_t)p.PT * p.regs_per_tile * esz * 256;
     p.hcn_pad_inf = false;
     p.grid = (int)p.workgroups;
     p.kch = p.KC;

@@ -62,10 +62,18 @@ struct SmallArgs {
 };
 
 __device__ __forceinline__ float max3f(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
+// max(a, b) of values below FLT_MAX as the median of (a, b, FLT_MAX): one instruction, where
+// fmaxf() spends two more on canonicalising its operands (with +inf as the third operand the
+// compiler turns it back into fmaxf).  A NaN operand gives NaN, which later sends the point to
+// the exact recomputation.
+__device__ __forceinline__ float max2f(float a, float b) { return __builtin_amdgcn_fmed3f(a, b, 3.402823466e38f); }
 
 // waves per workgroup sharing one staged centroid chunk (measured: 8 beats 4 for every D <= 32,
 // even where the exact re-evaluation then spills a few registers)
 static constexpr int smalld_waves(int nq) { return nq <= 4 ? 8 : 4; }
+// waves per SIMD the register budget is sized for (the second launch-bound is waves per
+// execution unit): two resident workgroups of eight waves need four
+static constexpr int smalld_min_wgs(int nq) { return nq <= 1 ? 4 : 2; }
 constexpr int SMALLD_MAX_FAULTS = 4;  // injected faults honoured per point block
 
 // Tile geometry: which centroid sits in register r of lane group g of tile T.
@@ -136,7 +144,7 @@ struct TileBest {
 };
 
 template <int NQ, int PT, bool FT>
-__global__ __launch_bounds__(smalld_waves(NQ) * 64) void assign_smalld_kernel(SmallArgs a)
+__global__ __launch_bounds__(smalld_waves(NQ) * 64, smalld_min_wgs(NQ)) void assign_smalld_kernel(SmallArgs a)
 {
     constexpr int SMALLD_WAVES = smalld_waves(NQ);
     constexpr int SMALLD_THREADS = SMALLD_WAVES * 64;
@@ -373,20 +381,22 @@ __global__ __launch_bounds__(smalld_waves(NQ) * 64) void assign_smalld_kernel(Sm
                     }
                 }
 
-                float tm = max3f(acc[0], acc[1], acc[2]);
-                tm = max3f(tm, acc[3], acc[4]);
-                tm = max3f(tm, acc[5], acc[6]);
-                tm = max3f(tm, acc[7], acc[8]);
-                tm = max3f(tm, acc[9], acc[10]);
-                tm = max3f(tm, acc[11], acc[12]);
-                tm = max3f(tm, acc[13], acc[14]);
-                if constexpr (!FT) tm = __builtin_fmaxf(tm, acc[15]);
+                float tm;
+                if constexpr (FT) {  // 15 scores
+                    tm = max3f(acc[0], acc[1], acc[2]);
+#pragma unroll
+                    for (int r = 3; r < 15; r += 2) tm = max3f(tm, acc[r], acc[r + 1]);
+                } else {             // 16 scores
+                    tm = max2f(acc[0], acc[1]);
+#pragma unroll
+                    for (int r = 2; r < 16; r += 2) tm = max3f(tm, acc[r], acc[r + 1]);
+                }
                 const float m1 = best[pt].m1, m2 = best[pt].m2;
                 const int t1 = best[pt].t1;
                 const bool c = tm > m1;
                 best[pt].m2 = __builtin_amdgcn_fmed3f(m1, m2, tm);
                 best[pt].t1 = c ? T : t1;
-                best[pt].m1 = __builtin_fmaxf(m1, tm);
+                best[pt].m1 = max2f(m1, tm);
             }
         };
 

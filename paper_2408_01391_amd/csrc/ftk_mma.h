@@ -96,6 +96,34 @@ __device__ __forceinline__ typename Mma<T>::frag_t load_frag(const T *row, int d
     return f;
 }
 
+// Branch-free variant for the hot loops: the access is clamped into the row, so elements at or
+// beyond D come back as copies of valid elements of the same row (finite whenever the row is).
+// A load inside a branch would force the compiler to wait for every outstanding load at the next
+// use; callers either multiply the surplus elements by zero or clear them with frag_keep().
+template <typename T, bool ALIGNED>
+__device__ __forceinline__ typename Mma<T>::frag_t load_frag_clamped(const T *row, int d0, int D)
+{
+    using F = typename Mma<T>::frag_t;
+    constexpr int E = Mma<T>::E;
+    if constexpr (ALIGNED) {
+        return *reinterpret_cast<const F *>(row + min(d0, D - E));
+    } else {
+        F f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) f[e] = row[min(d0 + e, D - 1)];
+        return f;
+    }
+}
+
+// Keeps element e of a fragment fetched at feature d0 if `keep` and d0 + e < D, else zero.
+template <typename T>
+__device__ __forceinline__ typename Mma<T>::frag_t frag_keep(typename Mma<T>::frag_t f, int d0, int D, bool keep)
+{
+#pragma unroll
+    for (int e = 0; e < Mma<T>::E; ++e) f[e] = (keep && d0 + e < D) ? f[e] : T(0);
+    return f;
+}
+
 // Squared distance in the direct-difference form of the basic kernel (Section 3.1.1),
 // accumulated in double.  Used to settle points whose best scores are closer than the
 // rounding-error bound of the expanded form.
