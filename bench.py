@@ -33,7 +33,7 @@ def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--ft", default="both", choices=["off", "on", "both"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -97,7 +97,7 @@ def main():
     from paper_2408_01391_amd import binding as ftk, synth
 
     w = synth.WORKLOADS[args.workload]
-    steps = args.steps if args.steps is not None else {"c1": 200, "c2": 50, "c3": 50, "c4": 10, "c5": 10}[w.name]
+    steps = args.steps if args.steps is not None else {"c1": 500, "c2": 200, "c3": 200, "c4": 40, "c5": 30}[w.name]
     dev = torch.device("cuda:0")
     X, _ = synth.make_points(w)
     C0 = X[synth.init_indices(w, w.N)].copy()

@@ -573,9 +573,15 @@ static ftk_status launch_generic_t(const AssignCall &c, const AssignPlan &p, con
     a.wl = w.wl;
     a.wl_count = w.wl_count;
     a.stats = c.stats;
-    // |fl(s) - s| <= gamma * (|x|.|c| + |c|^2/2) with gamma = (D+4) * 2u (matrix-core products and
-    // accumulation each rounded once, factor two of slack); two scores -> twice that.
-    a.band_coef = 4.0 * (c.D + 4) * Mma<T>::kEps;
+    // Rounding bound of one score.  On this hardware the matrix instructions (fp32 and fp64) return
+    // exactly the chain of fused multiply-adds over the contraction index in order, each rounded to
+    // nearest even (checked against fmaf/fma chains on several hundred thousand random operands).
+    // A score is therefore a chain of D8 fused steps started from the rounded -||c||^2/2; every
+    // step errs by at most u times its partial sum, and the partial sums stay below
+    // B = |x|.|c| + ||c||^2/2 (up to 1 + D8 u), so |fl(s) - s| <= (D8 + 1) u B (1 + D8 u).
+    // Two scores are compared: twice that, with D8 + 4 absorbing the second-order factor and the
+    // fp32 evaluation of B itself.
+    a.band_coef = 2.0 * (p.D8 + 4) * Mma<T>::kEps;
     a.chk_v1 = (const T *)w.chk_v1;
     a.chk_v2 = (const T *)w.chk_v2;
     a.chk_s = (const T *)w.chk_s;

@@ -648,7 +648,8 @@ ftk_status launch_assign_smalld(const AssignCall &c, const AssignPlan &p, const 
     a.wl = w.wl;
     a.wl_count = w.wl_count;
     a.stats = c.stats;
-    a.band_coef = 4.0 * (c.D + 4) * Mma<float>::kEps;
+    // two scores, each a chain of D8 fused multiply-adds rounded to nearest (see the generic variant)
+    a.band_coef = 2.0 * (p.D8 + 4) * Mma<float>::kEps;
     a.chk_v1 = (const float *)w.chk_v1;
     a.chk_v2 = (const float *)w.chk_v2;
     a.chk_s = (const float *)w.chk_s;

@@ -15,30 +15,37 @@ __global__ void reset_assign_state_kernel(double *scal, int32_t *wl_count)
     }
 }
 
-// One wave per centroid row j < Kpad: hcn[j] = ||c_j||^2 / 2 (accumulated in double), zero for
-// the padding rows; scal[0] = max_j ||c_j||^2 via an integer max on the bit pattern (valid for
-// non-negative doubles).
+// hcn[j] = ||c_j||^2 / 2 (accumulated in double) for j < Kpad, zero (or +inf) for the padding
+// rows; scal[0] = max_j ||c_j||^2 via an integer max on the bit pattern (valid for non-negative
+// doubles).  L = 2^lpr_log2 lanes share a row (one lane per row for short rows), and a wave
+// issues ONE atomic for all its rows: with one atomic per row the kernel time was the
+// serialised atomics on that single address.
 template <typename T>
 __global__ __launch_bounds__(256) void centroid_norms_kernel(const T *C, int D, int K, int Kpad, T *hcn,
-                                                             double *scal, int pad_inf)
+                                                             double *scal, int pad_inf, int lpr_log2)
 {
     const int lane = threadIdx.x & 63;
-    const int j = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    if (j >= Kpad) return;
+    const int L = 1 << lpr_log2;
+    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int j = wave * (64 >> lpr_log2) + (lane >> lpr_log2);
+    const int sub = lane & (L - 1);
     double s = 0.0;
     if (j < K) {
         const T *c = C + (int64_t)j * D;
-        for (int d = lane; d < D; d += 64) {
+        for (int d = sub; d < D; d += L) {
             const double v = (double)c[d];
             s = fma(v, v, s);
         }
     }
+    for (int mask = L >> 1; mask >= 1; mask >>= 1) s += __shfl_xor(s, mask, 64);
+    if (sub == 0 && j < Kpad) hcn[j] = (j >= K && pad_inf) ? (T)__builtin_huge_val() : (T)(0.5 * s);
+    double m = s;  // zero for rows at or beyond K
 #pragma unroll
-    for (int mask = 32; mask >= 1; mask >>= 1) s += __shfl_xor(s, mask, 64);
-    if (lane == 0) {
-        hcn[j] = (j >= K && pad_inf) ? (T)__builtin_huge_val() : (T)(0.5 * s);
-        if (j < K) atomicMax((unsigned long long *)scal, (unsigned long long)__double_as_longlong(s));
+    for (int mask = 32; mask >= 1; mask >>= 1) {
+        const double o = __shfl_xor(m, mask, 64);
+        m = o > m ? o : m;
     }
+    if (lane == 0 && m > 0.0) atomicMax((unsigned long long *)scal, (unsigned long long)__double_as_longlong(m));
 }
 
 // Checksum rows of one centroid tile (TM consecutive centroids): thread d forms
@@ -84,19 +91,21 @@ ftk_status launch_centroid_prologue(const AssignCall &c, const AssignPlan &p, co
 {
     hipLaunchKernelGGL(reset_assign_state_kernel, dim3(1), dim3(64), 0, st, w.scal, w.wl_count);
     const int Kpad = p.nkc * p.KC;
-    const int blocks = (int)ceil_div(Kpad, 4);
+    // lanes per row: 1 for rows up to 32 features, 8 up to 256, else the whole wave
+    const int lpr_log2 = c.D <= 32 ? 0 : (c.D <= 256 ? 3 : 6);
+    const int blocks = (int)ceil_div(Kpad, 4 * (64 >> lpr_log2));
     const int ntiles = p.nkc;  // generic variant: one checksum row pair per K-chunk
     const bool generic_ft = c.ft != FTK_FT_OFF && p.variant == VAR_GENERIC;
     if (c.dtype == FTK_F32) {
         hipLaunchKernelGGL((centroid_norms_kernel<float>), dim3(blocks), dim3(256), 0, st,
-                           (const float *)c.C, c.D, c.K, Kpad, (float *)w.hcn, w.scal, (int)p.hcn_pad_inf);
+                           (const float *)c.C, c.D, c.K, Kpad, (float *)w.hcn, w.scal, (int)p.hcn_pad_inf, lpr_log2);
         if (generic_ft)
             hipLaunchKernelGGL((centroid_checksum_kernel<float>), dim3(ntiles), dim3(256), 0, st,
                                (const float *)c.C, (const float *)w.hcn, c.D, p.D8, c.K, p.KC,
                                (float *)w.chk_v1, (float *)w.chk_v2, (float *)w.chk_s);
     } else {
         hipLaunchKernelGGL((centroid_norms_kernel<double>), dim3(blocks), dim3(256), 0, st,
-                           (const double *)c.C, c.D, c.K, Kpad, (double *)w.hcn, w.scal, (int)p.hcn_pad_inf);
+                           (const double *)c.C, c.D, c.K, Kpad, (double *)w.hcn, w.scal, (int)p.hcn_pad_inf, lpr_log2);
         if (generic_ft)
             hipLaunchKernelGGL((centroid_checksum_kernel<double>), dim3(ntiles), dim3(256), 0, st,
                                (const double *)c.C, (const double *)w.hcn, c.D, p.D8, c.K, p.KC,

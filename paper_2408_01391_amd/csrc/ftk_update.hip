@@ -22,6 +22,7 @@ namespace ftk {
 
 constexpr int UPD_CELLS = 8192;  // int64 cells per workgroup slice (64 KB)
 constexpr int UPD_TARGET_WGS = 512;
+constexpr int UPD_THREADS = 1024;  // threads per workgroup of the LDS path: many waves per 64 KB table hide the HBM latency
 
 struct UpdatePlan {
     int Ks, Ds, nks, nds, tx_log2;
@@ -54,7 +55,7 @@ static UpdatePlan plan_update(ftk_dtype dtype, const void *X, int64_t N, int D, 
     const int slices = u.nds * u.nks;
     int chunks = UPD_TARGET_WGS / slices;
     if (chunks < 1) chunks = 1;
-    if (chunks > ceil_div(N, 256)) chunks = (int)ceil_div(N, 256);
+    if (chunks > ceil_div(N, UPD_THREADS)) chunks = (int)ceil_div(N, UPD_THREADS);
     u.chunks = chunks;
     u.rows_per_chunk = ceil_div(N, chunks);
     const int ppr = u.aligned ? (u.Ds + E - 1) / E : u.Ds;  // pieces per row slice
@@ -93,7 +94,7 @@ __device__ __forceinline__ long long to_fixed(double x, double scale)
 }
 
 template <typename T, bool ALIGNED>
-__global__ __launch_bounds__(256) void update_accumulate_kernel(
+__global__ __launch_bounds__(UPD_THREADS) void update_accumulate_kernel(
     const T *X, const int32_t *labels, int64_t N, int D, int K, const double *absmax_p,
     unsigned long long *sums, int32_t *counts, int Ks, int Ds, int nds, int tx_log2,
     int64_t rows_per_chunk)
@@ -110,15 +111,15 @@ __global__ __launch_bounds__(256) void update_accumulate_kernel(
     const int d0 = ds_i * Ds, k0 = ks_i * Ks;
     const int dn = min(Ds, D - d0);  // features in this slice
     const int kn = min(Ks, K - k0);
-    for (int i = tid; i < Ks * Ds; i += 256) cell[i] = 0ull;
-    for (int i = tid; i < Ks; i += 256) cnt[i] = 0;
+    for (int i = tid; i < Ks * Ds; i += UPD_THREADS) cell[i] = 0ull;
+    for (int i = tid; i < Ks; i += UPD_THREADS) cnt[i] = 0;
     __syncthreads();
 
     // fp32 data: 24-bit mantissas leave ample room, one limb scaled for the whole of N;
     // fp64 data: scale for this workgroup's rows only and flush into two limbs
     constexpr bool TWO_LIMB = sizeof(T) == 8;
     const double scale = fixed_point_scale(*absmax_p, TWO_LIMB ? rows_per_chunk : N);
-    const int TX = 1 << tx_log2, TY = 256 >> tx_log2;
+    const int TX = 1 << tx_log2, TY = UPD_THREADS >> tx_log2;
     const int tx = tid & (TX - 1), ty = tid >> tx_log2;
     const int ppr = (dn + E - 1) / E;
     const int64_t r0 = (int64_t)blockIdx.x * rows_per_chunk;
@@ -173,7 +174,7 @@ __global__ __launch_bounds__(256) void update_accumulate_kernel(
         }
     }
     __syncthreads();
-    for (int i = tid; i < kn * Ds; i += 256) {
+    for (int i = tid; i < kn * Ds; i += UPD_THREADS) {
         const int k = i / Ds, d = i - k * Ds;
         const long long v = (long long)cell[i];
         if (v != 0ll && d < dn) {
@@ -187,7 +188,7 @@ __global__ __launch_bounds__(256) void update_accumulate_kernel(
         }
     }
     if (ds_i == 0)
-        for (int i = tid; i < kn; i += 256)
+        for (int i = tid; i < kn; i += UPD_THREADS)
             if (cnt[i]) atomicAdd(counts + k0 + i, cnt[i]);
 }
 
@@ -457,7 +458,7 @@ ftk_status launch_update(ftk_dtype dtype, const void *X, const int32_t *labels, 
 #undef FTK_LAUNCH_RED
     } else {
     const size_t lds = (size_t)u.Ks * u.Ds * 8 + (size_t)u.Ks * 4;
-    dim3 grid(u.chunks, u.nds * u.nks), block(256);
+    dim3 grid(u.chunks, u.nds * u.nks), block(UPD_THREADS);
 #define FTK_LAUNCH_ACC(T, AL)                                                                      \
     hipLaunchKernelGGL((update_accumulate_kernel<T, AL>), grid, block, lds, st, (const T *)X, labels, \
                        N, D, K, absmax, sums, counts, u.Ks, u.Ds, u.nds, u.tx_log2, u.rows_per_chunk)
