@@ -76,6 +76,8 @@ Workspace carve_workspace(void *base, ftk_dtype dtype, int64_t N, int D, int K, 
     w.wl_count = (int32_t *)take(4 * sizeof(int32_t));
     w.wl = (int32_t *)take((size_t)N * sizeof(int32_t));
     w.fx_sums = (int64_t *)take((size_t)K * D * 2 * sizeof(int64_t));  // two limbs per cell
+    w.upd_slab = (int64_t *)take((size_t)update_slab_cells_max(N, D, K) * sizeof(int64_t));
+    w.upd_cslab = (int32_t *)take((size_t)update_slab_chunks_max(N) * K * sizeof(int32_t));
     w.absmax = (double *)take(2 * sizeof(double));
     w.sort_idx = (int32_t *)take((size_t)N * sizeof(int32_t));
     w.sort_lab = (int32_t *)take((size_t)N * sizeof(int32_t));

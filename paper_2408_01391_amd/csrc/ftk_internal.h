@@ -65,7 +65,9 @@ struct Workspace {
     int32_t *wl_count;  // [4]   refine work-list length (+ padding)
     int32_t *wl;        // [N]   refine work-list (point indices)
     // update
-    int64_t *fx_sums;   // [K*D] fixed-point sums
+    int64_t *fx_sums;   // [K*D][2] fixed-point sums, two limbs (label-sorted path)
+    int64_t *upd_slab;  // [chunks][K*D] per-workgroup fixed-point tables (LDS path)
+    int32_t *upd_cslab; // [chunks][K]   per-workgroup member counts (LDS path)
     double *absmax;     // [2]
     int32_t *sort_idx;  // [N]   point indices grouped by label
     int32_t *sort_lab;  // [N]   their labels
@@ -80,6 +82,9 @@ struct Workspace {
 };
 constexpr int FIT_MAX_ITERS_IN_WS = 4096;
 Workspace carve_workspace(void *base, ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft);
+// upper bounds of the update step's per-workgroup tables, independent of pointer alignment
+int64_t update_slab_chunks_max(int64_t N);
+int64_t update_slab_cells_max(int64_t N, int D, int K);
 
 // ---- launches (each returns after enqueueing on `st`) ------------------------------------
 struct AssignCall {

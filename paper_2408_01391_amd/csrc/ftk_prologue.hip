@@ -20,32 +20,55 @@ __global__ void reset_assign_state_kernel(double *scal, int32_t *wl_count)
 // doubles).  L = 2^lpr_log2 lanes share a row (one lane per row for short rows), and a wave
 // issues ONE atomic for all its rows: with one atomic per row the kernel time was the
 // serialised atomics on that single address.
-template <typename T>
-__global__ __launch_bounds__(256) void centroid_norms_kernel(const T *C, int D, int K, int Kpad, T *hcn,
-                                                             double *scal, int pad_inf, int lpr_log2)
+//
+// SINGLE: the whole job in one workgroup of 1024 threads, which then also resets the per-call
+// state (plain stores instead of the reset kernel plus atomics) - one launch less for the
+// common case of a centroid matrix of a few hundred KB.
+template <typename T, bool SINGLE>
+__global__ __launch_bounds__(SINGLE ? 1024 : 256) void centroid_norms_kernel(const T *C, int D, int K, int Kpad,
+                                                                            T *hcn, double *scal, int pad_inf,
+                                                                            int lpr_log2, int32_t *wl_count)
 {
     const int lane = threadIdx.x & 63;
     const int L = 1 << lpr_log2;
-    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    const int j = wave * (64 >> lpr_log2) + (lane >> lpr_log2);
+    const int rpw = 64 >> lpr_log2;  // rows per wave and step
     const int sub = lane & (L - 1);
-    double s = 0.0;
-    if (j < K) {
-        const T *c = C + (int64_t)j * D;
-        for (int d = sub; d < D; d += L) {
-            const double v = (double)c[d];
-            s = fma(v, v, s);
+    const int wave0 = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int nwaves = (int)(blockDim.x >> 6);  // SINGLE: the workgroup strides over all rows
+    double m = 0.0;
+    for (int wave = wave0; wave * rpw < Kpad; wave = SINGLE ? wave + nwaves : Kpad) {
+        const int j = wave * rpw + (lane >> lpr_log2);
+        double s = 0.0;
+        if (j < K) {
+            const T *c = C + (int64_t)j * D;
+            for (int d = sub; d < D; d += L) {
+                const double v = (double)c[d];
+                s = fma(v, v, s);
+            }
         }
+        for (int mask = L >> 1; mask >= 1; mask >>= 1) s += __shfl_xor(s, mask, 64);
+        if (sub == 0 && j < Kpad) hcn[j] = (j >= K && pad_inf) ? (T)__builtin_huge_val() : (T)(0.5 * s);
+        m = s > m ? s : m;  // s is zero for rows at or beyond K
     }
-    for (int mask = L >> 1; mask >= 1; mask >>= 1) s += __shfl_xor(s, mask, 64);
-    if (sub == 0 && j < Kpad) hcn[j] = (j >= K && pad_inf) ? (T)__builtin_huge_val() : (T)(0.5 * s);
-    double m = s;  // zero for rows at or beyond K
 #pragma unroll
     for (int mask = 32; mask >= 1; mask >>= 1) {
         const double o = __shfl_xor(m, mask, 64);
         m = o > m ? o : m;
     }
-    if (lane == 0 && m > 0.0) atomicMax((unsigned long long *)scal, (unsigned long long)__double_as_longlong(m));
+    if constexpr (SINGLE) {
+        __shared__ double sh_m[16];
+        if (lane == 0) sh_m[threadIdx.x >> 6] = m;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int i = 1; i < (int)(blockDim.x >> 6); ++i) m = sh_m[i] > m ? sh_m[i] : m;
+            scal[0] = m;
+            wl_count[0] = 0;  // refine work-list length
+            wl_count[1] = 0;  // dynamic point-block counter of the persistent small-D kernel
+        }
+    } else {
+        if (lane == 0 && m > 0.0)
+            atomicMax((unsigned long long *)scal, (unsigned long long)__double_as_longlong(m));
+    }
 }
 
 // Checksum rows of one centroid tile (TM consecutive centroids): thread d forms
@@ -89,23 +112,37 @@ __global__ __launch_bounds__(256) void centroid_checksum_kernel(const T *C, cons
 ftk_status launch_centroid_prologue(const AssignCall &c, const AssignPlan &p, const Workspace &w,
                                     hipStream_t st)
 {
-    hipLaunchKernelGGL(reset_assign_state_kernel, dim3(1), dim3(64), 0, st, w.scal, w.wl_count);
     const int Kpad = p.nkc * p.KC;
     // lanes per row: 1 for rows up to 32 features, 8 up to 256, else the whole wave
     const int lpr_log2 = c.D <= 32 ? 0 : (c.D <= 256 ? 3 : 6);
-    const int blocks = (int)ceil_div(Kpad, 4 * (64 >> lpr_log2));
+    const bool single = (int64_t)Kpad * c.D <= 262144;
+    const int blocks = single ? 1 : (int)ceil_div(Kpad, 4 * (64 >> lpr_log2));
+    const int threads = single ? 1024 : 256;
+    if (!single) hipLaunchKernelGGL(reset_assign_state_kernel, dim3(1), dim3(64), 0, st, w.scal, w.wl_count);
     const int ntiles = p.nkc;  // generic variant: one checksum row pair per K-chunk
     const bool generic_ft = c.ft != FTK_FT_OFF && p.variant == VAR_GENERIC;
     if (c.dtype == FTK_F32) {
-        hipLaunchKernelGGL((centroid_norms_kernel<float>), dim3(blocks), dim3(256), 0, st,
-                           (const float *)c.C, c.D, c.K, Kpad, (float *)w.hcn, w.scal, (int)p.hcn_pad_inf, lpr_log2);
+        if (single)
+            hipLaunchKernelGGL((centroid_norms_kernel<float, true>), dim3(blocks), dim3(threads), 0, st,
+                               (const float *)c.C, c.D, c.K, Kpad, (float *)w.hcn, w.scal, (int)p.hcn_pad_inf,
+                               lpr_log2, w.wl_count);
+        else
+            hipLaunchKernelGGL((centroid_norms_kernel<float, false>), dim3(blocks), dim3(threads), 0, st,
+                               (const float *)c.C, c.D, c.K, Kpad, (float *)w.hcn, w.scal, (int)p.hcn_pad_inf,
+                               lpr_log2, w.wl_count);
         if (generic_ft)
             hipLaunchKernelGGL((centroid_checksum_kernel<float>), dim3(ntiles), dim3(256), 0, st,
                                (const float *)c.C, (const float *)w.hcn, c.D, p.D8, c.K, p.KC,
                                (float *)w.chk_v1, (float *)w.chk_v2, (float *)w.chk_s);
     } else {
-        hipLaunchKernelGGL((centroid_norms_kernel<double>), dim3(blocks), dim3(256), 0, st,
-                           (const double *)c.C, c.D, c.K, Kpad, (double *)w.hcn, w.scal, (int)p.hcn_pad_inf, lpr_log2);
+        if (single)
+            hipLaunchKernelGGL((centroid_norms_kernel<double, true>), dim3(blocks), dim3(threads), 0, st,
+                               (const double *)c.C, c.D, c.K, Kpad, (double *)w.hcn, w.scal, (int)p.hcn_pad_inf,
+                               lpr_log2, w.wl_count);
+        else
+            hipLaunchKernelGGL((centroid_norms_kernel<double, false>), dim3(blocks), dim3(threads), 0, st,
+                               (const double *)c.C, c.D, c.K, Kpad, (double *)w.hcn, w.scal, (int)p.hcn_pad_inf,
+                               lpr_log2, w.wl_count);
         if (generic_ft)
             hipLaunchKernelGGL((centroid_checksum_kernel<double>), dim3(ntiles), dim3(256), 0, st,
                                (const double *)c.C, (const double *)w.hcn, c.D, p.D8, c.K, p.KC,

@@ -31,6 +31,23 @@ struct UpdatePlan {
     bool aligned;
 };
 
+// Row chunks of the LDS path never exceed UPD_TARGET_WGS or one per UPD_THREADS rows; with S
+// slices of at most UPD_CELLS cells covering the K*D table, chunks <= UPD_TARGET_WGS / S, hence
+// chunks * K * D <= UPD_TARGET_WGS * UPD_CELLS whenever more than one chunk is used.
+int64_t update_slab_chunks_max(int64_t N)
+{
+    const int64_t by_rows = ceil_div(N, UPD_THREADS);
+    return by_rows < UPD_TARGET_WGS ? (by_rows < 1 ? 1 : by_rows) : UPD_TARGET_WGS;
+}
+int64_t update_slab_cells_max(int64_t N, int D, int K)
+{
+    const int64_t cells = (int64_t)K * D;
+    const int64_t cap = (int64_t)UPD_TARGET_WGS * UPD_CELLS;
+    int64_t v = update_slab_chunks_max(N) * cells;
+    if (v > cap) v = cap;
+    return v > cells ? v : cells;
+}
+
 static UpdatePlan plan_update(ftk_dtype dtype, const void *X, int64_t N, int D, int K)
 {
     UpdatePlan u;
@@ -96,7 +113,7 @@ __device__ __forceinline__ long long to_fixed(double x, double scale)
 template <typename T, bool ALIGNED>
 __global__ __launch_bounds__(UPD_THREADS) void update_accumulate_kernel(
     const T *X, const int32_t *labels, int64_t N, int D, int K, const double *absmax_p,
-    unsigned long long *sums, int32_t *counts, int Ks, int Ds, int nds, int tx_log2,
+    long long *slabs, int32_t *cslabs, int Ks, int Ds, int nds, int tx_log2,
     int64_t rows_per_chunk)
 {
     using F = typename Mma<T>::frag_t;
@@ -174,22 +191,85 @@ __global__ __launch_bounds__(UPD_THREADS) void update_accumulate_kernel(
         }
     }
     __syncthreads();
+    // Flush with plain stores into this row chunk's table in global memory (every cell of the
+    // slice, zeros included, so the tables need no clearing).  Device-wide atomics on one shared
+    // table cost a memory-side transaction per cell and workgroup; the tables are summed by the
+    // averaging kernel instead, in integers, so the result is still independent of any order.
+    long long *slab = slabs + (int64_t)blockIdx.x * ((int64_t)K * D);
     for (int i = tid; i < kn * Ds; i += UPD_THREADS) {
         const int k = i / Ds, d = i - k * Ds;
-        const long long v = (long long)cell[i];
-        if (v != 0ll && d < dn) {
-            unsigned long long *dst = sums + 2 * ((int64_t)(k0 + k) * D + d0 + d);
+        if (d < dn) slab[(int64_t)(k0 + k) * D + d0 + d] = (long long)cell[i];
+    }
+    if (ds_i == 0)
+        for (int i = tid; i < kn; i += UPD_THREADS) cslabs[(int64_t)blockIdx.x * K + k0 + i] = cnt[i];
+}
+
+// Sum of the per-chunk tables and averaging pass ("the last kernel", Section 3.1.1) in one:
+// C_j = sum_j / count_j, rounded once; a cluster without points keeps its previous centroid.
+// A workgroup owns RF_CELLS consecutive cells; its RF_GROUPS thread groups each add every
+// RF_GROUPS-th table (coalesced reads, several in flight), the partial sums meet in LDS.
+// fp64 data: the tables were scaled for one chunk's rows, so the sum over chunks is carried in
+// two limbs.
+constexpr int RF_CELLS = 32, RF_GROUPS = 32;
+template <typename T>
+__global__ __launch_bounds__(RF_CELLS * RF_GROUPS) void update_reduce_finalize_kernel(
+    const long long *slabs, const int32_t *cslabs, int chunks, int64_t N, int64_t rows_per_chunk, int D,
+    int K, const double *absmax_p, T *C, int32_t *counts)
+{
+    constexpr bool TWO_LIMB = sizeof(T) == 8;
+    __shared__ long long sh_hi[RF_GROUPS][RF_CELLS], sh_lo[RF_GROUPS][RF_CELLS];
+    __shared__ int sh_cnt[RF_GROUPS][RF_CELLS];
+    const int ci = threadIdx.x % RF_CELLS, grp = threadIdx.x / RF_CELLS;
+    const int64_t cells = (int64_t)K * D;
+    const int64_t cell0 = (int64_t)blockIdx.x * RF_CELLS;
+    const int64_t cell = cell0 + ci;
+    // member counts of the rows this workgroup touches (at most RF_CELLS): thread ci <-> row
+    const int row0 = (int)(cell0 / D);
+    const int64_t last_cell = cell0 + RF_CELLS - 1 < cells ? cell0 + RF_CELLS - 1 : cells - 1;
+    const int nrows = (int)(last_cell / D) - row0 + 1;
+    int c = 0;
+    long long hi = 0, lo = 0;
+#pragma unroll 4
+    for (int ch = grp; ch < chunks; ch += RF_GROUPS) {
+        if (ci < nrows) c += cslabs[(int64_t)ch * K + row0 + ci];
+        if (cell < cells) {
+            const long long v = slabs[(int64_t)ch * cells + cell];
             if (TWO_LIMB) {
-                atomicAdd(dst, (unsigned long long)(v >> UPD_LIMB_BITS));                      // high limb (floor)
-                atomicAdd(dst + 1, (unsigned long long)(v & ((1ll << UPD_LIMB_BITS) - 1)));   // low limb >= 0
+                hi += v >> UPD_LIMB_BITS;                      // floor
+                lo += v & ((1ll << UPD_LIMB_BITS) - 1);        // >= 0
             } else {
-                atomicAdd(dst + 1, (unsigned long long)v);
+                lo += v;
             }
         }
     }
-    if (ds_i == 0)
-        for (int i = tid; i < kn; i += UPD_THREADS)
-            if (cnt[i]) atomicAdd(counts + k0 + i, cnt[i]);
+    sh_hi[grp][ci] = hi;
+    sh_lo[grp][ci] = lo;
+    sh_cnt[grp][ci] = c;
+    __syncthreads();
+    if (grp == 0) {
+        for (int g2 = 1; g2 < RF_GROUPS; ++g2) {
+            hi += sh_hi[g2][ci];
+            lo += sh_lo[g2][ci];
+            c += sh_cnt[g2][ci];
+        }
+        sh_cnt[0][ci] = c;  // row totals, read back below by the threads of other cells
+    }
+    __syncthreads();
+    if (grp == 0) {
+        if (ci < nrows) {
+            // every row's first cell lies in exactly one workgroup: that one publishes the count
+            const int64_t first = (int64_t)(row0 + ci) * D;
+            if (first >= cell0 && first <= last_cell) counts[row0 + ci] = c;
+        }
+        if (cell < cells) {
+            const int n = sh_cnt[0][(int)(cell / D) - row0];
+            if (n > 0) {
+                const double inv = 1.0 / fixed_point_scale(*absmax_p, TWO_LIMB ? rows_per_chunk : N);
+                const double total = (double)hi * (double)(1ll << UPD_LIMB_BITS) + (double)lo;
+                C[cell] = (T)((total * inv) / (double)n);
+            }
+        }
+    }
 }
 
 // Averaging pass ("the last kernel", Section 3.1.1): C_j = sum_j / count_j, rounded once;
@@ -418,15 +498,15 @@ ftk_status launch_update(ftk_dtype dtype, const void *X, const int32_t *labels, 
     const UpdatePlan u = plan_update(dtype, X, N, D, K);
     const int64_t cells = (int64_t)K * D;
     unsigned long long *sums = reinterpret_cast<unsigned long long *>(w.fx_sums);
-    {
-        const int blocks = (int)(ceil_div(cells, 256) < 1024 ? ceil_div(cells, 256) : 1024);
-        hipLaunchKernelGGL(update_zero_kernel, dim3(blocks), dim3(256), 0, st, sums, 2 * cells, counts, K);
-    }
     const size_t esz = dtype == FTK_F32 ? 4 : 8;
     // rows of at least half a cache line gather efficiently; small problems are launch bound and
-    // take the three-kernel LDS path instead of the six-kernel sorted one
+    // take the two-kernel LDS path instead of the six-kernel sorted one
     const bool sorted_path = (size_t)D * esz >= 64 && N >= 65536;
     if (sorted_path) {
+        {
+            const int blocks = (int)(ceil_div(cells, 256) < 1024 ? ceil_div(cells, 256) : 1024);
+            hipLaunchKernelGGL(update_zero_kernel, dim3(blocks), dim3(256), 0, st, sums, 2 * cells, counts, K);
+        }
         const int chunks = (int)ceil_div(N, SORT_CHUNK);
         const size_t hl = K <= SORT_MAX_K_LDS ? (size_t)K * 4 : 0;
         hipLaunchKernelGGL(sort_hist_kernel, dim3(chunks), dim3(256), hl, st, labels, N, K, counts);
@@ -456,30 +536,41 @@ ftk_status launch_update(ftk_dtype dtype, const void *X, const int32_t *labels, 
             else FTK_LAUNCH_RED(double, false);
         }
 #undef FTK_LAUNCH_RED
+        {
+            const int blocks = (int)(ceil_div(cells, 256) < 1024 ? ceil_div(cells, 256) : 1024);
+            if (dtype == FTK_F32)
+                hipLaunchKernelGGL((update_finalize_kernel<float>), dim3(blocks), dim3(256), 0, st, sums,
+                                   counts, N, (int64_t)RED_ROWS_PER_LANE_MAX, D, K, absmax, (float *)C);
+            else
+                hipLaunchKernelGGL((update_finalize_kernel<double>), dim3(blocks), dim3(256), 0, st, sums,
+                                   counts, N, (int64_t)RED_ROWS_PER_LANE_MAX, D, K, absmax, (double *)C);
+        }
     } else {
-    const size_t lds = (size_t)u.Ks * u.Ds * 8 + (size_t)u.Ks * 4;
-    dim3 grid(u.chunks, u.nds * u.nks), block(UPD_THREADS);
+        if (u.chunks > update_slab_chunks_max(N) || (int64_t)u.chunks * cells > update_slab_cells_max(N, D, K)) {
+            set_error("internal: update tables exceed the workspace bound (chunks %d)", u.chunks);
+            return FTK_EINVAL;
+        }
+        const size_t lds = (size_t)u.Ks * u.Ds * 8 + (size_t)u.Ks * 4;
+        dim3 grid(u.chunks, u.nds * u.nks), block(UPD_THREADS);
+        long long *slabs = reinterpret_cast<long long *>(w.upd_slab);
 #define FTK_LAUNCH_ACC(T, AL)                                                                      \
     hipLaunchKernelGGL((update_accumulate_kernel<T, AL>), grid, block, lds, st, (const T *)X, labels, \
-                       N, D, K, absmax, sums, counts, u.Ks, u.Ds, u.nds, u.tx_log2, u.rows_per_chunk)
-    if (dtype == FTK_F32) {
-        if (u.aligned) FTK_LAUNCH_ACC(float, true);
-        else FTK_LAUNCH_ACC(float, false);
-    } else {
-        if (u.aligned) FTK_LAUNCH_ACC(double, true);
-        else FTK_LAUNCH_ACC(double, false);
-    }
+                       N, D, K, absmax, slabs, w.upd_cslab, u.Ks, u.Ds, u.nds, u.tx_log2, u.rows_per_chunk)
+        if (dtype == FTK_F32) {
+            if (u.aligned) FTK_LAUNCH_ACC(float, true);
+            else FTK_LAUNCH_ACC(float, false);
+        } else {
+            if (u.aligned) FTK_LAUNCH_ACC(double, true);
+            else FTK_LAUNCH_ACC(double, false);
+        }
 #undef FTK_LAUNCH_ACC
-    }
-    const int64_t fin_rows = sorted_path ? RED_ROWS_PER_LANE_MAX : u.rows_per_chunk;
-    {
-        const int blocks = (int)(ceil_div(cells, 256) < 1024 ? ceil_div(cells, 256) : 1024);
+        const int blocks = (int)ceil_div(cells, RF_CELLS);
         if (dtype == FTK_F32)
-            hipLaunchKernelGGL((update_finalize_kernel<float>), dim3(blocks), dim3(256), 0, st, sums,
-                               counts, N, fin_rows, D, K, absmax, (float *)C);
+            hipLaunchKernelGGL((update_reduce_finalize_kernel<float>), dim3(blocks), dim3(RF_CELLS * RF_GROUPS), 0, st, slabs,
+                               w.upd_cslab, u.chunks, N, u.rows_per_chunk, D, K, absmax, (float *)C, counts);
         else
-            hipLaunchKernelGGL((update_finalize_kernel<double>), dim3(blocks), dim3(256), 0, st, sums,
-                               counts, N, fin_rows, D, K, absmax, (double *)C);
+            hipLaunchKernelGGL((update_reduce_finalize_kernel<double>), dim3(blocks), dim3(RF_CELLS * RF_GROUPS), 0, st, slabs,
+                               w.upd_cslab, u.chunks, N, u.rows_per_chunk, D, K, absmax, (double *)C, counts);
     }
     FTK_TRY_HIP(hipGetLastError());
     return FTK_OK;
