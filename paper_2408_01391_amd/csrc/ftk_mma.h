@@ -127,13 +127,23 @@ __device__ __forceinline__ typename Mma<T>::frag_t frag_keep(typename Mma<T>::fr
 // Squared distance in the direct-difference form of the basic kernel (Section 3.1.1),
 // accumulated in double.  Used to settle points whose best scores are closer than the
 // rounding-error bound of the expanded form.
-template <typename T>
+// Features are added in index order into one accumulator (so two candidates evaluated here
+// always compare consistently, and identical centroids tie exactly); the loads are issued
+// several fragments ahead, since their latency - not the arithmetic - is what a lane waits for.
+template <typename T, bool ALIGNED>
 __device__ __forceinline__ double exact_sqdist(const T *x, const T *c, int D)
 {
+    constexpr int E = Mma<T>::E;
     double s = 0.0;
-    for (int d = 0; d < D; ++d) {
-        double diff = (double)x[d] - (double)c[d];
-        s = fma(diff, diff, s);
+#pragma unroll 4
+    for (int d0 = 0; d0 < D; d0 += E) {
+        const typename Mma<T>::frag_t xf = load_frag<T, ALIGNED>(x, d0, D);
+        const typename Mma<T>::frag_t cf = load_frag<T, ALIGNED>(c, d0, D);
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const double diff = (double)xf[e] - (double)cf[e];
+            s = fma(diff, diff, s);
+        }
     }
     return s;
 }

@@ -71,41 +71,59 @@ __global__ __launch_bounds__(SINGLE ? 1024 : 256) void centroid_norms_kernel(con
     }
 }
 
-// Checksum rows of one centroid tile (TM consecutive centroids): thread d forms
+// Checksum rows of one centroid tile (TM consecutive centroids, TM <= 1024):
 //   v1[d] = sum_r c_{r,d}            (weights e1 = 1)
 //   v2[d] = sum_r (r+1) c_{r,d}      (weights e2 = 1..TM)
-// in double and rounds once; thread 0 also forms the matching sums of the half norms.
+// in double, rounded once, and the matching sums of the half norms.  A workgroup covers 64
+// features of one tile: 16 thread groups each add every 16th row (coalesced 64-element reads),
+// the partial sums are combined in LDS in a fixed order.
 template <typename T>
-__global__ __launch_bounds__(256) void centroid_checksum_kernel(const T *C, const T *hcn, int D, int D8,
-                                                                int K, int TM, T *v1, T *v2, T *cs)
+__global__ __launch_bounds__(1024) void centroid_checksum_kernel(const T *C, const T *hcn, int D, int D8,
+                                                                 int K, int TM, T *v1, T *v2, T *cs)
 {
+    __shared__ double sh1[16][64], sh2[16][64];
     const int tile = blockIdx.x;
     const int j0 = tile * TM;
-    for (int d = threadIdx.x; d < D8; d += blockDim.x) {
-        double s1 = 0.0, s2 = 0.0;
-        if (d < D) {
-            for (int r = 0; r < TM; ++r) {
-                const int j = j0 + r;
-                if (j >= K) break;
-                const double v = (double)C[(int64_t)j * D + d];
-                s1 += v;
-                s2 = fma((double)(r + 1), v, s2);
-            }
+    const int dl = threadIdx.x & 63, rg = threadIdx.x >> 6;
+    const int d = blockIdx.y * 64 + dl;
+    double s1 = 0.0, s2 = 0.0;
+    if (d < D) {
+        for (int r = rg; r < TM && j0 + r < K; r += 16) {
+            const double v = (double)C[(int64_t)(j0 + r) * D + d];
+            s1 += v;
+            s2 = fma((double)(r + 1), v, s2);
+        }
+    }
+    sh1[rg][dl] = s1;
+    sh2[rg][dl] = s2;
+    __syncthreads();
+    if (rg == 0 && d < D8) {
+        for (int g2 = 1; g2 < 16; ++g2) {
+            s1 += sh1[g2][dl];
+            s2 += sh2[g2][dl];
         }
         v1[(int64_t)tile * D8 + d] = (T)s1;
         v2[(int64_t)tile * D8 + d] = (T)s2;
     }
-    if (threadIdx.x == 0) {
-        double h1 = 0.0, h2 = 0.0;
-        for (int r = 0; r < TM; ++r) {
-            const int j = j0 + r;
-            if (j >= K) break;
-            const double h = (double)hcn[j];
-            h1 += h;
-            h2 = fma((double)(r + 1), h, h2);
+    if (blockIdx.y == 0) {
+        __syncthreads();
+        double *f1 = &sh1[0][0], *f2 = &sh2[0][0];  // 1024 slots each
+        const int r = threadIdx.x;
+        const double h = (r < TM && j0 + r < K) ? (double)hcn[j0 + r] : 0.0;
+        f1[r] = h;
+        f2[r] = (double)(r + 1) * h;
+        __syncthreads();
+        for (int half = 512; half >= 1; half >>= 1) {
+            if (r < half) {
+                f1[r] += f1[r + half];
+                f2[r] += f2[r + half];
+            }
+            __syncthreads();
         }
-        cs[2 * tile] = (T)h1;
-        cs[2 * tile + 1] = (T)h2;
+        if (r == 0) {
+            cs[2 * tile] = (T)f1[0];
+            cs[2 * tile + 1] = (T)f2[0];
+        }
     }
 }
 
@@ -131,7 +149,7 @@ ftk_status launch_centroid_prologue(const AssignCall &c, const AssignPlan &p, co
                                (const float *)c.C, c.D, c.K, Kpad, (float *)w.hcn, w.scal, (int)p.hcn_pad_inf,
                                lpr_log2, w.wl_count);
         if (generic_ft)
-            hipLaunchKernelGGL((centroid_checksum_kernel<float>), dim3(ntiles), dim3(256), 0, st,
+            hipLaunchKernelGGL((centroid_checksum_kernel<float>), dim3(ntiles, (unsigned)ceil_div(p.D8, 64)), dim3(1024), 0, st,
                                (const float *)c.C, (const float *)w.hcn, c.D, p.D8, c.K, p.KC,
                                (float *)w.chk_v1, (float *)w.chk_v2, (float *)w.chk_s);
     } else {
@@ -144,7 +162,7 @@ ftk_status launch_centroid_prologue(const AssignCall &c, const AssignPlan &p, co
                                (const double *)c.C, c.D, c.K, Kpad, (double *)w.hcn, w.scal, (int)p.hcn_pad_inf,
                                lpr_log2, w.wl_count);
         if (generic_ft)
-            hipLaunchKernelGGL((centroid_checksum_kernel<double>), dim3(ntiles), dim3(256), 0, st,
+            hipLaunchKernelGGL((centroid_checksum_kernel<double>), dim3(ntiles, (unsigned)ceil_div(p.D8, 64)), dim3(1024), 0, st,
                                (const double *)c.C, (const double *)w.hcn, c.D, p.D8, c.K, p.KC,
                                (double *)w.chk_v1, (double *)w.chk_v2, (double *)w.chk_s);
     }
