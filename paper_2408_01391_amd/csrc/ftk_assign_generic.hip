@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256, GenericCfg<T>::WAVES_PER_SIMD) void assign_gen
     const T cmax2 = (T)a.scal[0];
     const T cmax = sqrt(cmax2);
     // wave-uniform event counters (kept in scalar registers: counted with ballots)
-    int n_checked = 0, n_injected = 0, n_detected = 0, n_corrected = 0, n_recomputed = 0;
+    int n_injected = 0, n_detected = 0, n_corrected = 0, n_recomputed = 0;
     float worst_resid = 0.f;
 
     // faults aimed at this workgroup
@@ -328,7 +328,6 @@ __global__ __launch_bounds__(256, GenericCfg<T>::WAVES_PER_SIMD) void assign_gen
                 const T tau = (T)a.ft_coef * (sqrt(xnp) * cmax + (T)0.5 * cmax2);
                 const T resid = s1 - (rf - s1ref);
                 const bool bad = !(fabs(resid) <= tau);
-                n_checked += TN;  // one verification per point of the tile
                 if (__builtin_expect(__any(bad), 0)) {
                     n_detected += (int)__popcll(__ballot(bad && g == 0));
                     if (a.ft_mode == FTK_FT_CORRECT) {
@@ -493,15 +492,24 @@ __global__ __launch_bounds__(256, GenericCfg<T>::WAVES_PER_SIMD) void assign_gen
             if (a.mindist) a.mindist[p] = dist;
         }
     }
+    // Statistics.  Several thousand waves adding to the same few words would keep the memory
+    // system busy long after the last wave has ended, so: the number of comparisons made is known
+    // in advance and added once; the other counters are touched only when non-zero (i.e. when a
+    // fault was seen); the residual maximum is read first and raised only by a wave that exceeds it.
     if (a.stats && (FT || a.n_faults > 0)) {
-        const int v[5] = {n_checked, n_injected, n_detected, n_corrected, n_recomputed};
+        const int v[5] = {0, n_injected, n_detected, n_corrected, n_recomputed};
 #pragma unroll
         for (int mask = 1; mask < 64; mask <<= 1) worst_resid = fmaxf(worst_resid, __shfl_xor(worst_resid, mask, 64));
         if (lane == 0) {
             unsigned long long *sp = reinterpret_cast<unsigned long long *>(a.stats);
-            for (int i = 0; i < 5; ++i)
+            if (FT && blockIdx.x == 0 && wave == 0)
+                atomicAdd(sp, (unsigned long long)gridDim.x * Cfg::WAVES * PT * TN * a.nkc);
+            for (int i = 1; i < 5; ++i)
                 if (v[i]) atomicAdd(sp + i, (unsigned long long)v[i]);
-            if (FT) atomicMax(sp + 7, (unsigned long long)(fminf(worst_resid, 4000.f) * 1.0e6f));
+            if (FT) {
+                const unsigned long long mine = (unsigned long long)(fminf(worst_resid, 4000.f) * 1.0e6f);
+                if (mine > *reinterpret_cast<volatile unsigned long long *>(sp + 7)) atomicMax(sp + 7, mine);
+            }
         }
     }
     if (a.stats) {

@@ -172,7 +172,7 @@ __global__ __launch_bounds__(smalld_waves(NQ) * 64, smalld_min_wgs(NQ)) void ass
     const float cmax = sqrtf(cmax2);
     const bool resident = a.nch == 1;
     // per-lane event counters, reduced over the wave at the end
-    int n_checked = 0, n_injected = 0, n_detected = 0, n_corrected = 0, n_recomputed = 0;
+    int n_injected = 0, n_detected = 0, n_corrected = 0, n_recomputed = 0;
     float worst_resid = 0.f;
 
     // operand fetch of one centroid tile: A fragments and the accumulator start values
@@ -493,29 +493,34 @@ __global__ __launch_bounds__(smalld_waves(NQ) * 64, smalld_min_wgs(NQ)) void ass
             // NaN scores, a third candidate, or a failed repair: exact recomputation
             worklist_push(live && g == 0 && (!(thr == thr) || over || forced), (int32_t)p, a.wl, a.wl_count);
         }
-        if (FT) n_checked += a.tiles_total * PT;
         __syncthreads();
         if (tid == 0) sh_next = (int)gridDim.x + atomicAdd(a.wl_count + 1, 1);
         __syncthreads();
         blk = sh_next;
     }
 
+    // Statistics.  Thousands of waves adding to the same few words would keep the memory system
+    // busy long after the last wave has ended, so: the number of comparisons made is known in
+    // advance and added once; the other counters are touched only when non-zero (i.e. when a
+    // fault was seen); the residual maximum is read first and raised only by a wave that exceeds it.
     if (a.stats && (FT || a.n_faults > 0)) {
-        int v[5] = {n_checked, n_injected, n_detected, n_corrected, n_recomputed};
+        int v[5] = {0, n_injected, n_detected, n_corrected, n_recomputed};
 #pragma unroll
-        for (int i = 0; i < 5; ++i)
+        for (int i = 1; i < 5; ++i)
 #pragma unroll
             for (int mask = 1; mask < 64; mask <<= 1) v[i] += __shfl_xor(v[i], mask, 64);
 #pragma unroll
         for (int mask = 1; mask < 64; mask <<= 1) worst_resid = fmaxf(worst_resid, __shfl_xor(worst_resid, mask, 64));
         if (lane == 0) {
             unsigned long long *s = reinterpret_cast<unsigned long long *>(a.stats);
-            if (v[0]) atomicAdd(s + 0, (unsigned long long)v[0]);
-            if (v[1]) atomicAdd(s + 1, (unsigned long long)v[1]);
-            if (v[2]) atomicAdd(s + 2, (unsigned long long)v[2]);
-            if (v[3]) atomicAdd(s + 3, (unsigned long long)v[3]);
-            if (v[4]) atomicAdd(s + 4, (unsigned long long)v[4]);
-            if (FT) atomicMax(s + 7, (unsigned long long)(fminf(worst_resid, 4000.f) * 1.0e6f));
+            if (FT && blockIdx.x == 0 && wave == 0)  // every (point, tile, lane group) is verified once
+                atomicAdd(s, (unsigned long long)a.nblocks * SMALLD_WAVES * PT * 64 * a.tiles_total);
+            for (int i = 1; i < 5; ++i)
+                if (v[i]) atomicAdd(s + i, (unsigned long long)v[i]);
+            if (FT) {
+                const unsigned long long mine = (unsigned long long)(fminf(worst_resid, 4000.f) * 1.0e6f);
+                if (mine > *reinterpret_cast<volatile unsigned long long *>(s + 7)) atomicMax(s + 7, mine);
+            }
         }
     }
 }
