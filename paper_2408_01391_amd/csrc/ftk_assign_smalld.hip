@@ -99,17 +99,18 @@ __device__ __forceinline__ void eval_rows(const floatx4 (&xlo)[NQ], const floatx
                                           const float *base, int stride, int T, int K, int D,
                                           int gw, int r0, float &dbest, int &jbest)
 {
-    float d[8];
-    int jj[8];
-#pragma unroll
+    // rows in register order, the running minimum updated as they come; with many features the
+    // loop is unrolled only twice (all eight rows in flight would need more registers than exist)
+    constexpr int UNROLL = NQ <= 2 ? 8 : 2;
+#pragma unroll UNROLL
     for (int i = 0; i < 8; ++i) {
         // register r = r0 + i of group gw holds tile row 8*(r/4) + 4*gw + r%4; r0 is 0 or 8
         const int row = 8 * (i >> 2) + (i & 3) + 2 * r0 + 4 * gw;
         const bool real = FT ? (r0 + i < 15) : true;
         const int j = FT ? 30 * T + 15 * gw + r0 + i : 32 * T + row;
-        jj[i] = (real && j < K) ? j : 0x7fffffff;
+        const int jj = (real && j < K) ? j : 0x7fffffff;
         const float *c = LDSROWS ? base + row * stride : base + (size_t)(j < K ? j : 0) * stride;
-        d[i] = 0.f;
+        float d = 0.f;
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
             floatx4 cl = {0.f, 0.f, 0.f, 0.f}, ch = {0.f, 0.f, 0.f, 0.f};
@@ -118,22 +119,19 @@ __device__ __forceinline__ void eval_rows(const floatx4 (&xlo)[NQ], const floatx
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float t = xlo[q][e] - cl[e];
-                d[i] = fmaf(t, t, d[i]);
+                d = fmaf(t, t, d);
             }
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float t = xhi[q][e] - ch[e];
-                d[i] = fmaf(t, t, d[i]);
+                d = fmaf(t, t, d);
             }
         }
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
         const float db = dbest;
         const int jb = jbest;
-        const bool better = (jj[i] != 0x7fffffff) & ((d[i] < db) | ((d[i] == db) & (jj[i] < jb)));
-        dbest = better ? d[i] : db;
-        jbest = better ? jj[i] : jb;
+        const bool better = (jj != 0x7fffffff) & ((d < db) | ((d == db) & (jj < jb)));
+        dbest = better ? d : db;
+        jbest = better ? jj : jb;
     }
 }
 
@@ -172,6 +170,7 @@ __global__ __launch_bounds__(smalld_waves(NQ) * 64, smalld_min_wgs(NQ)) void ass
     const float cmax = sqrtf(cmax2);
     const bool resident = a.nch == 1;
     // per-lane event counters, reduced over the wave at the end
+    // wave-uniform event counters (scalar registers: counted with ballots)
     int n_injected = 0, n_detected = 0, n_corrected = 0, n_recomputed = 0;
     float worst_resid = 0.f;
 
@@ -311,7 +310,7 @@ __global__ __launch_bounds__(smalld_waves(NQ) * 64, smalld_min_wgs(NQ)) void ass
                                 const unsigned bits = __float_as_uint(acc[r]);
                                 acc[r] = (me && r == reg) ? __uint_as_float(bits ^ mask) : acc[r];
                             }
-                            n_injected += me ? 1 : 0;
+                            n_injected += (int)__popcll(__ballot(me));
                         }
                     }
                 }
@@ -324,7 +323,7 @@ __global__ __launch_bounds__(smalld_waves(NQ) * 64, smalld_min_wgs(NQ)) void ass
                     float resid = s1 - acc[15];
                     const bool bad = !(fabsf(resid) <= tau[pt]);
                     if (__builtin_expect(__any(bad), 0)) {
-                        n_detected += bad ? 1 : 0;
+                        n_detected += (int)__popcll(__ballot(bad));
                         if (a.ft_mode == FTK_FT_CORRECT) {
                             // locate with the e2 = 1..15 weighted sum; the weighted reference is
                             // formed here on demand from the weighted checksum row
@@ -366,10 +365,10 @@ __global__ __launch_bounds__(smalld_waves(NQ) * 64, smalld_min_wgs(NQ)) void ass
 #pragma unroll
                             for (int r = 1; r < RG; ++r) s1b += acc[r];
                             ok = ok && (fabsf(s1b - acc[15]) <= tau[pt]);
-                            n_corrected += ok ? 1 : 0;
+                            n_corrected += (int)__popcll(__ballot(ok));
                             // not decodable (error in the checksum register itself, several errors,
                             // Inf/NaN): the point is recomputed outside the matrix path
-                            n_recomputed += (bad && !ok) ? 1 : 0;
+                            n_recomputed += (int)__popcll(__ballot(bad && !ok));
                             force_refine[pt] |= (bad && !ok) ? 1 : 0;
                         }
                     }
@@ -504,11 +503,7 @@ __global__ __launch_bounds__(smalld_waves(NQ) * 64, smalld_min_wgs(NQ)) void ass
     // advance and added once; the other counters are touched only when non-zero (i.e. when a
     // fault was seen); the residual maximum is read first and raised only by a wave that exceeds it.
     if (a.stats && (FT || a.n_faults > 0)) {
-        int v[5] = {0, n_injected, n_detected, n_corrected, n_recomputed};
-#pragma unroll
-        for (int i = 1; i < 5; ++i)
-#pragma unroll
-            for (int mask = 1; mask < 64; mask <<= 1) v[i] += __shfl_xor(v[i], mask, 64);
+        const int v[5] = {0, n_injected, n_detected, n_corrected, n_recomputed};
 #pragma unroll
         for (int mask = 1; mask < 64; mask <<= 1) worst_resid = fmaxf(worst_resid, __shfl_xor(worst_resid, mask, 64));
         if (lane == 0) {
