@@ -185,11 +185,17 @@ __global__ __launch_bounds__(256, GenericCfg<T>::WAVES_PER_SIMD) void assign_gen
             *reinterpret_cast<frag_t *>(base + KC * SB + (tid - 64) * 16) = pfx;
     };
 
-    // quad 0 of this wave's points; afterwards every quad is prefetched one step ahead and the
-    // prefetch wraps to quad 0 at the end of a K-chunk
-    frag_t xcur[PT];
+    // The point fragments of a whole stage (DQ quads) are fetched together, one stage ahead (the
+    // prefetch wraps to stage 0 at the end of a K-chunk): the DQ pieces of a row are neighbours in
+    // memory, and requesting them back to back consumes each cache line while it is resident
+    // instead of coming back for its second half a thousand cycles later.
+    // Features beyond D hold copies of valid ones: the staged centroid rows are zero there, so they
+    // add nothing to the scores; the norm masks them explicitly.
+    frag_t xs[PT][DQ];
 #pragma unroll
-    for (int pt = 0; pt < PT; ++pt) xcur[pt] = load_frag_clamped<T, ALIGNED>(xrow[pt], E * g, D);
+    for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+        for (int q = 0; q < DQ; ++q) xs[pt][q] = load_frag_clamped<T, ALIGNED>(xrow[pt], q * 8 + E * g, D);
 
     fetch(0, 0);
     commit(0, 0, 0);
@@ -224,24 +230,23 @@ __global__ __launch_bounds__(256, GenericCfg<T>::WAVES_PER_SIMD) void assign_gen
             const bool more = kc_n < a.nkc;
             if (more) fetch(kc_n, dc_n);
             const unsigned char *const sbuf = lds_raw + buf * STAGE_BYTES;
+            frag_t xnx[PT][DQ];
+            {
+                const int qn0 = chunk_end ? 0 : q0 + DQ;
+#pragma unroll
+                for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+                    for (int q = 0; q < DQ; ++q)
+                        xnx[pt][q] = load_frag_clamped<T, ALIGNED>(xrow[pt], (qn0 + q) * 8 + E * g, D);
+            }
 #pragma unroll
             for (int q = 0; q < DQ; ++q) {
                 if (q0 + q < nq) {
-                    // prefetch the next quad of this wave's points (wraps to quad 0 at the end).
-                    // Features beyond D hold copies of valid ones: the staged centroid rows are zero
-                    // there, so they add nothing to the scores; the norm masks them explicitly.
-                    int qn = q0 + q + 1;
-                    if (qn >= nq) qn = 0;
-                    frag_t xnext[PT];
-#pragma unroll
-                    for (int pt = 0; pt < PT; ++pt)
-                        xnext[pt] = load_frag_clamped<T, ALIGNED>(xrow[pt], qn * 8 + E * g, D);
-
                     if (kc == 0) {
                         const int d0 = (q0 + q) * 8 + E * g;
 #pragma unroll
                         for (int pt = 0; pt < PT; ++pt) {
-                            const frag_t xm = frag_keep<T>(xcur[pt], d0, D, true);
+                            const frag_t xm = frag_keep<T>(xs[pt][q], d0, D, true);
 #pragma unroll
                             for (int e = 0; e < E; ++e) xn[pt] = fma(xm[e], xm[e], xn[pt]);
                         }
@@ -253,7 +258,7 @@ __global__ __launch_bounds__(256, GenericCfg<T>::WAVES_PER_SIMD) void assign_gen
 #pragma unroll
                         for (int pt = 0; pt < PT; ++pt)
 #pragma unroll
-                            for (int e = 0; e < E; ++e) ref1[pt] = fma(xcur[pt][e], v[e], ref1[pt]);
+                            for (int e = 0; e < E; ++e) ref1[pt] = fma(xs[pt][q][e], v[e], ref1[pt]);
                     }
                     frag_t av[KT];
 #pragma unroll
@@ -267,11 +272,13 @@ __global__ __launch_bounds__(256, GenericCfg<T>::WAVES_PER_SIMD) void assign_gen
                         for (int t = 0; t < KT; ++t)
 #pragma unroll
                             for (int pt = 0; pt < PT; ++pt)
-                                acc[pt][t] = M::mma(av[t][e], xcur[pt][e], acc[pt][t]);
-#pragma unroll
-                    for (int pt = 0; pt < PT; ++pt) xcur[pt] = xnext[pt];
+                                acc[pt][t] = M::mma(av[t][e], xs[pt][q][e], acc[pt][t]);
                 }
             }
+#pragma unroll
+            for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+                for (int q = 0; q < DQ; ++q) xs[pt][q] = xnx[pt][q];
             if (more) commit(kc_n, dc_n, buf ^ 1);
             __syncthreads();
             buf ^= 1;

@@ -68,12 +68,16 @@ __device__ __forceinline__ float max3f(float a, float b, float c) { return __bui
 // the exact recomputation.
 __device__ __forceinline__ float max2f(float a, float b) { return __builtin_amdgcn_fmed3f(a, b, 3.402823466e38f); }
 
+#ifndef SMALLD_FT1_WAVES
+#define SMALLD_FT1_WAVES 8
+#define SMALLD_FT1_MINW 4
+#endif
 // waves per workgroup sharing one staged centroid chunk (measured: 8 beats 4 for every D <= 32,
 // even where the exact re-evaluation then spills a few registers)
-static constexpr int smalld_waves(int nq) { return nq <= 4 ? 8 : 4; }
+static constexpr int smalld_waves(int nq, bool ft) { return (nq == 1 && ft) ? SMALLD_FT1_WAVES : (nq <= 4 ? 8 : 4); }
 // waves per SIMD the register budget is sized for (the second launch-bound is waves per
 // execution unit): two resident workgroups of eight waves need four
-static constexpr int smalld_min_wgs(int nq) { return nq <= 1 ? 4 : 2; }
+static constexpr int smalld_min_wgs(int nq, bool ft) { return (nq == 1 && ft) ? SMALLD_FT1_MINW : (nq <= 1 ? 4 : 2); }
 constexpr int SMALLD_MAX_FAULTS = 4;  // injected faults honoured per point block
 
 // Tile geometry: which centroid sits in register r of lane group g of tile T.
@@ -142,9 +146,9 @@ struct TileBest {
 };
 
 template <int NQ, int PT, bool FT>
-__global__ __launch_bounds__(smalld_waves(NQ) * 64, smalld_min_wgs(NQ)) void assign_smalld_kernel(SmallArgs a)
+__global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) void assign_smalld_kernel(SmallArgs a)
 {
-    constexpr int SMALLD_WAVES = smalld_waves(NQ);
+    constexpr int SMALLD_WAVES = smalld_waves(NQ, FT);
     constexpr int SMALLD_THREADS = SMALLD_WAVES * 64;
     using M = Mma<float>;
     using G = TileGeom<FT>;
@@ -591,7 +595,7 @@ void plan_smalld(int64_t N, int D, int K, ftk_ft_mode ft, AssignPlan &p)
     p.D8 = (int)ceil_div(D, 8) * 8;
     p.PT = 2;
     p.KT = 1;
-    p.waves = smalld_waves(p.D8 / 8);
+    p.waves = smalld_waves(p.D8 / 8, FT);
     const int SW = p.D8 + 4;
     const int tile_bytes = (32 * SW + 4) * 4 + 32 * 4;
     const int tiles_total = (int)ceil_div(K, FT ? 30 : 32);
@@ -619,9 +623,9 @@ template <int NQ>
 static void launch_smalld_t(const SmallArgs &a, const AssignPlan &p, bool ft, hipStream_t st)
 {
     if (ft)
-        hipLaunchKernelGGL((assign_smalld_kernel<NQ, 2, true>), dim3(p.grid), dim3(smalld_waves(NQ) * 64), p.lds_bytes, st, a);
+        hipLaunchKernelGGL((assign_smalld_kernel<NQ, 2, true>), dim3(p.grid), dim3(smalld_waves(NQ, true) * 64), p.lds_bytes, st, a);
     else
-        hipLaunchKernelGGL((assign_smalld_kernel<NQ, 2, false>), dim3(p.grid), dim3(smalld_waves(NQ) * 64), p.lds_bytes, st, a);
+        hipLaunchKernelGGL((assign_smalld_kernel<NQ, 2, false>), dim3(p.grid), dim3(smalld_waves(NQ, false) * 64), p.lds_bytes, st, a);
 }
 
 ftk_status launch_assign_smalld(const AssignCall &c, const AssignPlan &p, const Workspace &w, hipStream_t st)
