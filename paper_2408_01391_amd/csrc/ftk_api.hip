@@ -73,6 +73,7 @@ Workspace carve_workspace(void *base, ftk_dtype dtype, int64_t N, int D, int K, 
     w.chk_v1 = take(ntiles * D8 * esz);
     w.chk_v2 = take(ntiles * D8 * esz);
     w.chk_s = take(ntiles * 2 * esz);
+    w.chk_sd = (double *)take(ntiles * 2 * sizeof(double));
     w.wl_count = (int32_t *)take(4 * sizeof(int32_t));
     w.wl = (int32_t *)take((size_t)N * sizeof(int32_t));
     w.fx_sums = (int64_t *)take((size_t)K * D * 2 * sizeof(int64_t));  // two limbs per cell

@@ -38,7 +38,7 @@ struct GenericArgs {
     // fault tolerance / injection
     const T *chk_v1;   // [nkc][D8] per-chunk plain checksum row  (sum of the chunk's centroids)
     const T *chk_v2;   // [nkc][D8] per-chunk weighted checksum row (weights 1..KC)
-    const T *chk_s;    // [nkc][2]  matching sums of the half squared norms
+    const double *chk_s;  // [nkc][2]  matching sums of the (rounded) half squared norms, in double
     const ftk_fault *faults;
     int n_faults;
     int ft_mode;
@@ -47,11 +47,15 @@ struct GenericArgs {
 
 constexpr int GENERIC_MAX_FAULTS = 4;
 
-// Safety factor on the noise model of the checksum residual.  Fault-free residuals measured on
-// the fp32 and fp64 workloads stay below a tenth of the model, so 0.35 still leaves a factor of
-// three; a false alarm is harmless (the point is recomputed exactly), while a smaller threshold
-// narrows the band of points that must be settled exactly when checking is on.
-constexpr double GENERIC_FT_KAPPA = 0.35;
+// Safety factor on the noise model of the checksum residual.  fp32: with the reference and the
+// score total carried in double (only quad- and tile-sized partial sums are rounded in fp32),
+// fault-free residuals measured on the workloads and test shapes stay below 0.04 of the model, so
+// 0.12 leaves a factor of three.  fp64 has no wider type to carry the totals in; its residuals
+// reach 0.06 of the model, hence 0.3.  A false alarm is harmless (the point is recomputed
+// exactly), while a smaller threshold narrows the band of points that must be settled exactly
+// when checking is on.
+template <typename T>
+constexpr double generic_ft_kappa() { return sizeof(T) == 4 ? 0.12 : 0.3; }
 
 template <typename T>
 struct GenericCfg;
@@ -217,9 +221,12 @@ __global__ __launch_bounds__(256, GenericCfg<T>::WAVES_PER_SIMD) void assign_gen
                 }
             }
         }
-        T ref1[PT];  // x . (sum of the chunk's centroids), this lane's share of the features
+        // x . (sum of the chunk's centroids), this lane's share of the features.  Each quad's four
+        // products are summed in the working precision and added to a double: the rounding then
+        // scales with one quad's partial sum, not with the running total of KC-fold magnitude.
+        double ref1[PT];
 #pragma unroll
-        for (int pt = 0; pt < PT; ++pt) ref1[pt] = T(0);
+        for (int pt = 0; pt < PT; ++pt) ref1[pt] = 0.0;
 
         for (int dc = 0; dc < ndc; ++dc) {
             const int q0 = dc * DQ;
@@ -256,9 +263,12 @@ __global__ __launch_bounds__(256, GenericCfg<T>::WAVES_PER_SIMD) void assign_gen
                         const frag_t v = *reinterpret_cast<const frag_t *>(
                             sbuf + KC * SB + q * (8 * (int)sizeof(T)) + g * 16);
 #pragma unroll
-                        for (int pt = 0; pt < PT; ++pt)
+                        for (int pt = 0; pt < PT; ++pt) {
+                            T part = xs[pt][q][0] * v[0];
 #pragma unroll
-                            for (int e = 0; e < E; ++e) ref1[pt] = fma(xs[pt][q][e], v[e], ref1[pt]);
+                            for (int e = 1; e < E; ++e) part = fma(xs[pt][q][e], v[e], part);
+                            ref1[pt] += (double)part;
+                        }
                     }
                     frag_t av[KT];
 #pragma unroll
@@ -315,25 +325,34 @@ __global__ __launch_bounds__(256, GenericCfg<T>::WAVES_PER_SIMD) void assign_gen
             // Verify the chunk before the arg-max reads it: for every point the KC scores must add
             // up to x . v1 - sum ||c||^2/2 (carried through the same feature loop).  A mismatch is
             // located with the weighted sum (weights 1..KC, Section 4.1) and corrected in place.
-            const T s1ref = a.chk_s[2 * kc];
+            const double s1ref = a.chk_s[2 * kc];
+            // this lane's share of a point's KC scores: tile sums in the working precision, their
+            // total in double (same reason as for the reference above)
+            auto chunk_sum = [&](int pt) {
+                double sd = 0.0;
+#pragma unroll
+                for (int t = 0; t < KT; ++t) {
+                    T ts = acc[pt][t][0];
+#pragma unroll
+                    for (int r = 1; r < R; ++r) ts += acc[pt][t][r];
+                    sd += (double)ts;
+                }
+                return sd;
+            };
 #pragma unroll
             for (int pt = 0; pt < PT; ++pt) {
-                T s1 = T(0);
-#pragma unroll
-                for (int t = 0; t < KT; ++t)
-#pragma unroll
-                    for (int r = 0; r < R; ++r) s1 += acc[pt][t][r];
-                T rf = ref1[pt];
+                double s1d = chunk_sum(pt);
+                double rfd = ref1[pt];
                 T xnp = xn[pt];
 #pragma unroll
                 for (int mask = TN; mask < 64; mask <<= 1) {
-                    s1 += shfl_xor_t(s1, mask);
-                    rf += shfl_xor_t(rf, mask);
+                    s1d += shfl_xor_t(s1d, mask);
+                    rfd += shfl_xor_t(rfd, mask);
                     xnp += shfl_xor_t(xnp, mask);
                 }
                 // xn is complete after the first chunk; later chunks reuse the same lanes' sums
                 const T tau = (T)a.ft_coef * (sqrt(xnp) * cmax + (T)0.5 * cmax2);
-                const T resid = s1 - (rf - s1ref);
+                const T resid = (T)(s1d - (rfd - s1ref));
                 const bool bad = !(fabs(resid) <= tau);
                 if (__builtin_expect(__any(bad), 0)) {
                     n_detected += (int)__popcll(__ballot(bad && g == 0));
@@ -342,23 +361,23 @@ __global__ __launch_bounds__(256, GenericCfg<T>::WAVES_PER_SIMD) void assign_gen
                         // lane-dependent part is factored out so that the per-register weights are
                         // literals (as precomputed per-lane values they would sit in 64 registers
                         // for the whole kernel)
-                        const T wlane = (T)(M::row(0, g) + 1);
-                        T s2 = T(0), s1l = T(0);
+                        const double wlane = (double)(M::row(0, g) + 1);
+                        double s2 = 0.0, s1l = 0.0;
 #pragma unroll
                         for (int t = 0; t < KT; ++t)
 #pragma unroll
                             for (int r = 0; r < R; ++r) {
-                                s1l += acc[pt][t][r];
-                                s2 = fma((T)(t * TM + M::row(r, 0)), acc[pt][t][r], s2);
+                                s1l += (double)acc[pt][t][r];
+                                s2 = fma((double)(t * TM + M::row(r, 0)), (double)acc[pt][t][r], s2);
                             }
                         s2 = fma(wlane, s1l, s2);
                         // weighted reference on demand: x . v2 over this lane's features
-                        T r2 = T(0);
+                        double r2 = 0.0;
                         for (int qq = 0; qq < nq; ++qq) {
                             const frag_t xv = load_frag<T, ALIGNED>(xrow[pt], qq * 8 + E * g, D);
                             const frag_t vv = *reinterpret_cast<const frag_t *>(a.chk_v2 + (size_t)kc * a.D8 + qq * 8 + E * g);
 #pragma unroll
-                            for (int e = 0; e < E; ++e) r2 = fma(xv[e], vv[e], r2);
+                            for (int e = 0; e < E; ++e) r2 = fma((double)xv[e], (double)vv[e], r2);
                         }
 #pragma unroll
                         for (int mask = TN; mask < 64; mask <<= 1) {
@@ -366,7 +385,7 @@ __global__ __launch_bounds__(256, GenericCfg<T>::WAVES_PER_SIMD) void assign_gen
                             r2 += shfl_xor_t(r2, mask);
                         }
                         r2 -= a.chk_s[2 * kc + 1];
-                        const T fpos = (s2 - r2) / resid;
+                        const T fpos = (T)((s2 - r2) / (double)resid);
                         const T rpos = rint(fpos);
                         const bool finite = fabs(resid) < M::huge();
                         // the location is trusted only when the error stands far enough above the rounding
@@ -380,14 +399,10 @@ __global__ __launch_bounds__(256, GenericCfg<T>::WAVES_PER_SIMD) void assign_gen
 #pragma unroll
                             for (int r = 0; r < R; ++r)
                                 acc[pt][t][r] = (t * TM + M::row(r, 0) == wfix) ? acc[pt][t][r] - resid : acc[pt][t][r];
-                        T s1b = T(0);
-#pragma unroll
-                        for (int t = 0; t < KT; ++t)
-#pragma unroll
-                            for (int r = 0; r < R; ++r) s1b += acc[pt][t][r];
+                        double s1b = chunk_sum(pt);
 #pragma unroll
                         for (int mask = TN; mask < 64; mask <<= 1) s1b += shfl_xor_t(s1b, mask);
-                        ok = ok && (fabs(s1b - (rf - s1ref)) <= tau);
+                        ok = ok && (fabs((T)(s1b - (rfd - s1ref))) <= tau);
                         n_corrected += (int)__popcll(__ballot(ok && g == 0));
                         n_recomputed += (int)__popcll(__ballot(bad && !ok && g == 0));
                         force_refine[pt] |= (bad && !ok) ? 1 : 0;
@@ -611,16 +626,16 @@ static ftk_status launch_generic_t(const AssignCall &c, const AssignPlan &p, con
     a.band_coef = 2.0 * (p.D8 + 4) * Mma<T>::kEps;
     a.chk_v1 = (const T *)w.chk_v1;
     a.chk_v2 = (const T *)w.chk_v2;
-    a.chk_s = (const T *)w.chk_s;
+    a.chk_s = w.chk_sd;
     a.faults = c.faults;
     a.n_faults = c.n_faults;
     a.ft_mode = (int)c.ft;
     // Residual "KC scores minus carried checksum" of a fault-free chunk is rounding noise: about
     // u B n (sqrt(n) + sqrt(D)) for n = KC terms of magnitude up to B (vector sum, checksum
-    // product of magnitude n B, and the scores themselves); factor GENERIC_FT_KAPPA on top.
+    // product of magnitude n B, and the scores themselves); factor generic_ft_kappa() on top.
     {
         const double n = (double)p.KC;
-        a.ft_coef = GENERIC_FT_KAPPA * Mma<T>::kEps * n * (std::sqrt(n) + std::sqrt((double)c.D + 4.0));
+        a.ft_coef = generic_ft_kappa<T>() * Mma<T>::kEps * n * (std::sqrt(n) + std::sqrt((double)c.D + 4.0));
     }
     const bool aligned = (c.D % Mma<T>::E == 0) && ((uintptr_t)c.X % 16 == 0) && ((uintptr_t)c.C % 16 == 0);
     const bool ft = c.ft != FTK_FT_OFF;

@@ -61,7 +61,8 @@ struct Workspace {
     double *scal;       // [8]   0: max_j ||c_j||^2 (as double bits, atomically maximised)
     void *chk_v1;       // [nkc*KT][D8] per-tile plain checksum rows (dtype)
     void *chk_v2;       // [nkc*KT][D8] per-tile weighted checksum rows (dtype)
-    void *chk_s;        // [nkc*KT][2]  their half-norm terms (dtype)
+    void *chk_s;        // [nkc*KT][2]  their half-norm terms (dtype; small-D variant)
+    double *chk_sd;     // [nkc][2]     the same per K-chunk, in double (generic variant)
     int32_t *wl_count;  // [4]   refine work-list length (+ padding)
     int32_t *wl;        // [N]   refine work-list (point indices)
     // update

@@ -74,12 +74,12 @@ __global__ __launch_bounds__(SINGLE ? 1024 : 256) void centroid_norms_kernel(con
 // Checksum rows of one centroid tile (TM consecutive centroids, TM <= 1024):
 //   v1[d] = sum_r c_{r,d}            (weights e1 = 1)
 //   v2[d] = sum_r (r+1) c_{r,d}      (weights e2 = 1..TM)
-// in double, rounded once, and the matching sums of the half norms.  A workgroup covers 64
+// in double, rounded once, and the matching sums of the (rounded) half norms, kept in double.  A workgroup covers 64
 // features of one tile: 16 thread groups each add every 16th row (coalesced 64-element reads),
 // the partial sums are combined in LDS in a fixed order.
 template <typename T>
 __global__ __launch_bounds__(1024) void centroid_checksum_kernel(const T *C, const T *hcn, int D, int D8,
-                                                                 int K, int TM, T *v1, T *v2, T *cs)
+                                                                 int K, int TM, T *v1, T *v2, double *cs)
 {
     __shared__ double sh1[16][64], sh2[16][64];
     const int tile = blockIdx.x;
@@ -121,8 +121,8 @@ __global__ __launch_bounds__(1024) void centroid_checksum_kernel(const T *C, con
             __syncthreads();
         }
         if (r == 0) {
-            cs[2 * tile] = (T)f1[0];
-            cs[2 * tile + 1] = (T)f2[0];
+            cs[2 * tile] = f1[0];
+            cs[2 * tile + 1] = f2[0];
         }
     }
 }
@@ -151,7 +151,7 @@ ftk_status launch_centroid_prologue(const AssignCall &c, const AssignPlan &p, co
         if (generic_ft)
             hipLaunchKernelGGL((centroid_checksum_kernel<float>), dim3(ntiles, (unsigned)ceil_div(p.D8, 64)), dim3(1024), 0, st,
                                (const float *)c.C, (const float *)w.hcn, c.D, p.D8, c.K, p.KC,
-                               (float *)w.chk_v1, (float *)w.chk_v2, (float *)w.chk_s);
+                               (float *)w.chk_v1, (float *)w.chk_v2, w.chk_sd);
     } else {
         if (single)
             hipLaunchKernelGGL((centroid_norms_kernel<double, true>), dim3(blocks), dim3(threads), 0, st,
@@ -164,7 +164,7 @@ ftk_status launch_centroid_prologue(const AssignCall &c, const AssignPlan &p, co
         if (generic_ft)
             hipLaunchKernelGGL((centroid_checksum_kernel<double>), dim3(ntiles, (unsigned)ceil_div(p.D8, 64)), dim3(1024), 0, st,
                                (const double *)c.C, (const double *)w.hcn, c.D, p.D8, c.K, p.KC,
-                               (double *)w.chk_v1, (double *)w.chk_v2, (double *)w.chk_s);
+                               (double *)w.chk_v1, (double *)w.chk_v2, w.chk_sd);
     }
     if (c.ft != FTK_FT_OFF && p.variant == VAR_SMALLD) FTK_TRY(launch_smalld_checksums(c, p, w, st));
     FTK_TRY_HIP(hipGetLastError());
