@@ -117,7 +117,7 @@ def main():
 
     results = {}
     modes = {"off": [("off", ftk.FT_OFF)], "on": [("on", ftk.FT_CORRECT)],
-             "both": [("off", ftk.FT_OFF), ("on", ftk.FT_CORRECT)]}[args.ft]
+             "both": [("off", ftk.FT_OFF), ("on", ftk.FT_CORRECT), ("strict", ftk.FT_STRICT)]}[args.ft]
     for name, mode in modes:
         C = C0d.clone()
         time_steps(ftk, torch, Xd, C, labels, mind, counts, absmax, ws, mode, stats, args.warmup)
@@ -172,6 +172,10 @@ def main():
             "overhead_assign_kernel": results["on"]["kernel_ms"] / results["off"]["kernel_ms"] - 1.0,
             "stats": ftk.stats_dict(stats),
         }
+        if "strict" in results:  # labels guaranteed equal to a fault-free run (near-ties settled exactly)
+            out["ft"]["strict_overhead_step"] = results["strict"]["sec"] / results["off"]["sec"] - 1.0
+            out["ft"]["strict_overhead_assign_kernel"] = (results["strict"]["kernel_ms"] /
+                                                          results["off"]["kernel_ms"] - 1.0)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, X, C0, args.cpu_seconds)
     print(json.dumps(out))

@@ -51,8 +51,15 @@ typedef enum { FTK_F32 = 0, FTK_F64 = 1 } ftk_dtype;
  *   OFF     : no checksums.
  *   DETECT  : checksums carried and verified, mismatches only counted.
  *   CORRECT : a mismatching tile is repaired in place from its location-encoded checksums
- *             (Section 4.1); if the location cannot be decoded the tile is recomputed. */
-typedef enum { FTK_FT_OFF = 0, FTK_FT_DETECT = 1, FTK_FT_CORRECT = 2 } ftk_ft_mode;
+ *             (Section 4.1); if the location cannot be decoded the tile is recomputed.
+ *             As in the paper, an error smaller than the detection threshold (the rounding
+ *             noise of the checksum comparison) passes unnoticed; it can change the label
+ *             of a point only if that point's two best scores are closer than the threshold.
+ *   STRICT  : CORRECT, and in addition every point whose best scores are closer than the
+ *             detection threshold is settled by exact re-evaluation outside the matrix
+ *             path, so the labels equal those of a fault-free run whatever single error
+ *             occurred.  Costs the exact re-evaluation of those points. */
+typedef enum { FTK_FT_OFF = 0, FTK_FT_DETECT = 1, FTK_FT_CORRECT = 2, FTK_FT_STRICT = 3 } ftk_ft_mode;
 
 /* One injected soft error (fault model of Section 2.1): flip `bit` of accumulator register
  * `reg` of lane `lane`, in the `tile`-th output tile that wave `wave` of workgroup

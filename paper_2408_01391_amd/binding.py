@@ -11,7 +11,7 @@ from pathlib import Path
 
 import torch
 
-FT_OFF, FT_DETECT, FT_CORRECT = 0, 1, 2
+FT_OFF, FT_DETECT, FT_CORRECT, FT_STRICT = 0, 1, 2, 3
 F32, F64 = 0, 1
 
 _LIB_PATH = Path(__file__).resolve().parent / "libftkmeans.so"

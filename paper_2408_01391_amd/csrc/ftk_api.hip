@@ -98,7 +98,7 @@ static ftk_status check_problem(ftk_dtype dtype, int64_t N, int D, int K, int ft
         set_error("unknown dtype %d", (int)dtype);
         return FTK_EINVAL;
     }
-    if (ft != FTK_FT_OFF && ft != FTK_FT_DETECT && ft != FTK_FT_CORRECT) {
+    if (ft != FTK_FT_OFF && ft != FTK_FT_DETECT && ft != FTK_FT_CORRECT && ft != FTK_FT_STRICT) {
         set_error("unknown ft_mode %d", ft);
         return FTK_EINVAL;
     }

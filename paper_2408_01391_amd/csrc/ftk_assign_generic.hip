@@ -43,6 +43,7 @@ struct GenericArgs {
     int n_faults;
     int ft_mode;
     double ft_coef;    // detection threshold = ft_coef * (||x|| * max||c|| + max||c||^2 / 2)
+    double widen_coef; // the same in strict mode (the ambiguity band grows by the threshold), else 0
 };
 
 constexpr int GENERIC_MAX_FAULTS = 4;
@@ -356,7 +357,7 @@ __global__ __launch_bounds__(256, GenericCfg<T>::WAVES_PER_SIMD) void assign_gen
                 const bool bad = !(fabs(resid) <= tau);
                 if (__builtin_expect(__any(bad), 0)) {
                     n_detected += (int)__popcll(__ballot(bad && g == 0));
-                    if (a.ft_mode == FTK_FT_CORRECT) {
+                    if (a.ft_mode >= FTK_FT_CORRECT) {
                         // weight of register (t, r) = its chunk row + 1 = wlane + (row at g = 0): the
                         // lane-dependent part is factored out so that the per-register weights are
                         // literals (as precomputed per-lane values they would sit in 64 registers
@@ -486,8 +487,8 @@ __global__ __launch_bounds__(256, GenericCfg<T>::WAVES_PER_SIMD) void assign_gen
         const int64_t p = p0 + pt * TN + col;
         const bool live = p < a.N;
         // scores inside `bound` of each other cannot be ordered: rounding of the expanded form,
-        // plus (FT on) an undetected error below the detection threshold
-        const T bound = (T)(a.band_coef + (FT ? a.ft_coef : 0.0)) * (sqrt(xn[pt]) * cmax + (T)0.5 * cmax2);
+        // plus (strict FT) an undetected error below the detection threshold
+        const T bound = (T)(a.band_coef + (FT ? a.widen_coef : 0.0)) * (sqrt(xn[pt]) * cmax + (T)0.5 * cmax2);
         const bool amb2 = (m1 - m2) <= bound;
         // a runner-up whose centroid is unknown cannot be settled in place: leave it to the refine kernel
         const bool amb3 = ((m1 - m3) <= bound) || force_refine[pt] != 0 || (amb2 && i2 < 0);
@@ -636,6 +637,7 @@ static ftk_status launch_generic_t(const AssignCall &c, const AssignPlan &p, con
     {
         const double n = (double)p.KC;
         a.ft_coef = generic_ft_kappa<T>() * Mma<T>::kEps * n * (std::sqrt(n) + std::sqrt((double)c.D + 4.0));
+        a.widen_coef = c.ft == FTK_FT_STRICT ? a.ft_coef : 0.0;
     }
     const bool aligned = (c.D % Mma<T>::E == 0) && ((uintptr_t)c.X % 16 == 0) && ((uintptr_t)c.C % 16 == 0);
     const bool ft = c.ft != FTK_FT_OFF;

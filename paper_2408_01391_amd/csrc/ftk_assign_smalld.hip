@@ -59,6 +59,7 @@ struct SmallArgs {
     int n_faults;
     int ft_mode;
     double ft_coef;       // detection threshold = ft_coef * (||x|| max||c|| + max||c||^2/2)
+    float widen;          // 1 in strict mode (the ambiguity band grows by the threshold), else 0
 };
 
 __device__ __forceinline__ float max3f(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
@@ -137,6 +138,17 @@ __device__ __forceinline__ void eval_rows(const floatx4 (&xlo)[NQ], const floatx
         dbest = better ? d : db;
         jbest = better ? jj : jb;
     }
+}
+
+// Sum of the 15 scores of one lane group, added pairwise: partial sums stay small, which roughly
+// halves the rounding noise of a running sum (and the four sub-sums are independent chains).
+__device__ __forceinline__ float sum15(const floatx16 &a)
+{
+    const float p0 = (a[0] + a[1]) + (a[2] + a[3]);
+    const float p1 = (a[4] + a[5]) + (a[6] + a[7]);
+    const float p2 = (a[8] + a[9]) + (a[10] + a[11]);
+    const float p3 = (a[12] + a[13]) + a[14];
+    return (p0 + p1) + (p2 + p3);
 }
 
 // Best tile maximum, the tile it came from, and the runner-up tile maximum of one lane.
@@ -321,14 +333,11 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
 
                 if constexpr (FT) {
                     // verify: the 15 scores of this lane must add up to the carried checksum
-                    float s1 = acc[0];
-#pragma unroll
-                    for (int r = 1; r < RG; ++r) s1 += acc[r];
-                    float resid = s1 - acc[15];
+                    float resid = sum15(acc) - acc[15];
                     const bool bad = !(fabsf(resid) <= tau[pt]);
                     if (__builtin_expect(__any(bad), 0)) {
                         n_detected += (int)__popcll(__ballot(bad));
-                        if (a.ft_mode == FTK_FT_CORRECT) {
+                        if (a.ft_mode >= FTK_FT_CORRECT) {
                             // locate with the e2 = 1..15 weighted sum; the weighted reference is
                             // formed here on demand from the weighted checksum row
                             float s2 = 0.f;
@@ -365,10 +374,7 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
                             const int rfix = ok ? (int)rpos - 1 : -1;
 #pragma unroll
                             for (int r = 0; r < RG; ++r) acc[r] = (r == rfix) ? acc[r] - delta : acc[r];
-                            float s1b = acc[0];
-#pragma unroll
-                            for (int r = 1; r < RG; ++r) s1b += acc[r];
-                            ok = ok && (fabsf(s1b - acc[15]) <= tau[pt]);
+                            ok = ok && (fabsf(sum15(acc) - acc[15]) <= tau[pt]);
                             n_corrected += (int)__popcll(__ballot(ok));
                             // not decodable (error in the checksum register itself, several errors,
                             // Inf/NaN): the point is recomputed outside the matrix path
@@ -447,9 +453,9 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
                     xhi[q][e] = g == 0 ? other : mine;
                 }
             // scores inside `bound` of each other cannot be ordered: rounding of the expanded
-            // form, plus (FT on) an undetected error below the detection threshold
+            // form, plus (strict FT) an undetected error below the detection threshold
             float bound = (float)a.band_coef * (sqrtf(xn[pt]) * cmax + 0.5f * cmax2);
-            if (FT) bound += tau[pt];
+            if (FT) bound = fmaf(a.widen, tau[pt], bound);
             const float om1 = __shfl_xor(best[pt].m1, 32, 64), om2 = __shfl_xor(best[pt].m2, 32, 64);
             const int ot1 = __shfl_xor(best[pt].t1, 32, 64);
             const bool mine_wins = best[pt].m1 > om1 || (best[pt].m1 == om1 && g == 0);
@@ -661,6 +667,7 @@ ftk_status launch_assign_smalld(const AssignCall &c, const AssignPlan &p, const 
     a.n_faults = c.n_faults;
     a.ft_mode = (int)c.ft;
     a.ft_coef = smalld_ft_coef(c.D);
+    a.widen = c.ft == FTK_FT_STRICT ? 1.0f : 0.0f;
     switch (p.D8 / 8) {
     case 1: launch_smalld_t<1>(a, p, FT, st); break;
     case 2: launch_smalld_t<2>(a, p, FT, st); break;
