@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--ft", default="both", choices=["off", "on", "both"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--inject-seconds", type=float, default=2.0,
+                    help="run time of the bit-flip injection leg (workloads with a flip rate; 0 = skip)")
     return ap.parse_args()
 
 
@@ -52,8 +54,37 @@ def time_steps(ftk, torch, Xd, C, labels, mind, counts, absmax, ws, ft_mode, sta
     return time.perf_counter() - t0
 
 
-def cpu_baseline(w, X, C0, seconds):
+def time_steps_injected(ftk, torch, np, w, Xd, C, labels, mind, counts, absmax, ws, stats, rate, step_s, seconds):
+    """FT on (correct mode) with single-bit flips arriving as a Poisson process of `rate` per second
+    of run time (fault model of Section 2.1): a seeded schedule draws, per Lloyd step, how many
+    accumulator elements of that step's assignment are corrupted, at uniformly random positions and
+    bits.  Runs for about `seconds`; returns (steps, seconds, flips scheduled)."""
+    code = ftk.F32 if w.dtype == "f32" else ftk.F64
+    geom = ftk.assign_geometry(code, w.N, w.D, w.K, ftk.FT_CORRECT)
+    steps = max(50, int(seconds / step_s))
+    rng = np.random.default_rng(w.seed + 77)
+    per_step = rng.poisson(rate * step_s, size=steps)
+    plan = {}
+    for i in np.flatnonzero(per_step):
+        rows = [(int(rng.integers(geom.workgroups)), int(rng.integers(geom.waves_per_workgroup)),
+                 int(rng.integers(geom.tiles_per_wave)), int(rng.integers(geom.regs_per_tile)),
+                 int(rng.integers(geom.lanes)), int(rng.integers(geom.bits))) for _ in range(per_step[i])]
+        plan[int(i)] = ftk.make_faults(rows, Xd.device)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        ftk.kmeans_assign(Xd, C, labels=labels, mindist=mind, ft_mode=ftk.FT_CORRECT, faults=plan.get(i),
+                          stats=stats, workspace=ws)
+        ftk.kmeans_update(Xd, labels, C, counts=counts, x_absmax=absmax, workspace=ws)
+    torch.cuda.synchronize()
+    return steps, time.perf_counter() - t0, int(per_step.sum())
+
+
+def cpu_baseline(w, X, C0, seconds, gpu_labels0):
     """The oracle as it stands, timed on the host cores for about `seconds`.
+
+    Its first assignment (against the initial centroids) doubles as a parity sample: the GPU
+    labels of the same rows are compared and the disagreements classified by the tie band.
 
     If one full Lloyd iteration (assign + update over all N points) does not fit the budget, the
     first S points are used against all K centroids and the rate is scaled linearly in N;
@@ -68,9 +99,21 @@ def cpu_baseline(w, X, C0, seconds):
     S = int(min(N, max(S, S * seconds / t_probe)))
     C = C0
     iters = 0
+    agreement = None
     t0 = time.perf_counter()
     while True:
-        lab, _, _ = oracle.assign(X[:S], C)
+        lab, best, _ = oracle.assign(X[:S], C)
+        if iters == 0:
+            t_pause = time.perf_counter()
+            import numpy as np
+            g = gpu_labels0[:S]
+            diff = np.flatnonzero(g != lab)
+            tol = 1e-5 if w.dtype == "f32" else 1e-12
+            d_gpu = ((X[diff].astype(np.float64) - C0[g[diff]].astype(np.float64)) ** 2).sum(1)
+            inside = int((d_gpu - best[diff] <= tol * best[diff]).sum())
+            agreement = {"rows": int(S), "identical": int(S - diff.size), "differ_inside_tie_band": inside,
+                         "differ_outside_tie_band": int(diff.size - inside), "tie_band_rel": tol}
+            t0 += time.perf_counter() - t_pause  # the comparison is not oracle time
         C, _ = oracle.update(X[:S], lab, C)
         iters += 1
         t = time.perf_counter() - t0
@@ -83,6 +126,7 @@ def cpu_baseline(w, X, C0, seconds):
         "kind": "oracle",
         "sample": "%d x (assign+update) of the first %d of %d points against all K=%d centroids took %.2f s%s"
                   % (iters, S, N, C0.shape[0], t, "; scaled linearly in N" if S < N else ""),
+        "label_agreement_first_assign": agreement,
     }
 
 
@@ -148,8 +192,8 @@ def main():
         "vs_baseline": None,
         "dtype": w.dtype,
         "data": "synthetic",
-        "config": {"workload": "%s: N=%d D=%d K=%d %s, seeded blobs, FT %s" % (
-            w.name, N, D, K, w.dtype, "off" if "off" in results else "on")},
+        "config": {"workload": "%s: N=%d D=%d K=%d %s, seeded %s, FT %s" % (
+            w.name, N, D, K, w.dtype, w.kind, "off" if "off" in results else "on")},
         "roofline": {
             "bound": "mfma",
             "kernel": "assign",
@@ -172,12 +216,31 @@ def main():
             "overhead_assign_kernel": results["on"]["kernel_ms"] / results["off"]["kernel_ms"] - 1.0,
             "stats": ftk.stats_dict(stats),
         }
+        if w.flips_per_s > 0 and args.inject_seconds > 0:
+            inj_stats = ftk.new_stats(dev)
+            C = C0d.clone()
+            time_steps(ftk, torch, Xd, C, labels, mind, counts, absmax, ws, ftk.FT_CORRECT, stats, args.warmup)
+            n_inj, sec_inj, flips = time_steps_injected(ftk, torch, np, w, Xd, C, labels, mind, counts, absmax, ws,
+                                                        inj_stats, w.flips_per_s, results["on"]["sec"] / steps,
+                                                        args.inject_seconds)
+            st = ftk.stats_dict(inj_stats)
+            out["ft"]["under_injection"] = {
+                "flips_per_s": w.flips_per_s, "steps": n_inj, "seconds": sec_inj,
+                "iters_per_s": n_inj / sec_inj,
+                "overhead_step": (sec_inj / n_inj) / (results["off"]["sec"] / steps) - 1.0,
+                "scheduled": flips, "injected": st["injected"], "detected": st["detected"],
+                "corrected": st["corrected"], "recomputed": st["recomputed"],
+                "uncorrectable": st["uncorrectable"],
+                "below_threshold": st["injected"] - st["detected"],
+            }
         if "strict" in results:  # labels guaranteed equal to a fault-free run (near-ties settled exactly)
             out["ft"]["strict_overhead_step"] = results["strict"]["sec"] / results["off"]["sec"] - 1.0
             out["ft"]["strict_overhead_assign_kernel"] = (results["strict"]["kernel_ms"] /
                                                           results["off"]["kernel_ms"] - 1.0)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, X, C0, args.cpu_seconds)
+        lab0, _ = ftk.kmeans_assign(Xd, C0d, labels=labels, mindist=mind, workspace=ws)
+        torch.cuda.synchronize()
+        out["cpu_baseline"] = cpu_baseline(w, X, C0, args.cpu_seconds, lab0.cpu().numpy())
     print(json.dumps(out))
 
 
