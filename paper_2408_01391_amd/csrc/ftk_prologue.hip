@@ -23,7 +23,7 @@ __global__ void reset_assign_state_kernel(double *scal, int32_t *wl_count)
 //
 // SINGLE: the whole job in one workgroup of 1024 threads, which then also resets the per-call
 // state (plain stores instead of the reset kernel plus atomics) - one launch less for the
-// common case of a centroid matrix of a few hundred KB.
+// common case of a small centroid matrix (up to 64K elements).
 template <typename T, bool SINGLE>
 __global__ __launch_bounds__(SINGLE ? 1024 : 256) void centroid_norms_kernel(const T *C, int D, int K, int Kpad,
                                                                             T *hcn, double *scal, int pad_inf,
@@ -41,6 +41,8 @@ __global__ __launch_bounds__(SINGLE ? 1024 : 256) void centroid_norms_kernel(con
         double s = 0.0;
         if (j < K) {
             const T *c = C + (int64_t)j * D;
+            // several loads in flight per lane: the job is a latency chain otherwise
+#pragma unroll 8
             for (int d = sub; d < D; d += L) {
                 const double v = (double)c[d];
                 s = fma(v, v, s);
@@ -133,7 +135,7 @@ ftk_status launch_centroid_prologue(const AssignCall &c, const AssignPlan &p, co
     const int Kpad = p.nkc * p.KC;
     // lanes per row: 1 for rows up to 32 features, 8 up to 256, else the whole wave
     const int lpr_log2 = c.D <= 32 ? 0 : (c.D <= 256 ? 3 : 6);
-    const bool single = (int64_t)Kpad * c.D <= 262144;
+    const bool single = (int64_t)Kpad * c.D <= 65536;
     const int blocks = single ? 1 : (int)ceil_div(Kpad, 4 * (64 >> lpr_log2));
     const int threads = single ? 1024 : 256;
     if (!single) hipLaunchKernelGGL(reset_assign_state_kernel, dim3(1), dim3(64), 0, st, w.scal, w.wl_count);
