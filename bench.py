@@ -49,7 +49,19 @@ def time_steps(ftk, torch, Xd, C, labels, mind, counts, absmax, ws, ft_mode, sta
     t0 = time.perf_counter()
     for _ in range(steps):
         ftk.kmeans_assign(Xd, C, labels=labels, mindist=mind, ft_mode=ft_mode, stats=stats, workspace=ws)
-        ftk.kmeans_update(Xd, labels, C, counts=counts, x_absmax=absmax, workspace=ws)
+        ftk.kmeans_update(Xd, labels, C, counts=counts, x_absmax=absmax, workspace=ws, ft_mode=ft_mode,
+                          stats=stats if ft_mode != ftk.FT_OFF else None)
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0
+
+
+def time_updates(ftk, torch, Xd, C, labels, counts, absmax, ws, ft_mode, stats, reps):
+    """`reps` update steps alone (labels fixed; C is rewritten with the same values); seconds."""
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        ftk.kmeans_update(Xd, labels, C, counts=counts, x_absmax=absmax, workspace=ws, ft_mode=ft_mode,
+                          stats=stats if ft_mode != ftk.FT_OFF else None)
     torch.cuda.synchronize()
     return time.perf_counter() - t0
 
@@ -75,7 +87,8 @@ def time_steps_injected(ftk, torch, np, w, Xd, C, labels, mind, counts, absmax, 
     for i in range(steps):
         ftk.kmeans_assign(Xd, C, labels=labels, mindist=mind, ft_mode=ftk.FT_CORRECT, faults=plan.get(i),
                           stats=stats, workspace=ws)
-        ftk.kmeans_update(Xd, labels, C, counts=counts, x_absmax=absmax, workspace=ws)
+        ftk.kmeans_update(Xd, labels, C, counts=counts, x_absmax=absmax, workspace=ws, ft_mode=ftk.FT_CORRECT,
+                          stats=stats)
     torch.cuda.synchronize()
     return steps, time.perf_counter() - t0, int(per_step.sum())
 
@@ -216,6 +229,14 @@ def main():
             "overhead_assign_kernel": results["on"]["kernel_ms"] / results["off"]["kernel_ms"] - 1.0,
             "stats": ftk.stats_dict(stats),
         }
+        # update step alone, plain and under dual modular redundancy
+        reps = max(20, steps // 2)
+        time_updates(ftk, torch, Xd, C, labels, counts, absmax, ws, ftk.FT_OFF, stats, 10)
+        t_plain = time_updates(ftk, torch, Xd, C, labels, counts, absmax, ws, ftk.FT_OFF, stats, reps)
+        time_updates(ftk, torch, Xd, C, labels, counts, absmax, ws, ftk.FT_CORRECT, stats, 10)
+        t_dmr = time_updates(ftk, torch, Xd, C, labels, counts, absmax, ws, ftk.FT_CORRECT, stats, reps)
+        out["ft"]["update_ms"] = 1e3 * t_plain / reps
+        out["ft"]["update_dmr_overhead"] = t_dmr / t_plain - 1.0
         if w.flips_per_s > 0 and args.inject_seconds > 0:
             inj_stats = ftk.new_stats(dev)
             C = C0d.clone()

@@ -130,6 +130,33 @@ ftk_status ftk_kmeans_update(ftk_dtype dtype, const void *X, const int32_t *labe
                              const double *x_absmax, void *workspace, size_t workspace_bytes,
                              void *hip_stream);
 
+/* The same update step protected by dual modular redundancy (Sections 2.3 and 4: the
+ * memory-bound update is covered by duplicating its arithmetic and comparing).  With
+ * ft != FTK_FT_OFF every arithmetic result of the step - conversion to fixed point, running
+ * sums, member counts, table sums, scaling and division - is produced twice from the same
+ * loaded operands and the two results are compared as integers before they leave the
+ * registers (label-sorted path) or through a shadow total per workgroup (LDS-table path).
+ *   DETECT           : a mismatch is counted (`detected`); the first result is used.
+ *   CORRECT / STRICT : the affected run / workgroup pass is recomputed (`recomputed`; a pass
+ *                      that mismatches again counts as `uncorrectable`), so the result equals
+ *                      the fault-free one bit for bit.
+ *   faults [n_faults] in : soft errors to inject into the first instruction stream of the
+ *                      accumulating kernel: flip `bit` (mod 64) of the running sum / converted
+ *                      operand number `reg` of lane `lane`, wave `wave`, workgroup `workgroup`,
+ *                      after step `tile` of its row loop; extents from ftk_update_geometry.
+ *                      With ft == FTK_FT_OFF they are injected unprotected.
+ *   stats             i/o : injected / detected / recomputed / uncorrectable are added to. */
+ftk_status ftk_kmeans_update_ft(ftk_dtype dtype, const void *X, const int32_t *labels, int64_t N,
+                                int32_t D, int32_t K, void *C, int32_t *counts,
+                                const double *x_absmax, ftk_ft_mode ft, const ftk_fault *faults,
+                                int32_t n_faults, ftk_ft_stats *stats, void *workspace,
+                                size_t workspace_bytes, void *hip_stream);
+
+/* Extents of the fault coordinates of ftk_kmeans_update_ft (rows_aligned16: whether X rows are
+ * 16-byte aligned, i.e. X % 16 == 0 and D * element size % 16 == 0). */
+ftk_status ftk_update_geometry(ftk_dtype dtype, int64_t N, int32_t D, int32_t K,
+                               int32_t rows_aligned16, ftk_geometry *out /* (host) */);
+
 /* Lloyd loop, Section 2: `iters` times { assign ; update }, fixed iteration count.
  *   C_init [K x D]        in  : initial centroids, or NULL to take K distinct points of X
  *                               chosen by Floyd sampling driven by SplitMix64(seed)
@@ -140,6 +167,7 @@ ftk_status ftk_kmeans_update(ftk_dtype dtype, const void *X, const int32_t *labe
  *   counts_out [K]        out : cluster sizes of that assignment.
  *   inertia_per_iter      out : (host, may be NULL) sum of mindist of every iteration;
  *                               when given, the call waits for the stream before returning.
+ *   ft                        : mode of the assignment (checksums) and of the update (DMR).
  *   stats                 i/o : fault-tolerance counters summed over iterations, may be NULL. */
 ftk_status ftk_kmeans_fit(ftk_dtype dtype, const void *X, int64_t N, int32_t D, int32_t K,
                           int32_t iters, uint64_t seed, const void *C_init, void *C_out,

@@ -53,6 +53,10 @@ def load():
     L.ftk_absmax.restype = i32
     L.ftk_kmeans_update.argtypes = [i32, vp, vp, i64, i32, i32, vp, vp, vp, vp, sz, vp]
     L.ftk_kmeans_update.restype = i32
+    L.ftk_kmeans_update_ft.argtypes = [i32, vp, vp, i64, i32, i32, vp, vp, vp, i32, vp, i32, vp, vp, sz, vp]
+    L.ftk_kmeans_update_ft.restype = i32
+    L.ftk_update_geometry.argtypes = [i32, i64, i32, i32, i32, ctypes.POINTER(Geometry)]
+    L.ftk_update_geometry.restype = i32
     L.ftk_kmeans_fit.argtypes = [i32, vp, i64, i32, i32, i32, u64, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
     L.ftk_kmeans_fit.restype = i32
     L.ftk_seeded_indices.argtypes = [u64, i64, i32, vp]
@@ -68,7 +72,7 @@ def load():
 
 
 EXPORTS = ("ftk_workspace_bytes", "ftk_assign_geometry", "ftk_kmeans_assign", "ftk_absmax",
-           "ftk_kmeans_update", "ftk_kmeans_fit", "ftk_seeded_indices", "ftk_profile_enable",
+           "ftk_kmeans_update", "ftk_kmeans_update_ft", "ftk_update_geometry", "ftk_kmeans_fit", "ftk_seeded_indices", "ftk_profile_enable",
            "ftk_profile_read", "ftk_last_error", "ftk_version")
 
 
@@ -167,8 +171,16 @@ def absmax(X: torch.Tensor) -> torch.Tensor:
     return out
 
 
-def kmeans_update(X, labels, C, counts=None, x_absmax=None, workspace=None):
-    """Update step (Eq. 2), in place on C.  Returns (C, counts int32 [K])."""
+def update_geometry(dtype_code: int, N: int, D: int, K: int, rows_aligned16: bool = True) -> Geometry:
+    g = Geometry()
+    _check(load().ftk_update_geometry(dtype_code, N, D, K, 1 if rows_aligned16 else 0, ctypes.byref(g)))
+    return g
+
+
+def kmeans_update(X, labels, C, counts=None, x_absmax=None, workspace=None, ft_mode=FT_OFF, faults=None,
+                  stats=None):
+    """Update step (Eq. 2), in place on C; with ft_mode on, under dual modular redundancy.
+    Returns (C, counts int32 [K])."""
     _dev2d(X, "X"), _dev2d(C, "C")
     N, D = X.shape
     K = C.shape[0]
@@ -179,8 +191,14 @@ def kmeans_update(X, labels, C, counts=None, x_absmax=None, workspace=None):
     if workspace is None:
         workspace = new_workspace(X, K, FT_OFF)
     wp, wn = _ws_args(workspace)
-    _check(load().ftk_kmeans_update(_dtype_code(X), X.data_ptr(), labels.data_ptr(), N, D, K,
-                                    C.data_ptr(), counts.data_ptr(), _ptr(x_absmax), wp, wn, _stream()))
+    if ft_mode == FT_OFF and faults is None and stats is None:
+        _check(load().ftk_kmeans_update(_dtype_code(X), X.data_ptr(), labels.data_ptr(), N, D, K,
+                                        C.data_ptr(), counts.data_ptr(), _ptr(x_absmax), wp, wn, _stream()))
+    else:
+        nf = 0 if faults is None else int(faults.shape[0])
+        _check(load().ftk_kmeans_update_ft(_dtype_code(X), X.data_ptr(), labels.data_ptr(), N, D, K,
+                                           C.data_ptr(), counts.data_ptr(), _ptr(x_absmax), ft_mode,
+                                           _ptr(faults), nf, _ptr(stats), wp, wn, _stream()))
     return C, counts
 
 

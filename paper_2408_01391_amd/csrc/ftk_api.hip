@@ -280,26 +280,53 @@ ftk_status ftk_absmax(ftk_dtype dtype, const void *X, int64_t count, double *out
     return launch_absmax(dtype, X, count, out_absmax, (hipStream_t)hip_stream);
 }
 
-ftk_status ftk_kmeans_update(ftk_dtype dtype, const void *X, const int32_t *labels, int64_t N,
-                             int32_t D, int32_t K, void *C, int32_t *counts, const double *x_absmax,
-                             void *workspace, size_t workspace_bytes, void *hip_stream)
+ftk_status ftk_kmeans_update_ft(ftk_dtype dtype, const void *X, const int32_t *labels, int64_t N,
+                                int32_t D, int32_t K, void *C, int32_t *counts, const double *x_absmax,
+                                ftk_ft_mode ft, const ftk_fault *faults, int32_t n_faults,
+                                ftk_ft_stats *stats, void *workspace, size_t workspace_bytes,
+                                void *hip_stream)
 {
-    FTK_TRY(check_problem(dtype, N, D, K, FTK_FT_OFF));
+    FTK_TRY(check_problem(dtype, N, D, K, ft));
     const size_t esz = dtype == FTK_F32 ? 4 : 8;
     FTK_TRY(check_ptr(X, esz, "X"));
     FTK_TRY(check_ptr(labels, 4, "labels"));
     FTK_TRY(check_ptr(C, esz, "C"));
     FTK_TRY(check_ptr(counts, 4, "counts"));
     if (x_absmax) FTK_TRY(check_ptr(x_absmax, 8, "x_absmax"));
-    FTK_TRY(check_workspace(workspace, workspace_bytes, ftk_workspace_bytes(dtype, N, D, K, FTK_FT_OFF)));
+    if (n_faults < 0 || (n_faults > 0 && !faults)) {
+        set_error("n_faults = %d with faults = %p", n_faults, (const void *)faults);
+        return FTK_EINVAL;
+    }
+    if (stats) FTK_TRY(check_ptr(stats, 8, "stats"));
+    FTK_TRY(check_workspace(workspace, workspace_bytes, ftk_workspace_bytes(dtype, N, D, K, ft)));
     FTK_TRY(check_device());
     hipStream_t st = (hipStream_t)hip_stream;
-    const Workspace w = carve_workspace(workspace, dtype, N, D, K, FTK_FT_OFF);
+    const Workspace w = carve_workspace(workspace, dtype, N, D, K, ft);
     if (!x_absmax) {
         FTK_TRY(launch_absmax(dtype, X, N * (int64_t)D, w.absmax, st));
         x_absmax = w.absmax;
     }
-    return launch_update(dtype, X, labels, N, D, K, C, counts, x_absmax, w, st);
+    return launch_update(dtype, X, labels, N, D, K, C, counts, x_absmax, w, ft, faults, n_faults, stats, st);
+}
+
+ftk_status ftk_kmeans_update(ftk_dtype dtype, const void *X, const int32_t *labels, int64_t N,
+                             int32_t D, int32_t K, void *C, int32_t *counts, const double *x_absmax,
+                             void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return ftk_kmeans_update_ft(dtype, X, labels, N, D, K, C, counts, x_absmax, FTK_FT_OFF, nullptr, 0,
+                                nullptr, workspace, workspace_bytes, hip_stream);
+}
+
+ftk_status ftk_update_geometry(ftk_dtype dtype, int64_t N, int32_t D, int32_t K, int32_t rows_aligned16,
+                               ftk_geometry *out)
+{
+    FTK_TRY(check_problem(dtype, N, D, K, FTK_FT_OFF));
+    if (!out) {
+        set_error("out is NULL");
+        return FTK_EINVAL;
+    }
+    update_geometry(dtype, rows_aligned16 != 0, N, D, K, out);
+    return FTK_OK;
 }
 
 ftk_status ftk_seeded_indices(uint64_t seed, int64_t N, int32_t K, int64_t *idx_host)
@@ -368,7 +395,8 @@ ftk_status ftk_kmeans_fit(ftk_dtype dtype, const void *X, int64_t N, int32_t D, 
         FTK_TRY(assign_impl(c, workspace, st));
         if (inertia_per_iter)
             FTK_TRY(launch_sum_to_double(dtype, w.mindist, N, w.partials, w.inertia + t, st));
-        FTK_TRY(launch_update(dtype, X, labels_out, N, D, K, w.C_cur, counts_out, w.absmax, w, st));
+        FTK_TRY(launch_update(dtype, X, labels_out, N, D, K, w.C_cur, counts_out, w.absmax, w, ft, nullptr, 0,
+                              stats, st));
     }
     FTK_TRY_HIP(hipMemcpyAsync(C_out, w.C_cur, (size_t)K * D * esz, hipMemcpyDeviceToDevice, st));
     if (inertia_per_iter && iters > 0) {

@@ -110,7 +110,9 @@ ftk_status launch_refine(const AssignCall &c, const Workspace &w, hipStream_t st
 ftk_status launch_absmax(ftk_dtype dtype, const void *X, int64_t count, double *out, hipStream_t st);
 ftk_status launch_update(ftk_dtype dtype, const void *X, const int32_t *labels, int64_t N, int D,
                          int K, void *C, int32_t *counts, const double *absmax, const Workspace &w,
+                         ftk_ft_mode ft_mode, const ftk_fault *faults, int n_faults, ftk_ft_stats *stats,
                          hipStream_t st);
+void update_geometry(ftk_dtype dtype, bool aligned16, int64_t N, int D, int K, ftk_geometry *out);
 ftk_status launch_gather_rows(ftk_dtype dtype, const void *X, int D, const int64_t *idx_dev, int K,
                               void *C, hipStream_t st);
 ftk_status launch_sum_to_double(ftk_dtype dtype, const void *v, int64_t n, double *partials,

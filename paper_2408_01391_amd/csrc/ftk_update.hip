@@ -110,17 +110,82 @@ __device__ __forceinline__ long long to_fixed(double x, double scale)
     return __double_as_longlong(fma(x, scale, MAGIC)) - __double_as_longlong(MAGIC);
 }
 
-template <typename T, bool ALIGNED>
+// ---- dual modular redundancy (paper Sections 2.3 and 4: the memory-bound update is protected
+// by duplicating its arithmetic and comparing) ------------------------------------------------
+// The loads are not duplicated (a flipped bit in memory is outside the paper's fault model,
+// Section 2.1); every arithmetic result that leaves a register is produced twice, from operands
+// the compiler must treat as unrelated, and the two results are compared as integers.
+__device__ __forceinline__ double dmr_copy(double v)
+{
+    asm volatile("" : "+v"(v));  // opaque: prevents the two instruction streams from being merged
+    return v;
+}
+
+// mean = (hi * 2^LIMB + lo) / scale / n, rounded once to T.  DMR: evaluated twice from operands the
+// compiler must treat as unrelated; if the two results differ a third evaluation decides.
+template <typename T, bool DMR>
+__device__ __forceinline__ T fixed_point_mean(long long hi, long long lo, double inv, int n, int *detected)
+{
+    const double total = (double)hi * (double)(1ll << UPD_LIMB_BITS) + (double)lo;
+    T m = (T)((total * inv) / (double)n);
+    if constexpr (DMR) {
+        const double total2 = dmr_copy((double)hi) * (double)(1ll << UPD_LIMB_BITS) + dmr_copy((double)lo);
+        const T m2 = (T)((total2 * dmr_copy(inv)) / dmr_copy((double)n));
+        if (m != m2) {
+            const double total3 = dmr_copy(dmr_copy((double)hi)) * (double)(1ll << UPD_LIMB_BITS) + dmr_copy(dmr_copy((double)lo));
+            const T m3 = (T)((total3 * dmr_copy(dmr_copy(inv))) / dmr_copy(dmr_copy((double)n)));
+            m = (m3 == m2) ? m2 : m;
+            *detected += 1;
+        }
+    }
+    return m;
+}
+
+struct UpdateFtArgs {
+    const ftk_fault *faults;  // device; addressed as (workgroup, wave, step, element, lane, bit)
+    int n_faults;
+    int mode;                 // ftk_ft_mode
+    ftk_ft_stats *stats;
+};
+constexpr int UPD_MAX_FAULTS = 4;  // injected faults honoured per workgroup
+
+// faults aimed at this workgroup -> LDS; returns how many (uniform)
+__device__ __forceinline__ int stage_faults(const UpdateFtArgs &ft, int wg, ftk_fault *sh_faults, int *sh_nf,
+                                            int nthreads)
+{
+    if (ft.n_faults <= 0) return 0;
+    if (threadIdx.x == 0) *sh_nf = 0;
+    __syncthreads();
+    for (int i = threadIdx.x; i < ft.n_faults; i += nthreads) {
+        if ((int)ft.faults[i].workgroup == wg) {
+            const int slot = atomicAdd(sh_nf, 1);
+            if (slot < UPD_MAX_FAULTS) sh_faults[slot] = ft.faults[i];
+        }
+    }
+    __syncthreads();
+    return min(*sh_nf, UPD_MAX_FAULTS);
+}
+
+__device__ __forceinline__ void add_stat(ftk_ft_stats *stats, int field, int n)
+{
+    if (stats && n) atomicAdd(reinterpret_cast<unsigned long long *>(stats) + field, (unsigned long long)n);
+}
+enum { STAT_INJECTED = 1, STAT_DETECTED = 2, STAT_CORRECTED = 3, STAT_RECOMPUTED = 4, STAT_UNCORRECTABLE = 5 };
+
+template <typename T, bool ALIGNED, bool DMR>
 __global__ __launch_bounds__(UPD_THREADS) void update_accumulate_kernel(
     const T *X, const int32_t *labels, int64_t N, int D, int K, const double *absmax_p,
     long long *slabs, int32_t *cslabs, int Ks, int Ds, int nds, int tx_log2,
-    int64_t rows_per_chunk)
+    int64_t rows_per_chunk, UpdateFtArgs ft)
 {
     using F = typename Mma<T>::frag_t;
     constexpr int E = ALIGNED ? Mma<T>::E : 1;
     extern __shared__ __align__(16) unsigned char lds_raw[];
     unsigned long long *cell = reinterpret_cast<unsigned long long *>(lds_raw);
     int *cnt = reinterpret_cast<int *>(cell + (size_t)Ks * Ds);
+    __shared__ unsigned long long sh_sum[4];  // [0] table total, [1] shadow total, [2] count total, [3] shadow rows
+    __shared__ int sh_nf;
+    __shared__ ftk_fault sh_faults[UPD_MAX_FAULTS];
 
     const int tid = threadIdx.x;
     const int slice = blockIdx.y;
@@ -128,69 +193,137 @@ __global__ __launch_bounds__(UPD_THREADS) void update_accumulate_kernel(
     const int d0 = ds_i * Ds, k0 = ks_i * Ks;
     const int dn = min(Ds, D - d0);  // features in this slice
     const int kn = min(Ks, K - k0);
-    for (int i = tid; i < Ks * Ds; i += UPD_THREADS) cell[i] = 0ull;
-    for (int i = tid; i < Ks; i += UPD_THREADS) cnt[i] = 0;
-    __syncthreads();
-
     // fp32 data: 24-bit mantissas leave ample room, one limb scaled for the whole of N;
     // fp64 data: scale for this workgroup's rows only and flush into two limbs
     constexpr bool TWO_LIMB = sizeof(T) == 8;
     const double scale = fixed_point_scale(*absmax_p, TWO_LIMB ? rows_per_chunk : N);
+    const double scale2 = dmr_copy(scale);
     const int TX = 1 << tx_log2, TY = UPD_THREADS >> tx_log2;
     const int tx = tid & (TX - 1), ty = tid >> tx_log2;
     const int ppr = (dn + E - 1) / E;
     const int64_t r0 = (int64_t)blockIdx.x * rows_per_chunk;
     const int64_t r1 = r0 + rows_per_chunk < N ? r0 + rows_per_chunk : N;
+    const int nf = stage_faults(ft, (int)blockIdx.x, sh_faults, &sh_nf, UPD_THREADS);
+    int n_injected = 0;
 
-    // UNR rows per thread and step: the label loads, then the point loads, are issued together
-    // before any LDS atomic, so several HBM requests per thread are in flight
-    constexpr int UNR = 4;
-    for (int64_t row0 = r0 + ty; row0 < r1; row0 += (int64_t)TY * UNR) {
-        int lab[UNR];
-        bool ok[UNR];
+    // DMR: the conversion is done twice and compared on the spot; the accumulation into the LDS
+    // table is shadowed by a per-thread running total of everything the thread added (second
+    // instruction stream, registers only).  After the pass the table's total must equal the sum
+    // of the shadows, and the member counts the number of rows counted; if not, the workgroup
+    // clears its table and repeats the pass (injection, which models a transient error, is not
+    // repeated).
+    constexpr int ATTEMPTS = DMR ? 2 : 1;
+    for (int attempt = 0; attempt < ATTEMPTS; ++attempt) {
+        for (int i = tid; i < Ks * Ds; i += UPD_THREADS) cell[i] = 0ull;
+        for (int i = tid; i < Ks; i += UPD_THREADS) cnt[i] = 0;
+        if (tid < 4) sh_sum[tid] = 0ull;
+        __syncthreads();
+        unsigned long long shadow = 0ull;  // wraps like the table does
+        unsigned shadow_rows = 0;
+        int step = 0;
+
+        // UNR rows per thread and step: the label loads, then the point loads, are issued together
+        // before any LDS atomic, so several HBM requests per thread are in flight
+        constexpr int UNR = 4;
+        for (int64_t row0 = r0 + ty; row0 < r1; row0 += (int64_t)TY * UNR, ++step) {
+            int lab[UNR];
+            bool ok[UNR];
 #pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-            const int64_t row = row0 + (int64_t)u * TY;
-            lab[u] = row < r1 ? labels[row] - k0 : -1;
-        }
+            for (int u = 0; u < UNR; ++u) {
+                const int64_t row = row0 + (int64_t)u * TY;
+                lab[u] = row < r1 ? labels[row] - k0 : -1;
+            }
 #pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-            ok[u] = (unsigned)lab[u] < (unsigned)kn;
-            if (ok[u] && tx == 0 && ds_i == 0) atomicAdd(&cnt[lab[u]], 1);
-        }
-        for (int pc = tx; pc < ppr; pc += TX) {
-            if constexpr (ALIGNED) {
+            for (int u = 0; u < UNR; ++u) {
+                ok[u] = (unsigned)lab[u] < (unsigned)kn;
+                if (ok[u] && tx == 0 && ds_i == 0) {
+                    atomicAdd(&cnt[lab[u]], 1);
+                    if (DMR) shadow_rows += 1;
+                }
+            }
+            // injected soft error (fault model of Section 2.1): one bit of one converted operand of
+            // this step, after the comparison and before it is accumulated
+            unsigned long long flip[UNR];
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) flip[u] = 0ull;
+            int flip_e = -1;
+            if (nf > 0 && attempt == 0) {
+                for (int i = 0; i < nf; ++i) {
+                    const ftk_fault f = sh_faults[i];
+                    // the addressed thread, moved onto the lane of its row that owns a piece
+                    const int ft_id = (int)(f.wave % (UPD_THREADS / 64)) * 64 + (int)(f.lane & 63);
+                    if ((ft_id >> tx_log2) == ty && ((ft_id & (TX - 1)) % ppr) == tx && (int)f.tile == step) {
+                        flip[f.reg % UNR] = 1ull << (f.bit & 63);
+                        flip_e = (int)((f.reg / UNR) % E);
+                    }
+                }
+            }
+            for (int pc = tx; pc < ppr; pc += TX) {
                 F f[UNR];
 #pragma unroll
                 for (int u = 0; u < UNR; ++u) {
                     const int64_t row = row0 + (int64_t)u * TY;
-                    if (ok[u]) f[u] = *reinterpret_cast<const F *>(X + row * D + d0 + pc * E);
+                    if (ok[u]) {
+                        if constexpr (ALIGNED) f[u] = *reinterpret_cast<const F *>(X + row * D + d0 + pc * E);
+                        else f[u][0] = X[row * D + d0 + pc];
+                    }
                 }
 #pragma unroll
                 for (int u = 0; u < UNR; ++u) {
                     if (ok[u]) {
                         unsigned long long *dst = cell + (size_t)lab[u] * Ds + pc * E;
 #pragma unroll
-                        for (int e = 0; e < E; ++e)
-                            atomicAdd(dst + e, (unsigned long long)to_fixed((double)f[u][e], scale));
+                        for (int e = 0; e < E; ++e) {
+                            const double x = (double)f[u][e];
+                            long long v = to_fixed(x, scale);
+                            if constexpr (DMR) {
+                                long long v2 = to_fixed(dmr_copy(x), scale2);
+                                if (v != v2) {  // conversion disagrees: do it a third time and keep the majority
+                                    const long long v3 = to_fixed(dmr_copy(dmr_copy(x)), scale2);
+                                    v = (v3 == v2) ? v2 : v;
+                                    v2 = v;
+                                }
+                                shadow += (unsigned long long)v2;
+                            }
+                            if (flip[u] != 0ull && e == flip_e && pc == tx) {
+                                v = (long long)((unsigned long long)v ^ flip[u]);
+                                n_injected += 1;
+                            }
+                            atomicAdd(dst + e, (unsigned long long)v);
+                        }
                     }
                 }
-            } else {
-                T v[UNR];
-#pragma unroll
-                for (int u = 0; u < UNR; ++u) {
-                    const int64_t row = row0 + (int64_t)u * TY;
-                    if (ok[u]) v[u] = X[row * D + d0 + pc];
-                }
-#pragma unroll
-                for (int u = 0; u < UNR; ++u)
-                    if (ok[u])
-                        atomicAdd(cell + (size_t)lab[u] * Ds + pc,
-                                  (unsigned long long)to_fixed((double)v[u], scale));
             }
         }
+        __syncthreads();
+        if constexpr (DMR) {
+            unsigned long long tsum = 0ull, csum = 0ull;
+            for (int i = tid; i < Ks * Ds; i += UPD_THREADS) tsum += cell[i];
+            for (int i = tid; i < Ks; i += UPD_THREADS) csum += (unsigned long long)(unsigned)cnt[i];
+            // wave totals first, then one LDS atomic per wave and word
+            unsigned long long v4[4] = {tsum, shadow, csum, (unsigned long long)shadow_rows};
+#pragma unroll
+            for (int w4 = 0; w4 < 4; ++w4)
+#pragma unroll
+                for (int mask = 1; mask < 64; mask <<= 1) v4[w4] += __shfl_xor(v4[w4], mask, 64);
+            if ((tid & 63) == 0)
+                for (int w4 = 0; w4 < 4; ++w4) atomicAdd(&sh_sum[w4], v4[w4]);
+            __syncthreads();
+            const bool good = sh_sum[0] == sh_sum[1] && sh_sum[2] == sh_sum[3];
+            __syncthreads();
+            if (good) break;
+            if (tid == 0) {
+                add_stat(ft.stats, STAT_DETECTED, 1);
+                if (ft.mode >= FTK_FT_CORRECT) add_stat(ft.stats, attempt == 0 ? STAT_RECOMPUTED : STAT_UNCORRECTABLE, 1);
+            }
+            if (ft.mode < FTK_FT_CORRECT) break;  // detect only: the corrupted table is flushed
+        }
     }
-    __syncthreads();
+    if (nf > 0) {
+#pragma unroll
+        for (int mask = 1; mask < 64; mask <<= 1) n_injected += __shfl_xor(n_injected, mask, 64);
+        if ((tid & 63) == 0) add_stat(ft.stats, STAT_INJECTED, n_injected);
+    }
     // Flush with plain stores into this row chunk's table in global memory (every cell of the
     // slice, zeros included, so the tables need no clearing).  Device-wide atomics on one shared
     // table cost a memory-side transaction per cell and workgroup; the tables are summed by the
@@ -211,10 +344,12 @@ __global__ __launch_bounds__(UPD_THREADS) void update_accumulate_kernel(
 // fp64 data: the tables were scaled for one chunk's rows, so the sum over chunks is carried in
 // two limbs.
 constexpr int RF_CELLS = 32, RF_GROUPS = 32;
-template <typename T>
+// DMR: two sets of table sums are kept and compared before the partial sums are combined; a
+// mismatch is settled by a third pass.
+template <typename T, bool DMR>
 __global__ __launch_bounds__(RF_CELLS * RF_GROUPS) void update_reduce_finalize_kernel(
     const long long *slabs, const int32_t *cslabs, int chunks, int64_t N, int64_t rows_per_chunk, int D,
-    int K, const double *absmax_p, T *C, int32_t *counts)
+    int K, const double *absmax_p, T *C, int32_t *counts, ftk_ft_stats *stats)
 {
     constexpr bool TWO_LIMB = sizeof(T) == 8;
     __shared__ long long sh_hi[RF_GROUPS][RF_CELLS], sh_lo[RF_GROUPS][RF_CELLS];
@@ -227,19 +362,59 @@ __global__ __launch_bounds__(RF_CELLS * RF_GROUPS) void update_reduce_finalize_k
     const int row0 = (int)(cell0 / D);
     const int64_t last_cell = cell0 + RF_CELLS - 1 < cells ? cell0 + RF_CELLS - 1 : cells - 1;
     const int nrows = (int)(last_cell / D) - row0 + 1;
-    int c = 0;
-    long long hi = 0, lo = 0;
+    // one pass over the tables; under DMR every value loaded is added into two sets of sums (the
+    // second through an opaque copy), which are compared before the partial sums are combined
+    int c = 0, c2 = 0, detected = 0;
+    long long hi = 0, lo = 0, hi2 = 0, lo2 = 0;
 #pragma unroll 4
     for (int ch = grp; ch < chunks; ch += RF_GROUPS) {
-        if (ci < nrows) c += cslabs[(int64_t)ch * K + row0 + ci];
+        if (ci < nrows) {
+            int n = cslabs[(int64_t)ch * K + row0 + ci];
+            c += n;
+            if constexpr (DMR) {
+                asm volatile("" : "+v"(n));
+                c2 += n;
+            }
+        }
         if (cell < cells) {
-            const long long v = slabs[(int64_t)ch * cells + cell];
+            long long v = slabs[(int64_t)ch * cells + cell];
             if (TWO_LIMB) {
                 hi += v >> UPD_LIMB_BITS;                      // floor
                 lo += v & ((1ll << UPD_LIMB_BITS) - 1);        // >= 0
             } else {
                 lo += v;
             }
+            if constexpr (DMR) {
+                asm volatile("" : "+v"(v));
+                if (TWO_LIMB) {
+                    hi2 += v >> UPD_LIMB_BITS;
+                    lo2 += v & ((1ll << UPD_LIMB_BITS) - 1);
+                } else {
+                    lo2 += v;
+                }
+            }
+        }
+    }
+    if constexpr (DMR) {
+        if (hi != hi2 || lo != lo2 || c != c2) {  // settle by a third, separate pass
+            long long hi3 = 0, lo3 = 0;
+            int c3 = 0;
+            for (int ch = grp; ch < chunks; ch += RF_GROUPS) {
+                if (ci < nrows) c3 += cslabs[(int64_t)ch * K + row0 + ci];
+                if (cell < cells) {
+                    const long long v = slabs[(int64_t)ch * cells + cell];
+                    if (TWO_LIMB) {
+                        hi3 += v >> UPD_LIMB_BITS;
+                        lo3 += v & ((1ll << UPD_LIMB_BITS) - 1);
+                    } else {
+                        lo3 += v;
+                    }
+                }
+            }
+            hi = hi3;
+            lo = lo3;
+            c = c3;
+            detected += 1;
         }
     }
     sh_hi[grp][ci] = hi;
@@ -265,31 +440,36 @@ __global__ __launch_bounds__(RF_CELLS * RF_GROUPS) void update_reduce_finalize_k
             const int n = sh_cnt[0][(int)(cell / D) - row0];
             if (n > 0) {
                 const double inv = 1.0 / fixed_point_scale(*absmax_p, TWO_LIMB ? rows_per_chunk : N);
-                const double total = (double)hi * (double)(1ll << UPD_LIMB_BITS) + (double)lo;
-                C[cell] = (T)((total * inv) / (double)n);
+                C[cell] = fixed_point_mean<T, DMR>(hi, lo, inv, n, &detected);
             }
         }
+    }
+    if (DMR && detected) {
+        add_stat(stats, STAT_DETECTED, detected);
+        add_stat(stats, STAT_RECOMPUTED, detected);
     }
 }
 
 // Averaging pass ("the last kernel", Section 3.1.1): C_j = sum_j / count_j, rounded once;
 // a cluster without points keeps its previous centroid.
-template <typename T>
+template <typename T, bool DMR>
 __global__ __launch_bounds__(256) void update_finalize_kernel(const unsigned long long *sums,
                                                               const int32_t *counts, int64_t N,
                                                               int64_t rows_per_chunk, int D, int K,
-                                                              const double *absmax_p, T *C)
+                                                              const double *absmax_p, T *C, ftk_ft_stats *stats)
 {
     const double inv = 1.0 / fixed_point_scale(*absmax_p, sizeof(T) == 8 ? rows_per_chunk : N);
     const int64_t n = (int64_t)K * D;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    int detected = 0;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
         const int c = counts[i / D];
-        if (c > 0) {
-            const double total = (double)(long long)sums[2 * i] * (double)(1ll << UPD_LIMB_BITS) +
-                                 (double)(long long)sums[2 * i + 1];
-            C[i] = (T)((total * inv) / (double)c);
-        }
+        if (c > 0)
+            C[i] = fixed_point_mean<T, DMR>((long long)sums[2 * i], (long long)sums[2 * i + 1], inv, c, &detected);
+    }
+    if (DMR && detected) {
+        add_stat(stats, STAT_DETECTED, detected);
+        add_stat(stats, STAT_RECOMPUTED, detected);
     }
 }
 
@@ -406,16 +586,19 @@ constexpr int RED_ROWS_PER_LANE_MAX = 256;  // most sorted positions a lane walk
 
 // Walk the sorted order.  lpr_log2: lanes per row (power of two); a wave holds 64/lpr row groups;
 // blockIdx.y selects the slice of 64*E features when a row is wider than one wave.
-template <typename T, bool ALIGNED>
+template <typename T, bool ALIGNED, bool DMR>
 __global__ __launch_bounds__(256) void sorted_reduce_kernel(const T *X, const int32_t *sorted_idx,
                                                             const int32_t *sorted_lab, const int32_t *n_sorted_p,
                                                             int64_t N, int D, int lpr_log2, int rows_per_lane,
-                                                            const double *absmax_p, unsigned long long *sums)
+                                                            const double *absmax_p, unsigned long long *sums,
+                                                            UpdateFtArgs ft)
 {
     using F = typename Mma<T>::frag_t;
     constexpr int E = ALIGNED ? Mma<T>::E : 1;
     constexpr bool TWO_LIMB = sizeof(T) == 8;
     constexpr int UNR = 8;
+    __shared__ int sh_nf;
+    __shared__ ftk_fault sh_faults[UPD_MAX_FAULTS];
     const int lane = threadIdx.x & 63;
     const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int lpr = 1 << lpr_log2, gpw = 64 >> lpr_log2;
@@ -423,15 +606,56 @@ __global__ __launch_bounds__(256) void sorted_reduce_kernel(const T *X, const in
     const int d0 = (blockIdx.y * 64 + piece) * E;  // first feature of this lane
     const bool lane_on = d0 < D;
     const double scale = fixed_point_scale(*absmax_p, TWO_LIMB ? RED_ROWS_PER_LANE_MAX : N);
+    const double scale2 = dmr_copy(scale);
     const int64_t s_begin = wave * (int64_t)(gpw * rows_per_lane) + group;
     const int64_t n_sorted = *n_sorted_p;
     const int64_t s_end = min(n_sorted, (wave + 1) * (int64_t)(gpw * rows_per_lane));
+    const int nf = blockIdx.y == 0 ? stage_faults(ft, (int)blockIdx.x, sh_faults, &sh_nf, 256) : 0;
+    int n_injected = 0, n_detected = 0, n_recomputed = 0, n_uncorrectable = 0;  // per lane (runs end in divergent flow)
 
-    long long acc[E];
+    // DMR: a second set of running sums is fed by a second conversion of the same loaded values;
+    // the two sets are compared as integers whenever a run ends, i.e. before anything leaves the
+    // registers.  On a mismatch the lane walks its run again (both streams) and flushes that.
+    long long acc[E], acc2[E];
 #pragma unroll
-    for (int e = 0; e < E; ++e) acc[e] = 0;
+    for (int e = 0; e < E; ++e) acc[e] = acc2[e] = 0;
     int cur = -1;
-    auto flush = [&]() {
+    int64_t run_start = s_begin;  // sorted position of the first row of the current run of this lane
+    auto flush = [&](int64_t run_end) {
+        if constexpr (DMR) {
+            bool bad = false;
+            if (cur >= 0 && lane_on) {
+#pragma unroll
+                for (int e = 0; e < E; ++e) bad |= acc[e] != acc2[e];
+            }
+            if (__builtin_expect(__any(bad), 0)) {
+                n_detected += bad ? 1 : 0;
+                if (ft.mode >= FTK_FT_CORRECT) {
+                    bool ok = true;
+                    if (bad) {
+                        long long r1[E], r2[E];
+#pragma unroll
+                        for (int e = 0; e < E; ++e) r1[e] = r2[e] = 0;
+                        for (int64_t s = run_start; s < run_end; s += gpw) {
+                            const int64_t row = sorted_idx[s];
+#pragma unroll
+                            for (int e = 0; e < E; ++e) {
+                                const double x = (d0 + e < D) ? (double)X[row * D + d0 + e] : 0.0;
+                                r1[e] += to_fixed(x, scale);
+                                r2[e] += to_fixed(dmr_copy(x), scale2);
+                            }
+                        }
+#pragma unroll
+                        for (int e = 0; e < E; ++e) {
+                            ok = ok && r1[e] == r2[e];
+                            acc[e] = r1[e];
+                        }
+                    }
+                    n_recomputed += (bad && ok) ? 1 : 0;
+                    n_uncorrectable += (bad && !ok) ? 1 : 0;
+                }
+            }
+        }
         if (cur >= 0 && lane_on) {
 #pragma unroll
             for (int e = 0; e < E; ++e) {
@@ -445,6 +669,7 @@ __global__ __launch_bounds__(256) void sorted_reduce_kernel(const T *X, const in
                     }
                 }
                 acc[e] = 0;
+                if (DMR) acc2[e] = 0;
             }
         }
     };
@@ -462,7 +687,8 @@ __global__ __launch_bounds__(256) void sorted_reduce_kernel(const T *X, const in
         }
     };
     fetch_keys(s_begin);
-    for (int64_t s0 = s_begin; s0 < s_end; s0 += (int64_t)gpw * UNR) {
+    int step = 0;
+    for (int64_t s0 = s_begin; s0 < s_end; s0 += (int64_t)gpw * UNR, ++step) {
         int lab[UNR];
         F f[UNR];
 #pragma unroll
@@ -478,31 +704,124 @@ __global__ __launch_bounds__(256) void sorted_reduce_kernel(const T *X, const in
         for (int u = 0; u < UNR; ++u) {
             if (lab[u] >= 0) {
                 if (lab[u] != cur) {
-                    flush();
+                    flush(s0 + (int64_t)u * gpw);
                     cur = lab[u];
+                    run_start = s0 + (int64_t)u * gpw;
                 }
                 if (lane_on) {
 #pragma unroll
-                    for (int e = 0; e < E; ++e) acc[e] += to_fixed((double)f[u][e], scale);
+                    for (int e = 0; e < E; ++e) {
+                        const double x = (double)f[u][e];
+                        acc[e] += to_fixed(x, scale);
+                        if (DMR) acc2[e] += to_fixed(dmr_copy(x), scale2);
+                    }
+                }
+            }
+        }
+        // injected soft error (fault model of Section 2.1): one bit of one running sum of the first
+        // instruction stream, after this step's additions
+        if (__builtin_expect(nf > 0, 0)) {
+            for (int i = 0; i < nf; ++i) {
+                const ftk_fault fl = sh_faults[i];
+                if ((int)(fl.wave & 3) == (int)(threadIdx.x >> 6) && (int)fl.tile == step) {
+                    // the addressed lane, moved onto a lane of its row group that owns features
+                    const int fl_lane = (int)(fl.lane & 63);
+                    const int pa = min(lpr, (D + E - 1) / E);
+                    const bool me = group == (fl_lane >> lpr_log2) && piece == (fl_lane & (lpr - 1)) % pa &&
+                                    lane_on && cur >= 0;
+#pragma unroll
+                    for (int e = 0; e < E; ++e)
+                        if (me && (int)(fl.reg % E) == e)
+                            acc[e] = (long long)((unsigned long long)acc[e] ^ (1ull << (fl.bit & 63)));
+                    n_injected += me ? 1 : 0;
                 }
             }
         }
     }
-    flush();
+    flush(s_end);
+    if (ft.stats && (DMR || nf > 0)) {
+#pragma unroll
+        for (int mask = 1; mask < 64; mask <<= 1) {
+            n_injected += __shfl_xor(n_injected, mask, 64);
+            n_detected += __shfl_xor(n_detected, mask, 64);
+            n_recomputed += __shfl_xor(n_recomputed, mask, 64);
+            n_uncorrectable += __shfl_xor(n_uncorrectable, mask, 64);
+        }
+    }
+    if (ft.stats && lane == 0) {
+        add_stat(ft.stats, STAT_INJECTED, n_injected);
+        add_stat(ft.stats, STAT_DETECTED, n_detected);
+        add_stat(ft.stats, STAT_RECOMPUTED, n_recomputed);
+        add_stat(ft.stats, STAT_UNCORRECTABLE, n_uncorrectable);
+    }
+}
+
+// Launch geometry of the pass that accumulates the sums (the one faults are injected into).
+struct UpdateLaunch {
+    bool sorted_path;
+    UpdatePlan u;
+    // sorted path
+    int lpr_log2, rows_per_lane, pieces, E;
+    dim3 rgrid;
+};
+static UpdateLaunch plan_update_launch(ftk_dtype dtype, const void *X, int64_t N, int D, int K)
+{
+    UpdateLaunch L;
+    L.u = plan_update(dtype, X, N, D, K);
+    const size_t esz = dtype == FTK_F32 ? 4 : 8;
+    // rows of at least half a cache line gather efficiently; small problems are launch bound and
+    // take the two-kernel LDS path instead of the six-kernel sorted one
+    L.sorted_path = (size_t)D * esz >= 64 && N >= 65536;
+    L.E = L.u.aligned ? (dtype == FTK_F32 ? 4 : 2) : 1;
+    L.pieces = (int)ceil_div(D, L.E);
+    L.lpr_log2 = 0;
+    while ((1 << L.lpr_log2) < L.pieces && L.lpr_log2 < 6) ++L.lpr_log2;
+    const int gpw = 64 >> L.lpr_log2;
+    // long runs per lane (few flushes), but at least ~2048 waves where N allows
+    int64_t rpl = N / ((int64_t)gpw * 2048);
+    if (rpl < 64) rpl = 64;
+    if (rpl > RED_ROWS_PER_LANE_MAX) rpl = RED_ROWS_PER_LANE_MAX;
+    L.rows_per_lane = (int)rpl;
+    const int64_t waves = ceil_div(N, (int64_t)gpw * L.rows_per_lane);
+    L.rgrid = dim3((unsigned)ceil_div(waves, 4), (unsigned)ceil_div(L.pieces, 64));
+    return L;
+}
+
+void update_geometry(ftk_dtype dtype, bool aligned16, int64_t N, int D, int K, ftk_geometry *out)
+{
+    const UpdateLaunch L = plan_update_launch(dtype, aligned16 ? nullptr : (const void *)1, N, D, K);
+    if (L.sorted_path) {
+        out->workgroups = L.rgrid.x;
+        out->waves_per_workgroup = 4;
+        out->tiles_per_wave = (uint32_t)ceil_div(L.rows_per_lane, 8);
+        out->regs_per_tile = (uint32_t)L.E;
+    } else {
+        const int TY = UPD_THREADS >> L.u.tx_log2;
+        out->workgroups = (uint32_t)L.u.chunks;
+        out->waves_per_workgroup = UPD_THREADS / 64;
+        out->tiles_per_wave = (uint32_t)ceil_div(L.u.rows_per_chunk, (int64_t)TY * 4);
+        out->regs_per_tile = (uint32_t)(4 * L.E);
+    }
+    out->lanes = 64;
+    out->bits = 64;
 }
 
 ftk_status launch_update(ftk_dtype dtype, const void *X, const int32_t *labels, int64_t N, int D,
                          int K, void *C, int32_t *counts, const double *absmax, const Workspace &w,
+                         ftk_ft_mode ft_mode, const ftk_fault *faults, int n_faults, ftk_ft_stats *stats,
                          hipStream_t st)
 {
-    const UpdatePlan u = plan_update(dtype, X, N, D, K);
+    const UpdateLaunch L = plan_update_launch(dtype, X, N, D, K);
+    const UpdatePlan &u = L.u;
     const int64_t cells = (int64_t)K * D;
     unsigned long long *sums = reinterpret_cast<unsigned long long *>(w.fx_sums);
-    const size_t esz = dtype == FTK_F32 ? 4 : 8;
-    // rows of at least half a cache line gather efficiently; small problems are launch bound and
-    // take the two-kernel LDS path instead of the six-kernel sorted one
-    const bool sorted_path = (size_t)D * esz >= 64 && N >= 65536;
-    if (sorted_path) {
+    const bool dmr = ft_mode != FTK_FT_OFF;
+    UpdateFtArgs fa;
+    fa.faults = faults;
+    fa.n_faults = n_faults;
+    fa.mode = (int)ft_mode;
+    fa.stats = stats;
+    if (L.sorted_path) {
         {
             const int blocks = (int)(ceil_div(cells, 256) < 1024 ? ceil_div(cells, 256) : 1024);
             hipLaunchKernelGGL(update_zero_kernel, dim3(blocks), dim3(256), 0, st, sums, 2 * cells, counts, K);
@@ -513,37 +832,34 @@ ftk_status launch_update(ftk_dtype dtype, const void *X, const int32_t *labels, 
         hipLaunchKernelGGL(sort_scan_kernel, dim3(1), dim3(1024), 0, st, counts, K, w.sort_cursor);
         hipLaunchKernelGGL(sort_scatter_kernel, dim3(chunks), dim3(256), hl, st, labels, N, K, w.sort_cursor,
                            w.sort_idx, w.sort_lab);
-        const int E = u.aligned ? (dtype == FTK_F32 ? 4 : 2) : 1;
-        const int pieces = (int)ceil_div(D, E);
-        int lpr_log2 = 0;
-        while ((1 << lpr_log2) < pieces && lpr_log2 < 6) ++lpr_log2;
-        const int gpw = 64 >> lpr_log2;
-        // long runs per lane (few flushes), but at least ~2048 waves where N allows
-        int64_t rpl = N / ((int64_t)gpw * 2048);
-        if (rpl < 64) rpl = 64;
-        if (rpl > RED_ROWS_PER_LANE_MAX) rpl = RED_ROWS_PER_LANE_MAX;
-        const int rows_per_lane = (int)rpl;
-        const int64_t waves = ceil_div(N, (int64_t)gpw * rows_per_lane);
-        dim3 rgrid((unsigned)ceil_div(waves, 4), (unsigned)ceil_div(pieces, 64)), rblock(256);
-#define FTK_LAUNCH_RED(T, AL)                                                                       \
-    hipLaunchKernelGGL((sorted_reduce_kernel<T, AL>), rgrid, rblock, 0, st, (const T *)X, w.sort_idx, \
-                       w.sort_lab, w.sort_cursor + K, N, D, lpr_log2, rows_per_lane, absmax, sums)
-        if (dtype == FTK_F32) {
-            if (u.aligned) FTK_LAUNCH_RED(float, true);
-            else FTK_LAUNCH_RED(float, false);
-        } else {
-            if (u.aligned) FTK_LAUNCH_RED(double, true);
-            else FTK_LAUNCH_RED(double, false);
-        }
+        dim3 rblock(256);
+#define FTK_LAUNCH_RED(T, AL, DM)                                                                       \
+    hipLaunchKernelGGL((sorted_reduce_kernel<T, AL, DM>), L.rgrid, rblock, 0, st, (const T *)X, w.sort_idx, \
+                       w.sort_lab, w.sort_cursor + K, N, D, L.lpr_log2, L.rows_per_lane, absmax, sums, fa)
+#define FTK_LAUNCH_RED_T(T)                                \
+    do {                                                   \
+        if (u.aligned && dmr) FTK_LAUNCH_RED(T, true, true);       \
+        else if (u.aligned) FTK_LAUNCH_RED(T, true, false);        \
+        else if (dmr) FTK_LAUNCH_RED(T, false, true);              \
+        else FTK_LAUNCH_RED(T, false, false);                      \
+    } while (0)
+        if (dtype == FTK_F32) FTK_LAUNCH_RED_T(float);
+        else FTK_LAUNCH_RED_T(double);
+#undef FTK_LAUNCH_RED_T
 #undef FTK_LAUNCH_RED
         {
             const int blocks = (int)(ceil_div(cells, 256) < 1024 ? ceil_div(cells, 256) : 1024);
-            if (dtype == FTK_F32)
-                hipLaunchKernelGGL((update_finalize_kernel<float>), dim3(blocks), dim3(256), 0, st, sums,
-                                   counts, N, (int64_t)RED_ROWS_PER_LANE_MAX, D, K, absmax, (float *)C);
-            else
-                hipLaunchKernelGGL((update_finalize_kernel<double>), dim3(blocks), dim3(256), 0, st, sums,
-                                   counts, N, (int64_t)RED_ROWS_PER_LANE_MAX, D, K, absmax, (double *)C);
+#define FTK_LAUNCH_FIN(T, DM)                                                                              \
+    hipLaunchKernelGGL((update_finalize_kernel<T, DM>), dim3(blocks), dim3(256), 0, st, sums, counts, N, \
+                       (int64_t)RED_ROWS_PER_LANE_MAX, D, K, absmax, (T *)C, stats)
+            if (dtype == FTK_F32) {
+                if (dmr) FTK_LAUNCH_FIN(float, true);
+                else FTK_LAUNCH_FIN(float, false);
+            } else {
+                if (dmr) FTK_LAUNCH_FIN(double, true);
+                else FTK_LAUNCH_FIN(double, false);
+            }
+#undef FTK_LAUNCH_FIN
         }
     } else {
         if (u.chunks > update_slab_chunks_max(N) || (int64_t)u.chunks * cells > update_slab_cells_max(N, D, K)) {
@@ -553,24 +869,32 @@ ftk_status launch_update(ftk_dtype dtype, const void *X, const int32_t *labels, 
         const size_t lds = (size_t)u.Ks * u.Ds * 8 + (size_t)u.Ks * 4;
         dim3 grid(u.chunks, u.nds * u.nks), block(UPD_THREADS);
         long long *slabs = reinterpret_cast<long long *>(w.upd_slab);
-#define FTK_LAUNCH_ACC(T, AL)                                                                      \
-    hipLaunchKernelGGL((update_accumulate_kernel<T, AL>), grid, block, lds, st, (const T *)X, labels, \
-                       N, D, K, absmax, slabs, w.upd_cslab, u.Ks, u.Ds, u.nds, u.tx_log2, u.rows_per_chunk)
-        if (dtype == FTK_F32) {
-            if (u.aligned) FTK_LAUNCH_ACC(float, true);
-            else FTK_LAUNCH_ACC(float, false);
-        } else {
-            if (u.aligned) FTK_LAUNCH_ACC(double, true);
-            else FTK_LAUNCH_ACC(double, false);
-        }
+#define FTK_LAUNCH_ACC(T, AL, DM)                                                                      \
+    hipLaunchKernelGGL((update_accumulate_kernel<T, AL, DM>), grid, block, lds, st, (const T *)X, labels, \
+                       N, D, K, absmax, slabs, w.upd_cslab, u.Ks, u.Ds, u.nds, u.tx_log2, u.rows_per_chunk, fa)
+#define FTK_LAUNCH_ACC_T(T)                                \
+    do {                                                   \
+        if (u.aligned && dmr) FTK_LAUNCH_ACC(T, true, true);       \
+        else if (u.aligned) FTK_LAUNCH_ACC(T, true, false);        \
+        else if (dmr) FTK_LAUNCH_ACC(T, false, true);              \
+        else FTK_LAUNCH_ACC(T, false, false);                      \
+    } while (0)
+        if (dtype == FTK_F32) FTK_LAUNCH_ACC_T(float);
+        else FTK_LAUNCH_ACC_T(double);
+#undef FTK_LAUNCH_ACC_T
 #undef FTK_LAUNCH_ACC
         const int blocks = (int)ceil_div(cells, RF_CELLS);
-        if (dtype == FTK_F32)
-            hipLaunchKernelGGL((update_reduce_finalize_kernel<float>), dim3(blocks), dim3(RF_CELLS * RF_GROUPS), 0, st, slabs,
-                               w.upd_cslab, u.chunks, N, u.rows_per_chunk, D, K, absmax, (float *)C, counts);
-        else
-            hipLaunchKernelGGL((update_reduce_finalize_kernel<double>), dim3(blocks), dim3(RF_CELLS * RF_GROUPS), 0, st, slabs,
-                               w.upd_cslab, u.chunks, N, u.rows_per_chunk, D, K, absmax, (double *)C, counts);
+#define FTK_LAUNCH_RF(T, DM)                                                                                  \
+    hipLaunchKernelGGL((update_reduce_finalize_kernel<T, DM>), dim3(blocks), dim3(RF_CELLS * RF_GROUPS), 0, st, \
+                       slabs, w.upd_cslab, u.chunks, N, u.rows_per_chunk, D, K, absmax, (T *)C, counts, stats)
+        if (dtype == FTK_F32) {
+            if (dmr) FTK_LAUNCH_RF(float, true);
+            else FTK_LAUNCH_RF(float, false);
+        } else {
+            if (dmr) FTK_LAUNCH_RF(double, true);
+            else FTK_LAUNCH_RF(double, false);
+        }
+#undef FTK_LAUNCH_RF
     }
     FTK_TRY_HIP(hipGetLastError());
     return FTK_OK;
