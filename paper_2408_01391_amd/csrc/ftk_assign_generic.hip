@@ -209,6 +209,7 @@ __global__ __launch_bounds__(256, GenericCfg<T>::WAVES_PER_SIMD) void assign_gen
 
     for (int kc = 0; kc < a.nkc; ++kc) {
         const int jbase = kc * KC;
+        const int kt_act = min(KT, (a.K - jbase + TM - 1) / TM);  // tiles of this chunk with real centroids
         acc_t acc[PT][KT];
         {
             const T *const hl = reinterpret_cast<const T *>(lds_hcn) + (kc & 1) * KC;
@@ -276,14 +277,18 @@ __global__ __launch_bounds__(256, GenericCfg<T>::WAVES_PER_SIMD) void assign_gen
                     for (int t = 0; t < KT; ++t)
                         av[t] = *reinterpret_cast<const frag_t *>(
                             sbuf + (t * TM + lane % TM) * SB + q * (8 * (int)sizeof(T)) + g * 16);
-                    // KT*PT independent accumulator chains interleave on the matrix pipe
+                    // tiles that hold only padding rows (K small, or the last chunk) are skipped;
+                    // their accumulators keep the start value of a zero row, exactly zero
 #pragma unroll
-                    for (int e = 0; e < E; ++e)
+                    for (int t = 0; t < KT; ++t) {
+                        if (t < kt_act) {
 #pragma unroll
-                        for (int t = 0; t < KT; ++t)
+                            for (int e = 0; e < E; ++e)
 #pragma unroll
-                            for (int pt = 0; pt < PT; ++pt)
-                                acc[pt][t] = M::mma(av[t][e], xs[pt][q][e], acc[pt][t]);
+                                for (int pt = 0; pt < PT; ++pt)
+                                    acc[pt][t] = M::mma(av[t][e], xs[pt][q][e], acc[pt][t]);
+                        }
+                    }
                 }
             }
 #pragma unroll
@@ -421,6 +426,7 @@ __global__ __launch_bounds__(256, GenericCfg<T>::WAVES_PER_SIMD) void assign_gen
             for (int pt = 0; pt < PT; ++pt) {
 #pragma unroll
                 for (int t = 0; t < KT; ++t) {
+                    if (TAIL && t >= kt_act) continue;
                     if constexpr (TAIL) {
 #pragma unroll
                         for (int r = 0; r < R; ++r)

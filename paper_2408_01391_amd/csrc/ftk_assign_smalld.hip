@@ -608,6 +608,8 @@ void plan_smalld(int64_t N, int D, int K, ftk_ft_mode ft, AssignPlan &p)
     // chunk: as many tiles as fit 72 KB of LDS (two workgroups per CU), all of them if possible
     int tpc = (72 * 1024) / tile_bytes;
     if (tpc > tiles_total) tpc = tiles_total;
+    // equal chunks: the same number of passes, but no short last chunk paying a full stage
+    tpc = (int)ceil_div(tiles_total, ceil_div(tiles_total, tpc));
     p.kch = tpc * 32;
     p.KC = tpc * 32;
     p.nkc = (int)ceil_div(tiles_total, tpc);
