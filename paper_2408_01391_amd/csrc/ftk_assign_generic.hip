@@ -48,35 +48,46 @@ struct GenericArgs {
 
 constexpr int GENERIC_MAX_FAULTS = 4;
 
-// Safety factor on the noise model of the checksum residual.  fp32: with the reference and the
-// score total carried in double (only quad- and tile-sized partial sums are rounded in fp32),
-// fault-free residuals measured on the workloads and test shapes stay below 0.04 of the model, so
-// 0.12 leaves a factor of three.  fp64 has no wider type to carry the totals in; its residuals
-// reach 0.06 of the model, hence 0.3.  A false alarm is harmless (the point is recomputed
-// exactly), while a smaller threshold narrows the band of points that must be settled exactly
-// when checking is on.
+// Detection threshold = coefficient * u * B, B = ||x|| max||c|| + max||c||^2/2, for a check over
+// n = KC scores of D features.  The coefficient models the rounding noise of a fault-free
+// residual and carries a safety factor calibrated on the workloads and test shapes (largest
+// fault-free residuals stay below a third of the threshold); a false alarm is harmless (the
+// point is recomputed exactly), while a smaller threshold narrows the band of points that strict
+// mode must settle exactly.
+//   fp32: the reference and the score total are carried in double, so what is rounded in fp32 is
+//     the n scores themselves (independent, each ~sqrt(D) u B), the tile sums of 16 scores, and
+//     the quad-sized partial products of the reference against a checksum row of magnitude
+//     n |c| (plus that row's own rounding):  sqrt(n) (sqrt(D+4) + 4) + 3 n / sqrt(D+4).
+//   fp64: no wider type to carry the totals in; the running sums of n-fold magnitude dominate:
+//     n (sqrt(n) + sqrt(D+4)).
 template <typename T>
-constexpr double generic_ft_kappa() { return sizeof(T) == 4 ? 0.12 : 0.3; }
+static double generic_ft_coef(int n, int D)
+{
+    const double dn = (double)n, dd = std::sqrt((double)D + 4.0);
+    if (sizeof(T) == 4) return 1.7 * (std::sqrt(dn) * (dd + 4.0) + 3.0 * dn / dd);
+    return 0.3 * dn * (std::sqrt(dn) + dd);
+}
 
+// Blocking per wave: PT = 2 point tiles by KT centroid tiles of accumulators, DQ quads per LDS
+// stage, and the waves per SIMD the register budget is sized for.  KT = 4 is the workhorse (fp64
+// tiles are 16x16, so it leaves room for a third resident wave).  For K of at most one or two
+// tiles the stages hold little matrix work and the kernel is bound by the latency of the point
+// loads; KT = 1 / 2 free the accumulator registers for more resident waves, i.e. more loads in
+// flight.
+template <typename T, int KT_>
+struct GenericCfg {
+    static constexpr int PT = 2, KT = KT_, WAVES = 4, DQ = 2;
+    static constexpr int WAVES_PER_SIMD = KT_ == 4 ? (sizeof(T) == 4 ? 2 : 3) : (KT_ == 2 ? 3 : 4);
+};
+// number of accumulator tiles used for a problem with K centroids
 template <typename T>
-struct GenericCfg;
-// PT point tiles by KT centroid tiles of accumulators per wave, DQ quads per LDS stage, and the
-// waves per SIMD the register budget is sized for.  fp64 tiles are 16x16, so the same 4x2 blocking
-// leaves room for a third resident wave.
-template <>
-struct GenericCfg<float> {
-    static constexpr int PT = 2, KT = 4, WAVES = 4, DQ = 2, WAVES_PER_SIMD = 2;
-};
-template <>
-struct GenericCfg<double> {
-    static constexpr int PT = 2, KT = 4, WAVES = 4, DQ = 2, WAVES_PER_SIMD = 3;
-};
+constexpr int generic_kt(int K) { return K <= Mma<T>::TM ? 1 : (K <= 2 * Mma<T>::TM ? 2 : 4); }
 
-template <typename T, bool ALIGNED, bool FT>
-__global__ __launch_bounds__(256, GenericCfg<T>::WAVES_PER_SIMD) void assign_generic_kernel(GenericArgs<T> a)
+template <typename T, int KTV, bool ALIGNED, bool FT>
+__global__ __launch_bounds__(256, (GenericCfg<T, KTV>::WAVES_PER_SIMD)) void assign_generic_kernel(GenericArgs<T> a)
 {
     using M = Mma<T>;
-    using Cfg = GenericCfg<T>;
+    using Cfg = GenericCfg<T, KTV>;
     using frag_t = typename M::frag_t;
     using acc_t = typename M::acc_t;
     constexpr int TM = M::TM, TN = M::TN, G = M::G, R = M::R, E = M::E;
@@ -149,8 +160,9 @@ __global__ __launch_bounds__(256, GenericCfg<T>::WAVES_PER_SIMD) void assign_gen
     constexpr int PPR = DQ * 8 / E;                      // 16-byte pieces per staged row
     constexpr int SB = DQ * 8 * (int)sizeof(T) + 16;     // row stride in bytes (bank spread)
     constexpr int STAGE_BYTES = (KC + 1) * SB;
-    constexpr int NP = KC * PPR / 256;                   // pieces per thread per stage
-    static_assert(KC * PPR % 256 == 0, "stage must divide evenly over the workgroup");
+    constexpr int NPIECES = KC * PPR;                    // 16-byte pieces per stage
+    constexpr int NP = (NPIECES + 255) / 256;            // pieces per thread per stage
+    static_assert(NPIECES % 256 == 0 || NPIECES < 256, "whole rounds over the workgroup, or a single partial one");
     static_assert(KC / E <= 64 && PPR <= 64, "extra pieces: half-norms on wave 0, checksum row on wave 1");
     unsigned char *const lds_hcn = lds_raw + 2 * STAGE_BYTES;
     // per-lane parking slots for the accumulators of the best tile so far ([pt][piece][thread])
@@ -163,7 +175,7 @@ __global__ __launch_bounds__(256, GenericCfg<T>::WAVES_PER_SIMD) void assign_gen
         const int q0 = dc * DQ;
 #pragma unroll
         for (int i = 0; i < NP; ++i) {
-            const int idx = tid + 256 * i;
+            const int idx = min(tid + 256 * i, NPIECES - 1);  // surplus threads repeat the last piece (not stored)
             const int rrow = idx / PPR, pc = idx % PPR;
             const int j = kc * KC + rrow;
             const int d0 = q0 * 8 + pc * E;
@@ -182,7 +194,8 @@ __global__ __launch_bounds__(256, GenericCfg<T>::WAVES_PER_SIMD) void assign_gen
 #pragma unroll
         for (int i = 0; i < NP; ++i) {
             const int idx = tid + 256 * i;
-            *reinterpret_cast<frag_t *>(base + (idx / PPR) * SB + (idx % PPR) * 16) = pf[i];
+            if (NPIECES % 256 == 0 || idx < NPIECES)
+                *reinterpret_cast<frag_t *>(base + (idx / PPR) * SB + (idx % PPR) * 16) = pf[i];
         }
         if (dc == 0 && tid < KC / E)
             *reinterpret_cast<frag_t *>(lds_hcn + ((kc & 1) * KC + tid * E) * (int)sizeof(T)) = pfx;
@@ -637,25 +650,25 @@ static ftk_status launch_generic_t(const AssignCall &c, const AssignPlan &p, con
     a.faults = c.faults;
     a.n_faults = c.n_faults;
     a.ft_mode = (int)c.ft;
-    // Residual "KC scores minus carried checksum" of a fault-free chunk is rounding noise: about
-    // u B n (sqrt(n) + sqrt(D)) for n = KC terms of magnitude up to B (vector sum, checksum
-    // product of magnitude n B, and the scores themselves); factor generic_ft_kappa() on top.
-    {
-        const double n = (double)p.KC;
-        a.ft_coef = generic_ft_kappa<T>() * Mma<T>::kEps * n * (std::sqrt(n) + std::sqrt((double)c.D + 4.0));
-        a.widen_coef = c.ft == FTK_FT_STRICT ? a.ft_coef : 0.0;
-    }
+    a.ft_coef = generic_ft_coef<T>(p.KC, c.D) * Mma<T>::kEps;
+    a.widen_coef = c.ft == FTK_FT_STRICT ? a.ft_coef : 0.0;
     const bool aligned = (c.D % Mma<T>::E == 0) && ((uintptr_t)c.X % 16 == 0) && ((uintptr_t)c.C % 16 == 0);
     const bool ft = c.ft != FTK_FT_OFF;
     dim3 grid((unsigned)p.workgroups), block(256);
-    if (aligned && ft)
-        hipLaunchKernelGGL((assign_generic_kernel<T, true, true>), grid, block, p.lds_bytes, st, a);
-    else if (aligned)
-        hipLaunchKernelGGL((assign_generic_kernel<T, true, false>), grid, block, p.lds_bytes, st, a);
-    else if (ft)
-        hipLaunchKernelGGL((assign_generic_kernel<T, false, true>), grid, block, p.lds_bytes, st, a);
-    else
-        hipLaunchKernelGGL((assign_generic_kernel<T, false, false>), grid, block, p.lds_bytes, st, a);
+#define FTK_LAUNCH_GEN(KV, AL, F) \
+    hipLaunchKernelGGL((assign_generic_kernel<T, KV, AL, F>), grid, block, p.lds_bytes, st, a)
+#define FTK_LAUNCH_GEN_K(KV)                          \
+    do {                                              \
+        if (aligned && ft) FTK_LAUNCH_GEN(KV, true, true);     \
+        else if (aligned) FTK_LAUNCH_GEN(KV, true, false);     \
+        else if (ft) FTK_LAUNCH_GEN(KV, false, true);          \
+        else FTK_LAUNCH_GEN(KV, false, false);                 \
+    } while (0)
+    if (p.KT == 4) FTK_LAUNCH_GEN_K(4);
+    else if (p.KT == 2) FTK_LAUNCH_GEN_K(2);
+    else FTK_LAUNCH_GEN_K(1);
+#undef FTK_LAUNCH_GEN_K
+#undef FTK_LAUNCH_GEN
     FTK_TRY_HIP(hipGetLastError());
     return FTK_OK;
 }
@@ -696,13 +709,13 @@ void plan_generic(ftk_dtype dtype, int64_t N, int D, int K, AssignPlan &p)
     p.variant = VAR_GENERIC;
     p.TM = f32 ? Mma<float>::TM : Mma<double>::TM;
     p.TN = f32 ? Mma<float>::TN : Mma<double>::TN;
-    p.PT = f32 ? GenericCfg<float>::PT : GenericCfg<double>::PT;
-    p.KT = f32 ? GenericCfg<float>::KT : GenericCfg<double>::KT;
+    p.PT = 2;
+    p.KT = f32 ? generic_kt<float>(K) : generic_kt<double>(K);
     p.waves = 4;
     p.KC = p.KT * p.TM;
     p.nkc = (int)ceil_div(K, p.KC);
     p.D8 = (int)ceil_div(D, 8) * 8;
-    p.DQ = f32 ? GenericCfg<float>::DQ : GenericCfg<double>::DQ;
+    p.DQ = 2;
     p.points_per_wg = p.waves * p.PT * p.TN;
     p.workgroups = ceil_div(N, p.points_per_wg);
     p.tiles_per_wave = p.nkc * p.PT * p.KT;

@@ -23,6 +23,9 @@ SHAPES = [
     ("generic f32 unaligned", 2000, 33, 130, "f32"),
     ("generic f64", 3000, 64, 100, "f64"),
     ("generic f64 large D", 1500, 512, 64, "f64"),
+    ("generic f32 one tile of centroids", 5000, 96, 24, "f32"),
+    ("generic f32 two tiles of centroids", 5000, 96, 50, "f32"),
+    ("generic f64 two tiles of centroids", 3000, 64, 20, "f64"),
 ]
 
 

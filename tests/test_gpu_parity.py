@@ -15,6 +15,8 @@ SHAPES = [
     (1, 1, 1), (5, 3, 2), (64, 4, 64), (100, 7, 5), (300, 8, 33), (1000, 16, 8), (257, 2, 600),
     (777, 33, 130), (2048, 128, 256), (513, 200, 70), (100, 1, 300), (1500, 64, 129), (640, 24, 1025),
     (3000, 8, 3000), (1111, 32, 900), (450000, 8, 40), (2500, 12, 77), (9000, 20, 2049),
+    # few centroids, many features: the one- and two-tile blockings of the generic kernel
+    (4000, 72, 40), (3000, 40, 20), (2000, 100, 64), (70000, 256, 12),
 ]
 
 
