@@ -106,7 +106,7 @@ __device__ __forceinline__ void eval_rows(const floatx4 (&xlo)[NQ], const floatx
 {
     // rows in register order, the running minimum updated as they come; with many features the
     // loop is unrolled only twice (all eight rows in flight would need more registers than exist)
-    constexpr int UNROLL = NQ <= 2 ? 8 : 2;
+    constexpr int UNROLL = NQ == 1 ? 4 : (NQ == 2 ? 8 : 2);
 #pragma unroll UNROLL
     for (int i = 0; i < 8; ++i) {
         // register r = r0 + i of group gw holds tile row 8*(r/4) + 4*gw + r%4; r0 is 0 or 8
