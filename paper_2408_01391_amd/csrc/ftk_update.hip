@@ -777,8 +777,9 @@ static UpdateLaunch plan_update_launch(ftk_dtype dtype, const void *X, int64_t N
     L.lpr_log2 = 0;
     while ((1 << L.lpr_log2) < L.pieces && L.lpr_log2 < 6) ++L.lpr_log2;
     const int gpw = 64 >> L.lpr_log2;
-    // long runs per lane (few flushes), but at least ~2048 waves where N allows
-    int64_t rpl = N / ((int64_t)gpw * 2048);
+    // long runs per lane: every run ends in device-wide atomics, and their number - not the
+    // gather - is what the kernel time follows; about 1024 waves where N allows
+    int64_t rpl = N / ((int64_t)gpw * 1024);
     if (rpl < 64) rpl = 64;
     if (rpl > RED_ROWS_PER_LANE_MAX) rpl = RED_ROWS_PER_LANE_MAX;
     L.rows_per_lane = (int)rpl;
