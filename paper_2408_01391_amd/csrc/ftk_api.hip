@@ -77,8 +77,14 @@ Workspace carve_workspace(void *base, ftk_dtype dtype, int64_t N, int D, int K, 
     w.wl_count = (int32_t *)take(4 * sizeof(int32_t));
     w.wl = (int32_t *)take((size_t)N * sizeof(int32_t));
     w.fx_sums = (int64_t *)take((size_t)K * D * 2 * sizeof(int64_t));  // two limbs per cell
-    w.upd_slab = (int64_t *)take((size_t)update_slab_cells_max(N, D, K) * sizeof(int64_t));
-    w.upd_cslab = (int32_t *)take((size_t)update_slab_chunks_max(N) * K * sizeof(int32_t));
+    {   // shared by the two update paths: per-workgroup tables, or two tagged slots per walker
+        const size_t slab_cells = (size_t)update_slab_cells_max(N, D, K);
+        const size_t slot_cells = (size_t)update_walkers_max(N) * 2 * (size_t)D;
+        w.upd_slab = (int64_t *)take((slab_cells > slot_cells ? slab_cells : slot_cells) * sizeof(int64_t));
+        const size_t slab_counts = (size_t)update_slab_chunks_max(N) * K;
+        const size_t slot_tags = (size_t)update_walkers_max(N) * 2;
+        w.upd_cslab = (int32_t *)take((slab_counts > slot_tags ? slab_counts : slot_tags) * sizeof(int32_t));
+    }
     w.absmax = (double *)take(2 * sizeof(double));
     w.sort_idx = (int32_t *)take((size_t)N * sizeof(int32_t));
     w.sort_lab = (int32_t *)take((size_t)N * sizeof(int32_t));

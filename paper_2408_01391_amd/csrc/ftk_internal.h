@@ -67,12 +67,13 @@ struct Workspace {
     int32_t *wl;        // [N]   refine work-list (point indices)
     // update
     int64_t *fx_sums;   // [K*D][2] fixed-point sums, two limbs (label-sorted path)
-    int64_t *upd_slab;  // [chunks][K*D] per-workgroup fixed-point tables (LDS path)
-    int32_t *upd_cslab; // [chunks][K]   per-workgroup member counts (LDS path)
+    int64_t *upd_slab;  // [chunks][K*D] per-workgroup fixed-point tables (LDS path), or
+                        // [walkers][2][D] tagged partial sums (label-sorted path)
+    int32_t *upd_cslab; // [chunks][K] per-workgroup member counts, or [walkers][2] slot tags
     double *absmax;     // [2]
     int32_t *sort_idx;  // [N]   point indices grouped by label
     int32_t *sort_lab;  // [N]   their labels
-    int32_t *sort_cursor;  // [K] bucket cursors
+    int32_t *sort_cursor;  // [K+1] segment starts, after the scatter segment ends; [K] = total
     // fit
     void *C_cur;        // [K*D] running centroids (dtype)
     void *mindist;      // [N]   (dtype)
@@ -86,6 +87,7 @@ Workspace carve_workspace(void *base, ftk_dtype dtype, int64_t N, int D, int K, 
 // upper bounds of the update step's per-workgroup tables, independent of pointer alignment
 int64_t update_slab_chunks_max(int64_t N);
 int64_t update_slab_cells_max(int64_t N, int D, int K);
+int64_t update_walkers_max(int64_t N);
 
 // ---- launches (each returns after enqueueing on `st`) ------------------------------------
 struct AssignCall {

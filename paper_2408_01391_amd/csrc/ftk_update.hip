@@ -39,6 +39,8 @@ int64_t update_slab_chunks_max(int64_t N)
     const int64_t by_rows = ceil_div(N, UPD_THREADS);
     return by_rows < UPD_TARGET_WGS ? (by_rows < 1 ? 1 : by_rows) : UPD_TARGET_WGS;
 }
+// walkers of the label-sorted path: one per RED_ROWS_PER_LANE_MIN rows at most
+int64_t update_walkers_max(int64_t N) { return ceil_div(N, 64) + 1; }
 int64_t update_slab_cells_max(int64_t N, int D, int K)
 {
     const int64_t cells = (int64_t)K * D;
@@ -450,29 +452,6 @@ __global__ __launch_bounds__(RF_CELLS * RF_GROUPS) void update_reduce_finalize_k
     }
 }
 
-// Averaging pass ("the last kernel", Section 3.1.1): C_j = sum_j / count_j, rounded once;
-// a cluster without points keeps its previous centroid.
-template <typename T, bool DMR>
-__global__ __launch_bounds__(256) void update_finalize_kernel(const unsigned long long *sums,
-                                                              const int32_t *counts, int64_t N,
-                                                              int64_t rows_per_chunk, int D, int K,
-                                                              const double *absmax_p, T *C, ftk_ft_stats *stats)
-{
-    const double inv = 1.0 / fixed_point_scale(*absmax_p, sizeof(T) == 8 ? rows_per_chunk : N);
-    const int64_t n = (int64_t)K * D;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    int detected = 0;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
-        const int c = counts[i / D];
-        if (c > 0)
-            C[i] = fixed_point_mean<T, DMR>((long long)sums[2 * i], (long long)sums[2 * i + 1], inv, c, &detected);
-    }
-    if (DMR && detected) {
-        add_stat(stats, STAT_DETECTED, detected);
-        add_stat(stats, STAT_RECOMPUTED, detected);
-    }
-}
-
 // ======================= label-sorted path (rows of at least one cache line) =================
 // Points are first bucketed by label (counting sort: histogram, scan, scatter); the reduction
 // then walks the sorted order, where a lane sees long runs of one label and can keep the
@@ -582,16 +561,27 @@ __global__ __launch_bounds__(256) void sort_scatter_kernel(const int32_t *labels
     }
 }
 
-constexpr int RED_ROWS_PER_LANE_MAX = 256;  // most sorted positions a lane walks (stride = groups per wave)
+constexpr int RED_ROWS_PER_LANE_MAX = 256;  // most sorted positions one walker covers
+constexpr int RED_ROWS_PER_LANE_MIN = 64;
 
-// Walk the sorted order.  lpr_log2: lanes per row (power of two); a wave holds 64/lpr row groups;
-// blockIdx.y selects the slice of 64*E features when a row is wider than one wave.
+// Walk the sorted order.  lpr_log2: lanes per row (power of two); a wave holds 64/lpr "walkers"
+// (row groups), each covering rows_per_lane consecutive sorted positions; blockIdx.y selects the
+// slice of 64*E features when a row is wider than one wave.
+//
+// Where the sums go when a run of one label ends - without any atomics:
+//   * the label's whole segment lies inside this walker's range: the walker owns the result and
+//     stores it straight into `sums`;
+//   * the segment started before the range (then the run is the walker's first) or continues
+//     after it (then it is the last): the partial sum goes to the walker's slot 0 resp. 1,
+//     tagged with the label, and the averaging kernel adds the slots of the walkers a segment
+//     touches.  (cursor[k] is the end of segment k after the scatter, cursor[K] their total.)
 template <typename T, bool ALIGNED, bool DMR>
 __global__ __launch_bounds__(256) void sorted_reduce_kernel(const T *X, const int32_t *sorted_idx,
-                                                            const int32_t *sorted_lab, const int32_t *n_sorted_p,
-                                                            int64_t N, int D, int lpr_log2, int rows_per_lane,
-                                                            const double *absmax_p, unsigned long long *sums,
-                                                            UpdateFtArgs ft)
+                                                            const int32_t *sorted_lab, const int32_t *cursor,
+                                                            int K, int64_t N, int D, int lpr_log2, int rows_per_lane,
+                                                            int64_t n_walkers, const double *absmax_p,
+                                                            long long *sums, long long *slot_val,
+                                                            int32_t *slot_lab, UpdateFtArgs ft)
 {
     using F = typename Mma<T>::frag_t;
     constexpr int E = ALIGNED ? Mma<T>::E : 1;
@@ -605,22 +595,25 @@ __global__ __launch_bounds__(256) void sorted_reduce_kernel(const T *X, const in
     const int group = lane >> lpr_log2, piece = lane & (lpr - 1);
     const int d0 = (blockIdx.y * 64 + piece) * E;  // first feature of this lane
     const bool lane_on = d0 < D;
+    // fp32: one limb scaled for the whole of N; fp64: scaled for one walker's rows, two limbs later
     const double scale = fixed_point_scale(*absmax_p, TWO_LIMB ? RED_ROWS_PER_LANE_MAX : N);
     const double scale2 = dmr_copy(scale);
-    const int64_t s_begin = wave * (int64_t)(gpw * rows_per_lane) + group;
-    const int64_t n_sorted = *n_sorted_p;
-    const int64_t s_end = min(n_sorted, (wave + 1) * (int64_t)(gpw * rows_per_lane));
+    const int64_t walker = wave * gpw + group;
+    const int64_t n_sorted = cursor[K];
+    const int64_t s_begin = min(n_sorted, walker * (int64_t)rows_per_lane);
+    const int64_t s_end = min(n_sorted, (walker + 1) * (int64_t)rows_per_lane);
     const int nf = blockIdx.y == 0 ? stage_faults(ft, (int)blockIdx.x, sh_faults, &sh_nf, 256) : 0;
     int n_injected = 0, n_detected = 0, n_recomputed = 0, n_uncorrectable = 0;  // per lane (runs end in divergent flow)
 
     // DMR: a second set of running sums is fed by a second conversion of the same loaded values;
     // the two sets are compared as integers whenever a run ends, i.e. before anything leaves the
-    // registers.  On a mismatch the lane walks its run again (both streams) and flushes that.
+    // registers.  On a mismatch the lane walks its run again (both streams) and stores that.
     long long acc[E], acc2[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) acc[e] = acc2[e] = 0;
     int cur = -1;
-    int64_t run_start = s_begin;  // sorted position of the first row of the current run of this lane
+    int slot_label0 = -1, slot_label1 = -1;
+    int64_t run_start = s_begin;  // sorted position of the first row of the current run
     auto flush = [&](int64_t run_end) {
         if constexpr (DMR) {
             bool bad = false;
@@ -636,7 +629,7 @@ __global__ __launch_bounds__(256) void sorted_reduce_kernel(const T *X, const in
                         long long r1[E], r2[E];
 #pragma unroll
                         for (int e = 0; e < E; ++e) r1[e] = r2[e] = 0;
-                        for (int64_t s = run_start; s < run_end; s += gpw) {
+                        for (int64_t s = run_start; s < run_end; ++s) {
                             const int64_t row = sorted_idx[s];
 #pragma unroll
                             for (int e = 0; e < E; ++e) {
@@ -656,20 +649,33 @@ __global__ __launch_bounds__(256) void sorted_reduce_kernel(const T *X, const in
                 }
             }
         }
-        if (cur >= 0 && lane_on) {
+        if (cur >= 0) {
+            const int64_t seg_a = cur ? cursor[cur - 1] : 0, seg_b = cursor[cur];
+            const bool interior = seg_a >= s_begin && seg_b <= s_end;
+            const int slot = seg_a < s_begin ? 0 : 1;
+            if (!interior) {
+                if (slot == 0) slot_label0 = cur;
+                else slot_label1 = cur;
+            }
+            if (lane_on) {
 #pragma unroll
-            for (int e = 0; e < E; ++e) {
-                if (d0 + e < D && acc[e] != 0) {
-                    unsigned long long *dst = sums + 2 * ((int64_t)cur * D + d0 + e);
-                    if (TWO_LIMB) {
-                        atomicAdd(dst, (unsigned long long)(acc[e] >> UPD_LIMB_BITS));
-                        atomicAdd(dst + 1, (unsigned long long)(acc[e] & ((1ll << UPD_LIMB_BITS) - 1)));
-                    } else {
-                        atomicAdd(dst + 1, (unsigned long long)acc[e]);
+                for (int e = 0; e < E; ++e) {
+                    if (d0 + e < D) {
+                        if (interior) {
+                            long long *dst = sums + 2 * ((int64_t)cur * D + d0 + e);
+                            if (TWO_LIMB) {
+                                dst[0] = acc[e] >> UPD_LIMB_BITS;                      // floor
+                                dst[1] = acc[e] & ((1ll << UPD_LIMB_BITS) - 1);        // >= 0
+                            } else {
+                                dst[1] = acc[e];
+                            }
+                        } else {
+                            slot_val[(walker * 2 + slot) * D + d0 + e] = acc[e];
+                        }
                     }
+                    acc[e] = 0;
+                    if (DMR) acc2[e] = 0;
                 }
-                acc[e] = 0;
-                if (DMR) acc2[e] = 0;
             }
         }
     };
@@ -680,7 +686,7 @@ __global__ __launch_bounds__(256) void sorted_reduce_kernel(const T *X, const in
     auto fetch_keys = [&](int64_t s0) {
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
-            const int64_t s = s0 + (int64_t)u * gpw;
+            const int64_t s = s0 + u;
             const bool in = s < s_end;
             lab_n[u] = in ? sorted_lab[s] : -1;
             row_n[u] = in ? sorted_idx[s] : 0;
@@ -688,7 +694,7 @@ __global__ __launch_bounds__(256) void sorted_reduce_kernel(const T *X, const in
     };
     fetch_keys(s_begin);
     int step = 0;
-    for (int64_t s0 = s_begin; s0 < s_end; s0 += (int64_t)gpw * UNR, ++step) {
+    for (int64_t s0 = s_begin; s0 < s_end; s0 += UNR, ++step) {
         int lab[UNR];
         F f[UNR];
 #pragma unroll
@@ -699,14 +705,14 @@ __global__ __launch_bounds__(256) void sorted_reduce_kernel(const T *X, const in
                 else f[u][0] = X[row_n[u] * D + d0];
             }
         }
-        fetch_keys(s0 + (int64_t)gpw * UNR);
+        fetch_keys(s0 + UNR);
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
             if (lab[u] >= 0) {
                 if (lab[u] != cur) {
-                    flush(s0 + (int64_t)u * gpw);
+                    flush(s0 + u);
                     cur = lab[u];
-                    run_start = s0 + (int64_t)u * gpw;
+                    run_start = s0 + u;
                 }
                 if (lane_on) {
 #pragma unroll
@@ -739,6 +745,11 @@ __global__ __launch_bounds__(256) void sorted_reduce_kernel(const T *X, const in
         }
     }
     flush(s_end);
+    // slot tags (the same from every feature slice)
+    if (piece == 0 && walker < n_walkers) {
+        slot_lab[walker * 2 + 0] = slot_label0;
+        slot_lab[walker * 2 + 1] = slot_label1;
+    }
     if (ft.stats && (DMR || nf > 0)) {
 #pragma unroll
         for (int mask = 1; mask < 64; mask <<= 1) {
@@ -756,12 +767,104 @@ __global__ __launch_bounds__(256) void sorted_reduce_kernel(const T *X, const in
     }
 }
 
+// Averaging pass of the label-sorted path: per cell, the sum stored by the owning walker (zero if
+// none) plus the tagged slots of the walkers the label's segment touches; then the mean.  Same
+// tiling idea as update_reduce_finalize_kernel: thread groups stride over the walkers.
+// a segment touches few walkers (its length / rows per walker + 2), so few thread groups per cell
+constexpr int SF_CELLS = 32, SF_GROUPS = 8;
+template <typename T, bool DMR>
+__global__ __launch_bounds__(SF_CELLS * SF_GROUPS) void sorted_finalize_kernel(
+    const long long *sums, const long long *slot_val, const int32_t *slot_lab, const int32_t *cursor,
+    int rows_per_lane, int64_t N, int D, int K, const double *absmax_p, T *C, ftk_ft_stats *stats)
+{
+    constexpr bool TWO_LIMB = sizeof(T) == 8;
+    __shared__ long long sh_hi[SF_GROUPS][SF_CELLS], sh_lo[SF_GROUPS][SF_CELLS];
+    const int ci = threadIdx.x % SF_CELLS, grp = threadIdx.x / SF_CELLS;
+    const int64_t cells = (int64_t)K * D;
+    const int64_t cell = (int64_t)blockIdx.x * SF_CELLS + ci;
+    const bool on = cell < cells;
+    const int k = on ? (int)(cell / D) : 0;
+    const int d = on ? (int)(cell - (int64_t)k * D) : 0;
+    const int64_t seg_a = k ? cursor[k - 1] : 0, seg_b = cursor[k];
+    const int n = (int)(seg_b - seg_a);
+    long long hi = 0, lo = 0, hi2 = 0, lo2 = 0;
+    int detected = 0;
+    if (on && n > 0) {
+        if (grp == 0) {
+            hi = hi2 = sums[2 * cell];
+            lo = lo2 = sums[2 * cell + 1];
+        }
+        const int64_t w_lo = seg_a / rows_per_lane, w_hi = (seg_b - 1) / rows_per_lane;
+        // tags and values are loaded unconditionally (unused slots hold stale data that the tag
+        // deselects): no load depends on another, so several walkers are in flight per thread
+#pragma unroll 4
+        for (int64_t w = w_lo + grp; w <= w_hi; w += SF_GROUPS) {
+#pragma unroll
+            for (int slot = 0; slot < 2; ++slot) {
+                const int tag = slot_lab[w * 2 + slot];
+                long long v = slot_val[(w * 2 + slot) * D + d];
+                v = tag == k ? v : 0ll;
+                if (TWO_LIMB) {
+                    hi += v >> UPD_LIMB_BITS;
+                    lo += v & ((1ll << UPD_LIMB_BITS) - 1);
+                } else {
+                    lo += v;
+                }
+                if constexpr (DMR) {
+                    asm volatile("" : "+v"(v));
+                    if (TWO_LIMB) {
+                        hi2 += v >> UPD_LIMB_BITS;
+                        lo2 += v & ((1ll << UPD_LIMB_BITS) - 1);
+                    } else {
+                        lo2 += v;
+                    }
+                }
+            }
+        }
+        if constexpr (DMR) {
+            if (hi != hi2 || lo != lo2) {  // settle by a third pass
+                long long hi3 = grp == 0 ? sums[2 * cell] : 0, lo3 = grp == 0 ? sums[2 * cell + 1] : 0;
+                for (int64_t w = w_lo + grp; w <= w_hi; w += SF_GROUPS)
+                    for (int slot = 0; slot < 2; ++slot)
+                        if (slot_lab[w * 2 + slot] == k) {
+                            const long long v = slot_val[(w * 2 + slot) * D + d];
+                            if (TWO_LIMB) {
+                                hi3 += v >> UPD_LIMB_BITS;
+                                lo3 += v & ((1ll << UPD_LIMB_BITS) - 1);
+                            } else {
+                                lo3 += v;
+                            }
+                        }
+                hi = hi3;
+                lo = lo3;
+                detected += 1;
+            }
+        }
+    }
+    sh_hi[grp][ci] = hi;
+    sh_lo[grp][ci] = lo;
+    __syncthreads();
+    if (grp == 0 && on && n > 0) {
+        for (int g2 = 1; g2 < SF_GROUPS; ++g2) {
+            hi += sh_hi[g2][ci];
+            lo += sh_lo[g2][ci];
+        }
+        const double inv = 1.0 / fixed_point_scale(*absmax_p, TWO_LIMB ? RED_ROWS_PER_LANE_MAX : N);
+        C[cell] = fixed_point_mean<T, DMR>(hi, lo, inv, n, &detected);
+    }
+    if (DMR && detected) {
+        add_stat(stats, STAT_DETECTED, detected);
+        add_stat(stats, STAT_RECOMPUTED, detected);
+    }
+}
+
 // Launch geometry of the pass that accumulates the sums (the one faults are injected into).
 struct UpdateLaunch {
     bool sorted_path;
     UpdatePlan u;
     // sorted path
     int lpr_log2, rows_per_lane, pieces, E;
+    int64_t n_walkers;
     dim3 rgrid;
 };
 static UpdateLaunch plan_update_launch(ftk_dtype dtype, const void *X, int64_t N, int D, int K)
@@ -777,13 +880,13 @@ static UpdateLaunch plan_update_launch(ftk_dtype dtype, const void *X, int64_t N
     L.lpr_log2 = 0;
     while ((1 << L.lpr_log2) < L.pieces && L.lpr_log2 < 6) ++L.lpr_log2;
     const int gpw = 64 >> L.lpr_log2;
-    // long runs per lane: every run ends in device-wide atomics, and their number - not the
-    // gather - is what the kernel time follows; about 1024 waves where N allows
-    int64_t rpl = N / ((int64_t)gpw * 1024);
-    if (rpl < 64) rpl = 64;
+    // about 2048 waves where N allows (run ends cost only plain stores, so parallelism is free)
+    int64_t rpl = N / ((int64_t)gpw * 2048);
+    if (rpl < RED_ROWS_PER_LANE_MIN) rpl = RED_ROWS_PER_LANE_MIN;
     if (rpl > RED_ROWS_PER_LANE_MAX) rpl = RED_ROWS_PER_LANE_MAX;
     L.rows_per_lane = (int)rpl;
-    const int64_t waves = ceil_div(N, (int64_t)gpw * L.rows_per_lane);
+    L.n_walkers = ceil_div(N, L.rows_per_lane);
+    const int64_t waves = ceil_div(L.n_walkers, gpw);
     L.rgrid = dim3((unsigned)ceil_div(waves, 4), (unsigned)ceil_div(L.pieces, 64));
     return L;
 }
@@ -834,9 +937,16 @@ ftk_status launch_update(ftk_dtype dtype, const void *X, const int32_t *labels, 
         hipLaunchKernelGGL(sort_scatter_kernel, dim3(chunks), dim3(256), hl, st, labels, N, K, w.sort_cursor,
                            w.sort_idx, w.sort_lab);
         dim3 rblock(256);
+        long long *slot_val = reinterpret_cast<long long *>(w.upd_slab);
+        int32_t *slot_lab = w.upd_cslab;
+        if (L.n_walkers > update_walkers_max(N)) {
+            set_error("internal: %lld walkers exceed the workspace bound", (long long)L.n_walkers);
+            return FTK_EINVAL;
+        }
 #define FTK_LAUNCH_RED(T, AL, DM)                                                                       \
     hipLaunchKernelGGL((sorted_reduce_kernel<T, AL, DM>), L.rgrid, rblock, 0, st, (const T *)X, w.sort_idx, \
-                       w.sort_lab, w.sort_cursor + K, N, D, L.lpr_log2, L.rows_per_lane, absmax, sums, fa)
+                       w.sort_lab, w.sort_cursor, K, N, D, L.lpr_log2, L.rows_per_lane, L.n_walkers, absmax, \
+                       reinterpret_cast<long long *>(sums), slot_val, slot_lab, fa)
 #define FTK_LAUNCH_RED_T(T)                                \
     do {                                                   \
         if (u.aligned && dmr) FTK_LAUNCH_RED(T, true, true);       \
@@ -849,10 +959,11 @@ ftk_status launch_update(ftk_dtype dtype, const void *X, const int32_t *labels, 
 #undef FTK_LAUNCH_RED_T
 #undef FTK_LAUNCH_RED
         {
-            const int blocks = (int)(ceil_div(cells, 256) < 1024 ? ceil_div(cells, 256) : 1024);
+            const int blocks = (int)ceil_div(cells, SF_CELLS);
 #define FTK_LAUNCH_FIN(T, DM)                                                                              \
-    hipLaunchKernelGGL((update_finalize_kernel<T, DM>), dim3(blocks), dim3(256), 0, st, sums, counts, N, \
-                       (int64_t)RED_ROWS_PER_LANE_MAX, D, K, absmax, (T *)C, stats)
+    hipLaunchKernelGGL((sorted_finalize_kernel<T, DM>), dim3(blocks), dim3(SF_CELLS * SF_GROUPS), 0, st,  \
+                       reinterpret_cast<const long long *>(sums), slot_val, slot_lab, w.sort_cursor,       \
+                       L.rows_per_lane, N, D, K, absmax, (T *)C, stats)
             if (dtype == FTK_F32) {
                 if (dmr) FTK_LAUNCH_FIN(float, true);
                 else FTK_LAUNCH_FIN(float, false);
