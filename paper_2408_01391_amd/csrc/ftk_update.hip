@@ -21,7 +21,7 @@
 namespace ftk {
 
 constexpr int UPD_CELLS = 8192;  // int64 cells per workgroup slice (64 KB)
-constexpr int UPD_TARGET_WGS = 512;
+constexpr int UPD_TARGET_WGS = 256;  // one 1024-thread workgroup per CU: every extra table is one more slab to write and re-read
 constexpr int UPD_THREADS = 1024;  // threads per workgroup of the LDS path: many waves per 64 KB table hide the HBM latency
 
 struct UpdatePlan {
