@@ -562,40 +562,72 @@ __global__ __launch_bounds__(256, (GenericCfg<T, KTV>::WAVES_PER_SIMD)) void ass
     }
 }
 
-// One wave per queued point: all K exact distances (direct-difference form, double), wave-wide
-// arg-min with the lowest index on ties.  Rows are fetched with 16-byte loads, several in
-// flight per lane; every row is summed in the same feature order, so identical centroids tie.
-template <typename T, bool ALIGNED>
+// Exact settlement of the queued points: all K distances of a point in the direct-difference form
+// (double), then the arg-min with the lowest index on ties.  The work is a chain of memory
+// latencies rather than arithmetic, so the kernel spreads it as widely as the queue allows: a
+// short queue gives every point a whole workgroup, a long one gives it a wave; either way each
+// thread keeps JU centroid rows with DU fragments of each in flight, and all loads are clamped
+// into their rows instead of branched around.  Every row is summed in feature order into one
+// accumulator, so identical centroids tie exactly.
+template <typename T, bool ALIGNED, int JU>
 __global__ __launch_bounds__(256) void refine_kernel(const T *X, const T *C, int D, int K,
                                                      const int32_t *wl, const int32_t *wl_count,
                                                      int32_t *labels, T *mindist, ftk_ft_stats *stats)
 {
     constexpr int E = Mma<T>::E;
-    const int lane = threadIdx.x & 63;
-    const int wave_global = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    const int n_waves = (gridDim.x * blockDim.x) >> 6;
+    constexpr int DU = 16 / JU;
+    using F = typename Mma<T>::frag_t;
+    __shared__ double sh_best[4];
+    __shared__ int sh_j[4];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
     const int count = *wl_count;
-    for (int w = wave_global; w < count; w += n_waves) {
+    const bool wide = count <= (int)gridDim.x;     // a workgroup per point (else a wave per point)
+    const int tpp = wide ? 256 : 64;               // threads per point
+    const int tg = wide ? tid : lane;              // this thread's rank among them
+    const int first = wide ? (int)blockIdx.x : (int)blockIdx.x * 4 + wave;
+    const int stride = wide ? (int)gridDim.x : (int)gridDim.x * 4;
+    for (int w = first; w < count; w += stride) {
         const int64_t p = wl[w];
         const T *x = X + p * D;
         double best = __builtin_huge_val();
         int bj = 0x7fffffff;
-        for (int j = lane; j < K; j += 64) {
-            const T *c = C + (int64_t)j * D;
-            double s = 0.0;
-#pragma unroll 4
-            for (int d0 = 0; d0 < D; d0 += E) {
-                const auto cf = load_frag<T, ALIGNED>(c, d0, D);
-                const auto xf = load_frag<T, ALIGNED>(x, d0, D);
+        for (int j0 = tg; j0 < K; j0 += tpp * JU) {
+            const T *c[JU];
+            double s[JU];
 #pragma unroll
-                for (int e = 0; e < E; ++e) {
-                    const double diff = (double)xf[e] - (double)cf[e];
-                    s = fma(diff, diff, s);
-                }
+            for (int u = 0; u < JU; ++u) {
+                c[u] = C + (int64_t)min(j0 + tpp * u, K - 1) * D;
+                s[u] = 0.0;
             }
-            if (s < best) {  // j increases within a lane: first minimum kept
-                best = s;
-                bj = j;
+            for (int d0 = 0; d0 < D; d0 += E * DU) {
+                F xf[DU], cf[JU][DU];
+#pragma unroll
+                for (int v = 0; v < DU; ++v) xf[v] = load_frag_clamped<T, ALIGNED>(x, d0 + v * E, D);
+#pragma unroll
+                for (int u = 0; u < JU; ++u)
+#pragma unroll
+                    for (int v = 0; v < DU; ++v) cf[u][v] = load_frag_clamped<T, ALIGNED>(c[u], d0 + v * E, D);
+#pragma unroll
+                for (int v = 0; v < DU; ++v)
+#pragma unroll
+                    for (int e = 0; e < E; ++e) {
+                        const bool keep = d0 + v * E + e < D;
+#pragma unroll
+                        for (int u = 0; u < JU; ++u) {
+                            const double diff = keep ? (double)xf[v][e] - (double)cf[u][v][e] : 0.0;
+                            s[u] = fma(diff, diff, s[u]);
+                        }
+                    }
+            }
+#pragma unroll
+            for (int u = 0; u < JU; ++u) {  // j increases within a thread: first minimum kept
+                const int j = j0 + tpp * u;
+                if (j < K && s[u] < best) {
+                    best = s[u];
+                    bj = j;
+                }
             }
         }
 #pragma unroll
@@ -607,12 +639,29 @@ __global__ __launch_bounds__(256) void refine_kernel(const T *X, const T *C, int
                 bj = oj;
             }
         }
-        if (lane == 0) {
+        if (wide) {  // uniform over the workgroup, which walks the queue in step
+            if (lane == 0) {
+                sh_best[wave] = best;
+                sh_j[wave] = bj;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const double ob = sh_best[v];
+                const int oj = sh_j[v];
+                if (ob < best || (ob == best && oj < bj)) {
+                    best = ob;
+                    bj = oj;
+                }
+            }
+            __syncthreads();  // the slots are rewritten for the next point
+        }
+        if (tg == 0) {
             labels[p] = bj == 0x7fffffff ? 0 : bj;
             if (mindist) mindist[p] = (T)best;
         }
     }
-    if (stats && wave_global == 0 && lane == 0 && count > 0)
+    if (stats && blockIdx.x == 0 && tid == 0 && count > 0)
         atomicAdd((unsigned long long *)&stats->refined, (unsigned long long)count);
 }
 
@@ -685,12 +734,22 @@ static void launch_refine_t(const AssignCall &c, const Workspace &w, hipStream_t
 {
     const bool aligned = (c.D % Mma<T>::E == 0) && ((uintptr_t)c.X % 16 == 0) && ((uintptr_t)c.C % 16 == 0);
     dim3 grid(1024), block(256);
-    if (aligned)
-        hipLaunchKernelGGL((refine_kernel<T, true>), grid, block, 0, st, (const T *)c.X, (const T *)c.C,
-                           c.D, c.K, w.wl, w.wl_count, c.labels, (T *)c.mindist, c.stats);
-    else
-        hipLaunchKernelGGL((refine_kernel<T, false>), grid, block, 0, st, (const T *)c.X, (const T *)c.C,
-                           c.D, c.K, w.wl, w.wl_count, c.labels, (T *)c.mindist, c.stats);
+#define FTK_LAUNCH_REFINE(AL, JU)                                                                      \
+    hipLaunchKernelGGL((refine_kernel<T, AL, JU>), grid, block, 0, st, (const T *)c.X, (const T *)c.C, \
+                       c.D, c.K, w.wl, w.wl_count, c.labels, (T *)c.mindist, c.stats)
+#define FTK_LAUNCH_REFINE_J(JU)                   \
+    do {                                          \
+        if (aligned) FTK_LAUNCH_REFINE(true, JU); \
+        else FTK_LAUNCH_REFINE(false, JU);        \
+    } while (0)
+    // sixteen 16-byte loads in flight per thread: short rows leave room for more rows at once
+    const int nfrag = (int)ceil_div(c.D, Mma<T>::E);
+    if (nfrag <= 2) FTK_LAUNCH_REFINE_J(8);
+    else if (nfrag <= 4) FTK_LAUNCH_REFINE_J(4);
+    else if (nfrag <= 8) FTK_LAUNCH_REFINE_J(2);
+    else FTK_LAUNCH_REFINE_J(1);
+#undef FTK_LAUNCH_REFINE_J
+#undef FTK_LAUNCH_REFINE
 }
 
 ftk_status launch_refine(const AssignCall &c, const Workspace &w, hipStream_t st)
