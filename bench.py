@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the assignment kernel (FT off), from two rocprofv3 --pmc runs
 # (FETCH_SIZE, WRITE_SIZE) scaled by the readings of a device copy of X in the same run;
 # the summaries and commands are in profiles/<workload>_assign_update.txt
-MEASURED_TRAFFIC_BYTES = {"c2": 50.2e6, "c3": 309.5e6, "c4": 4673.8e6, "c5": 290.9e6}
+MEASURED_TRAFFIC_BYTES = {"c2": 42.6e6, "c3": 311.5e6, "c4": 4687.5e6, "c5": 290.8e6}
 
 
 def parse():
