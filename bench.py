@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--ft", default="both", choices=["off", "on", "both"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--ablation", action="store_true",
+                    help="also time the naive and the unfused GEMM + arg-min variants of the assignment "
+                         "(Section 3.1.1 / 3.1.2) and report them next to the fused kernel")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--inject-seconds", type=float, default=2.0,
                     help="run time of the bit-flip injection leg (workloads with a flip rate; 0 = skip)")
@@ -91,6 +94,38 @@ def time_steps_injected(ftk, torch, np, w, Xd, C, labels, mind, counts, absmax, 
                           stats=stats)
     torch.cuda.synchronize()
     return steps, time.perf_counter() - t0, int(per_step.sum())
+
+
+def ablation_times(ftk, torch, Xd, C, labels, mind, ws, esz):
+    """Whole assignment (all its kernels) by the three steps of Section 3.1: milliseconds per call
+    and the labels each variant changes against the fused kernel."""
+    from paper_2408_01391_amd import ablation
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return 1e3 * (time.perf_counter() - t0) / reps
+
+    N, K = Xd.shape[0], C.shape[0]
+    res = {}
+    ref = labels.clone()
+    res["fused_ms"] = timed(lambda: ftk.kmeans_assign(Xd, C, labels=ref, mindist=mind, workspace=ws), 20)
+    lab = torch.empty_like(labels)
+    res["naive_ms"] = timed(lambda: ablation.naive_assign(Xd, C, labels=lab, mindist=mind), 3)
+    res["naive_labels_differing"] = int((lab != ref).sum().item())
+    if N * K * esz <= 48e9:
+        gws = ablation.gemm_workspace(Xd, K)
+        res["gemm_unfused_ms"] = timed(lambda: ablation.gemm_assign(Xd, C, labels=lab, mindist=mind, workspace=gws), 5)
+        res["gemm_unfused_labels_differing"] = int((lab != ref).sum().item())
+        res["gemm_unfused_product_bytes"] = N * K * esz
+        del gws
+    else:
+        res["gemm_unfused_ms"] = None  # the N x K product alone would take more than 48 GB
+    return res
 
 
 def cpu_baseline(w, X, C0, seconds, gpu_labels0):
@@ -258,6 +293,8 @@ def main():
             out["ft"]["strict_overhead_step"] = results["strict"]["sec"] / results["off"]["sec"] - 1.0
             out["ft"]["strict_overhead_assign_kernel"] = (results["strict"]["kernel_ms"] /
                                                           results["off"]["kernel_ms"] - 1.0)
+    if args.ablation:
+        out["ablation"] = ablation_times(ftk, torch, Xd, C0d, labels, mind, ws, esz)
     if not args.no_cpu_baseline:
         lab0, _ = ftk.kmeans_assign(Xd, C0d, labels=labels, mindist=mind, workspace=ws)
         torch.cuda.synchronize()

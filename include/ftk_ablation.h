@@ -1,0 +1,52 @@
+/*
+ * ftk_ablation.h -- the earlier steps of the paper's stepwise optimisation (Section 3.1, the
+ * stepwise figure of Section 5.1), kept as separately built measurement kernels so that the
+ * fused matrix-core kernel of ftkmeans.h can be placed against what it replaces:
+ *
+ *   naive         the basic kernel of Section 3.1.1: one thread per point walks all K
+ *                 centroids and all D features (direct-difference form) and keeps the minimum;
+ *   gemm_unfused  variant V1 of Section 3.1.2: centroid norms, the product X C^T from the
+ *                 vendor GEMM (rocBLAS) written to memory in full, and a separate kernel that
+ *                 reads it back to take the per-point arg-min.
+ *
+ * These are not part of the product path (libftkmeans.so neither links nor calls them).
+ * Conventions as in ftkmeans.h: device pointers owned by the caller, row-major X [N x D] and
+ * C [K x D], squared distances, lowest index on exact ties, work only enqueued on `hip_stream`,
+ * errors by return code (0 = ok, 1 = invalid argument, 3 = workspace too small, 4 = device or
+ * library failure) with ftk_abl_last_error() giving the text.
+ *
+ * The unfused variant decides in the working precision from the expanded form, so on data whose
+ * norms are large against the nearest distance its labels can differ from the exact arg-min
+ * where two candidates are closer than the rounding error of that form; the naive variant
+ * decides from the direct form and differs only on near-exact ties.
+ */
+#ifndef FTK_ABLATION_H
+#define FTK_ABLATION_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* dtype: 0 = fp32, 1 = fp64.  labels [N] int32 out; mindist [N] (working precision) out,
+ * may be NULL. */
+int ftk_abl_naive_assign(int dtype, const void *X, const void *C, int64_t N, int32_t D, int32_t K,
+                         int32_t *labels, void *mindist, void *hip_stream);
+
+/* Bytes of device scratch ftk_abl_gemm_assign needs: the [N x K] product plus the K norms. */
+size_t ftk_abl_gemm_workspace_bytes(int dtype, int64_t N, int32_t K);
+
+/* The first call creates a rocBLAS handle for the calling process (this allocates and may take
+ * seconds); later calls reuse it. */
+int ftk_abl_gemm_assign(int dtype, const void *X, const void *C, int64_t N, int32_t D, int32_t K,
+                        int32_t *labels, void *mindist, void *workspace, size_t workspace_bytes,
+                        void *hip_stream);
+
+const char *ftk_abl_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

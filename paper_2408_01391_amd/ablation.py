@@ -1,0 +1,81 @@
+"""ctypes binding of libftk_ablation (measurement-only kernels: the naive kernel and the
+unfused GEMM + arg-min variant that precede the fused kernel in the paper's Section 3.1).
+
+Not part of the product path: nothing in ``binding.py`` imports this module.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+
+import torch
+
+_LIB_PATH = Path(__file__).resolve().parent / "libftk_ablation.so"
+_lib = None
+
+EXPORTS = ("ftk_abl_naive_assign", "ftk_abl_gemm_workspace_bytes", "ftk_abl_gemm_assign",
+           "ftk_abl_last_error")
+
+
+def load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not _LIB_PATH.exists():
+        raise FileNotFoundError(
+            "%s not found: build it with `python __graft_entry__.py` (hipcc, gfx950)" % _LIB_PATH)
+    L = ctypes.CDLL(str(_LIB_PATH))
+    vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
+    L.ftk_abl_naive_assign.argtypes = [i32, vp, vp, i64, i32, i32, vp, vp, vp]
+    L.ftk_abl_naive_assign.restype = i32
+    L.ftk_abl_gemm_workspace_bytes.argtypes = [i32, i64, i32]
+    L.ftk_abl_gemm_workspace_bytes.restype = sz
+    L.ftk_abl_gemm_assign.argtypes = [i32, vp, vp, i64, i32, i32, vp, vp, vp, sz, vp]
+    L.ftk_abl_gemm_assign.restype = i32
+    L.ftk_abl_last_error.restype = ctypes.c_char_p
+    _lib = L
+    return L
+
+
+def _check(rc):
+    if rc != 0:
+        raise RuntimeError("ftk_ablation error %d: %s" % (rc, load().ftk_abl_last_error().decode()))
+
+
+def _prep(X, C):
+    assert X.is_cuda and C.is_cuda and X.dtype == C.dtype and X.is_contiguous() and C.is_contiguous()
+    assert X.dtype in (torch.float32, torch.float64) and X.shape[1] == C.shape[1]
+    return 0 if X.dtype == torch.float32 else 1
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def naive_assign(X, C, labels=None, mindist=None):
+    code = _prep(X, C)
+    N, D = X.shape
+    K = C.shape[0]
+    labels = labels if labels is not None else torch.empty(N, dtype=torch.int32, device=X.device)
+    mindist = mindist if mindist is not None else torch.empty(N, dtype=X.dtype, device=X.device)
+    _check(load().ftk_abl_naive_assign(code, X.data_ptr(), C.data_ptr(), N, D, K, labels.data_ptr(),
+                                       mindist.data_ptr(), _stream()))
+    return labels, mindist
+
+
+def gemm_workspace(X, K):
+    code = 0 if X.dtype == torch.float32 else 1
+    nbytes = load().ftk_abl_gemm_workspace_bytes(code, X.shape[0], K)
+    return torch.empty(nbytes, dtype=torch.uint8, device=X.device)
+
+
+def gemm_assign(X, C, labels=None, mindist=None, workspace=None):
+    code = _prep(X, C)
+    N, D = X.shape
+    K = C.shape[0]
+    labels = labels if labels is not None else torch.empty(N, dtype=torch.int32, device=X.device)
+    mindist = mindist if mindist is not None else torch.empty(N, dtype=X.dtype, device=X.device)
+    workspace = workspace if workspace is not None else gemm_workspace(X, K)
+    _check(load().ftk_abl_gemm_assign(code, X.data_ptr(), C.data_ptr(), N, D, K, labels.data_ptr(),
+                                      mindist.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()))
+    return labels, mindist
