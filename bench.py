@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--ft", default="both", choices=["off", "on", "both"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-fast", action="store_true",
+                    help="skip the extra timing of the split-bf16 fast assignment (fp32 workloads with D <= 32)")
     ap.add_argument("--ablation", action="store_true",
                     help="also time the naive and the unfused GEMM + arg-min variants of the assignment "
                          "(Section 3.1.1 / 3.1.2) and report them next to the fused kernel")
@@ -94,6 +96,37 @@ def time_steps_injected(ftk, torch, np, w, Xd, C, labels, mind, counts, absmax, 
                           stats=stats)
     torch.cuda.synchronize()
     return steps, time.perf_counter() - t0, int(per_step.sum())
+
+
+def fast_mode_times(ftk, torch, Xd, C0d, labels, mind, counts, absmax, ws, warmup, steps, sec_per_step_fp32):
+    """Lloyd steps with the assignment on the split-bf16 matrix path (the counterpart of the paper's
+    TF32 variant): reported next to the headline, never as the headline."""
+    def run(n, C):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            ftk.kmeans_assign_fast(Xd, C, labels=labels, mindist=mind, workspace=ws)
+            ftk.kmeans_update(Xd, labels, C, counts=counts, x_absmax=absmax, workspace=ws)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    C = C0d.clone()
+    run(warmup, C)
+    sec = run(steps, C)
+    ftk.profile_enable(True)
+    run(min(steps, 10), C)
+    ftk.profile_enable(False)
+    ms, launches = ftk.profile_read()
+    ref, _ = ftk.kmeans_assign(Xd, C0d, workspace=ws)
+    fast, _ = ftk.kmeans_assign_fast(Xd, C0d, workspace=ws)
+    N, D = Xd.shape
+    K = C0d.shape[0]
+    kern_ms = ms / max(launches, 1)
+    return {"iters_per_s": steps / sec, "ms_per_step": 1e3 * sec / steps,
+            "speedup_vs_fp32_step": sec_per_step_fp32 / (sec / steps),
+            "assign_kernels_ms": kern_ms, "dtype": "bf16x3 split of f32, f32 accumulate",
+            "fp32_equivalent_tflops": 2.0 * N * D * K / (kern_ms * 1e-3) / 1e12,
+            "labels_differing_from_fp32_path": int((ref != fast).sum().item())}
 
 
 def ablation_times(ftk, torch, Xd, C, labels, mind, ws, esz):
@@ -293,6 +326,9 @@ def main():
             out["ft"]["strict_overhead_step"] = results["strict"]["sec"] / results["off"]["sec"] - 1.0
             out["ft"]["strict_overhead_assign_kernel"] = (results["strict"]["kernel_ms"] /
                                                           results["off"]["kernel_ms"] - 1.0)
+    if w.dtype == "f32" and D <= 32 and D % 4 == 0 and not args.no_fast:
+        out["fast_mode"] = fast_mode_times(ftk, torch, Xd, C0d, labels, mind, counts, absmax, ws, args.warmup, steps,
+                                           primary["sec"] / steps)
     if args.ablation:
         out["ablation"] = ablation_times(ftk, torch, Xd, C0d, labels, mind, ws, esz)
     if not args.no_cpu_baseline:

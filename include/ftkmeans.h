@@ -111,6 +111,21 @@ ftk_status ftk_kmeans_assign(ftk_dtype dtype, const void *X, const void *C, int6
                              const ftk_fault *faults, int32_t n_faults, ftk_ft_stats *stats,
                              void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Assignment step on the reduced-precision matrix path - the counterpart of the paper's TF32
+ * tensor-core variant (Section 3.1.5; gfx950 has no TF32 format, its fast matrix format is bf16).
+ * Same outputs and tie rule as ftk_kmeans_assign with fault tolerance off.  fp32 operands are
+ * split into three bf16 pieces each and the six largest piece products are accumulated in fp32 by
+ * the bf16 matrix instructions; the rounding bound of that evaluation is known, and points whose
+ * best scores fall inside it are settled by exact re-evaluation as in the fp32 path, so labels
+ * meet the same tolerance (identical to the exact arg-min except on near-exact ties) and
+ * mindist is the exact-form distance to the chosen centroid.
+ * Covers dtype == FTK_F32 with D <= 32 and D a multiple of 4, X and C 16-byte aligned; anything
+ * else returns FTK_EINVAL / FTK_EALIGN.  No checksums and no fault injection on this path.
+ * workspace: ftk_workspace_bytes(dtype, N, D, K, FTK_FT_OFF) bytes. */
+ftk_status ftk_kmeans_assign_fast(ftk_dtype dtype, const void *X, const void *C, int64_t N, int32_t D,
+                                  int32_t K, int32_t *labels, void *mindist /* nullable */,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Largest |x| over `count` elements, written as one double to out_absmax (device).
  * ftk_kmeans_update needs it to fix the scale of its order-independent accumulation. */
 ftk_status ftk_absmax(ftk_dtype dtype, const void *X, int64_t count, double *out_absmax,

@@ -49,6 +49,8 @@ def load():
     L.ftk_assign_geometry.restype = i32
     L.ftk_kmeans_assign.argtypes = [i32, vp, vp, i64, i32, i32, vp, vp, i32, vp, i32, vp, vp, sz, vp]
     L.ftk_kmeans_assign.restype = i32
+    L.ftk_kmeans_assign_fast.argtypes = [i32, vp, vp, i64, i32, i32, vp, vp, vp, sz, vp]
+    L.ftk_kmeans_assign_fast.restype = i32
     L.ftk_absmax.argtypes = [i32, vp, i64, vp, vp]
     L.ftk_absmax.restype = i32
     L.ftk_kmeans_update.argtypes = [i32, vp, vp, i64, i32, i32, vp, vp, vp, vp, sz, vp]
@@ -71,7 +73,7 @@ def load():
     return L
 
 
-EXPORTS = ("ftk_workspace_bytes", "ftk_assign_geometry", "ftk_kmeans_assign", "ftk_absmax",
+EXPORTS = ("ftk_workspace_bytes", "ftk_assign_geometry", "ftk_kmeans_assign", "ftk_kmeans_assign_fast", "ftk_absmax",
            "ftk_kmeans_update", "ftk_kmeans_update_ft", "ftk_update_geometry", "ftk_kmeans_fit", "ftk_seeded_indices", "ftk_profile_enable",
            "ftk_profile_read", "ftk_last_error", "ftk_version")
 
@@ -162,6 +164,25 @@ def kmeans_assign(X, C, labels=None, mindist=None, ft_mode=FT_OFF, faults=None, 
     _check(load().ftk_kmeans_assign(_dtype_code(X), X.data_ptr(), C.data_ptr(), N, D, K,
                                     labels.data_ptr(), _ptr(mindist), ft_mode, _ptr(faults), nf,
                                     _ptr(stats), wp, wn, _stream()))
+    return labels, mindist
+
+
+def kmeans_assign_fast(X, C, labels=None, mindist=None, workspace=None, want_mindist=True):
+    """Assignment step on the split-bf16 matrix path (fp32 data, D <= 32).  Returns (labels, mindist)."""
+    _dev2d(X, "X"), _dev2d(C, "C")
+    if X.dtype != C.dtype or X.shape[1] != C.shape[1]:
+        raise ValueError("X [N,D] and C [K,D] must share dtype and D")
+    N, D = X.shape
+    K = C.shape[0]
+    if labels is None:
+        labels = torch.empty(N, dtype=torch.int32, device=X.device)
+    if mindist is None and want_mindist:
+        mindist = torch.empty(N, dtype=X.dtype, device=X.device)
+    if workspace is None:
+        workspace = new_workspace(X, K, FT_OFF)
+    wp, wn = _ws_args(workspace)
+    _check(load().ftk_kmeans_assign_fast(_dtype_code(X), X.data_ptr(), C.data_ptr(), N, D, K,
+                                         labels.data_ptr(), _ptr(mindist), wp, wn, _stream()))
     return labels, mindist
 
 

@@ -94,6 +94,7 @@ Workspace carve_workspace(void *base, ftk_dtype dtype, int64_t N, int D, int K, 
     w.inertia = (double *)take(FIT_MAX_ITERS_IN_WS * sizeof(double));
     w.partials = (double *)take(1024 * sizeof(double));
     w.idx = (int64_t *)take((size_t)K * sizeof(int64_t));
+    w.csplit = take(fast_split_bytes(dtype, D, K));
     w.total = off;
     return w;
 }
@@ -165,22 +166,31 @@ static ftk_status check_device()
 static bool g_profile = false;
 static std::vector<std::pair<hipEvent_t, hipEvent_t>> g_profile_events;
 
-static ftk_status assign_impl(const AssignCall &c, void *workspace, hipStream_t st)
+static ftk_status assign_impl(const AssignCall &c, void *workspace, hipStream_t st, bool fast = false)
 {
     const bool aligned16 = ((uintptr_t)c.X % 16 == 0) && ((uintptr_t)c.C % 16 == 0);
-    const AssignPlan p = plan_assign(c.dtype, c.N, c.D, c.K, c.ft, aligned16);
+    AssignPlan p;
+    if (fast) {
+        memset(&p, 0, sizeof(p));
+        plan_fast_prologue(c.D, c.K, p);
+    } else {
+        p = plan_assign(c.dtype, c.N, c.D, c.K, c.ft, aligned16);
+    }
     const Workspace w = carve_workspace(workspace, c.dtype, c.N, c.D, c.K, c.ft);
     FTK_TRY(launch_centroid_prologue(c, p, w, st));
+    hipEvent_t e0 = nullptr, e1 = nullptr;
     if (g_profile) {
-        hipEvent_t e0, e1;
         FTK_TRY_HIP(hipEventCreate(&e0));
         FTK_TRY_HIP(hipEventCreate(&e1));
         FTK_TRY_HIP(hipEventRecord(e0, st));
+    }
+    if (fast)
+        FTK_TRY(launch_assign_fast(c, w, st));
+    else
         FTK_TRY(launch_assign(c, p, w, st));
+    if (g_profile) {
         FTK_TRY_HIP(hipEventRecord(e1, st));
         g_profile_events.emplace_back(e0, e1);
-    } else {
-        FTK_TRY(launch_assign(c, p, w, st));
     }
     FTK_TRY(launch_refine(c, w, st));
     return FTK_OK;
@@ -268,6 +278,26 @@ ftk_status ftk_kmeans_assign(ftk_dtype dtype, const void *X, const void *C, int6
     FTK_TRY(check_device());
     AssignCall c{dtype, X, C, N, D, K, labels, mindist, ft, faults, n_faults, stats};
     return assign_impl(c, workspace, (hipStream_t)hip_stream);
+}
+
+ftk_status ftk_kmeans_assign_fast(ftk_dtype dtype, const void *X, const void *C, int64_t N, int32_t D,
+                                  int32_t K, int32_t *labels, void *mindist, void *workspace,
+                                  size_t workspace_bytes, void *hip_stream)
+{
+    FTK_TRY(check_problem(dtype, N, D, K, FTK_FT_OFF));
+    if (!fast_supported(dtype, D)) {
+        set_error("the fast assignment covers fp32 data with D <= 32 and D a multiple of 4 (got dtype=%d D=%d)",
+                  (int)dtype, D);
+        return FTK_EINVAL;
+    }
+    FTK_TRY(check_ptr(X, 16, "X"));
+    FTK_TRY(check_ptr(C, 16, "C"));
+    FTK_TRY(check_ptr(labels, 4, "labels"));
+    if (mindist) FTK_TRY(check_ptr(mindist, 4, "mindist"));
+    FTK_TRY(check_workspace(workspace, workspace_bytes, ftk_workspace_bytes(dtype, N, D, K, FTK_FT_OFF)));
+    FTK_TRY(check_device());
+    AssignCall c{dtype, X, C, N, D, K, labels, mindist, FTK_FT_OFF, nullptr, 0, nullptr};
+    return assign_impl(c, workspace, (hipStream_t)hip_stream, true);
 }
 
 ftk_status ftk_absmax(ftk_dtype dtype, const void *X, int64_t count, double *out_absmax, void *hip_stream)

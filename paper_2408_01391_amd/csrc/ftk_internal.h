@@ -80,6 +80,8 @@ struct Workspace {
     double *inertia;    // [iters_max] per-iteration objective
     double *partials;   // [1024] block partial sums
     int64_t *idx;       // [K]   seeded initial point indices
+    // fast (split-bf16) assignment
+    void *csplit;       // centroid pieces in LDS image order (fp32 data with D <= 32, else empty)
     size_t total;
 };
 constexpr int FIT_MAX_ITERS_IN_WS = 4096;
@@ -108,6 +110,10 @@ ftk_status launch_smalld_checksums(const AssignCall &c, const AssignPlan &p, con
                                    hipStream_t st);
 ftk_status launch_assign(const AssignCall &c, const AssignPlan &p, const Workspace &w, hipStream_t st);
 ftk_status launch_refine(const AssignCall &c, const Workspace &w, hipStream_t st);
+bool fast_supported(ftk_dtype dtype, int D);
+size_t fast_split_bytes(ftk_dtype dtype, int D, int K);
+void plan_fast_prologue(int D, int K, AssignPlan &p);
+ftk_status launch_assign_fast(const AssignCall &c, const Workspace &w, hipStream_t st);
 
 ftk_status launch_absmax(ftk_dtype dtype, const void *X, int64_t count, double *out, hipStream_t st);
 ftk_status launch_update(ftk_dtype dtype, const void *X, const int32_t *labels, int64_t N, int D,

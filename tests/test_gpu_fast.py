@@ -1,0 +1,92 @@
+"""The split-bf16 fast assignment (ftk_kmeans_assign_fast) against the CPU oracle: the same bar as
+the fp32 path - labels identical except inside the 1e-5 tie band, exact ties to the lowest index,
+mindist the exact-form distance."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import cpu as oracle
+from paper_2408_01391_amd import binding as ftk, synth
+from tests.gpu_util import check_assign, to_dev
+
+pytestmark = pytest.mark.gpu
+
+SHAPES = [
+    (1, 4, 1), (64, 4, 64), (300, 8, 33), (1000, 16, 8), (257, 4, 600), (640, 24, 1025), (3000, 8, 3000),
+    (1111, 32, 900), (450000, 8, 40), (2500, 12, 77), (9000, 20, 2049), (5000, 28, 31), (70000, 32, 4100),
+    (2049, 8, 1024), (100000, 16, 100),
+]
+
+
+def fast_assign(X, C, **kw):
+    labels, mind = ftk.kmeans_assign_fast(to_dev(X), to_dev(C), **kw)
+    torch.cuda.synchronize()
+    return labels.cpu().numpy(), mind.cpu().numpy()
+
+
+@pytest.mark.parametrize("N,D,K", SHAPES)
+def test_fast_assign_matches_oracle_on_ragged_shapes(N, D, K):
+    X, C = synth.random_problem(N * 7 + D * 3 + K, N, D, K, "f32")
+    print("fast assign", N, D, K, flush=True)
+    labels, mind = fast_assign(X, C)
+    check_assign(X, C, labels, mind)
+
+
+def test_fast_assign_exact_on_integers_with_duplicate_centroids():
+    X, C = synth.random_problem(5, 3000, 12, 40, "f32", integer=True)
+    C[17] = C[3]
+    C[39] = C[3]
+    C[8] = C[30]
+    labels, mind = fast_assign(X, C)
+    lab_o, d1, _ = oracle.assign(X, C)
+    assert np.array_equal(labels, lab_o)
+    assert not np.isin(labels, [17, 39, 30]).any()
+    assert np.allclose(mind, d1, rtol=1e-6, atol=1e-3)
+
+
+def test_fast_assign_offset_data_needs_the_exact_tie_break():
+    """Large common offset: the norms are ~1e8 while cluster gaps are ~1, far below what the
+    expanded form can resolve in either matrix precision."""
+    rng = np.random.default_rng(3)
+    X = (rng.normal(size=(4000, 8)) + 3000.0).astype(np.float32)
+    C = X[rng.choice(4000, 50, replace=False)].copy()
+    labels, _ = fast_assign(X, C)
+    check_assign(X, C, labels)
+
+
+def test_fast_assign_wide_dynamic_range_within_rows():
+    """Features of very different magnitude in one row: the three pieces of each element are taken
+    per element, so small features keep their own leading bits."""
+    rng = np.random.default_rng(8)
+    scale = np.array([1e-3, 1.0, 1e3, 1e-2, 30.0, 1e2, 1e-1, 5.0], dtype=np.float64)
+    X = (rng.normal(size=(6000, 8)) * scale).astype(np.float32)
+    C = X[rng.choice(6000, 200, replace=False)].copy()
+    labels, mind = fast_assign(X, C)
+    check_assign(X, C, labels, mind)
+
+
+@pytest.mark.parametrize("name", ["c2", "c5"])
+def test_fast_assign_full_size_sampled_rows(name):
+    w = synth.WORKLOADS[name]
+    X, _ = synth.make_points(w)
+    C = X[synth.init_indices(w, w.N)].copy()
+    labels, mind = fast_assign(X, C)
+    rows = np.random.default_rng(1).choice(w.N, 3000, replace=False)
+    rows[:3] = [0, w.N - 1, w.N // 2]
+    check_assign(X, C, labels, mind, rows=np.sort(rows))
+    # and the fp32 path agrees except where both are inside the band of a near-tie
+    lab32, _ = ftk.kmeans_assign(to_dev(X), to_dev(C))
+    differ = int((lab32.cpu().numpy() != labels).sum())
+    assert differ <= w.N // 100000 + 2, differ
+
+
+def test_fast_assign_rejects_what_it_does_not_cover():
+    X = torch.zeros(64, 40, device="cuda:0")
+    C = torch.zeros(4, 40, device="cuda:0")
+    with pytest.raises(ftk.FtkError):
+        ftk.kmeans_assign_fast(X, C)
+    Xd = torch.zeros(64, 8, dtype=torch.float64, device="cuda:0")
+    with pytest.raises(ftk.FtkError):
+        ftk.kmeans_assign_fast(Xd, torch.zeros(4, 8, dtype=torch.float64, device="cuda:0"))
+    with pytest.raises(ftk.FtkError):
+        ftk.kmeans_assign_fast(torch.zeros(64, 6, device="cuda:0"), torch.zeros(4, 6, device="cuda:0"))
