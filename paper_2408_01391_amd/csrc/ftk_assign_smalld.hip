@@ -174,11 +174,13 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
         __syncthreads();
     }
 
-    // Blocks of SMALLD_WAVES units (PT*32 points per wave) are handed out dynamically from an
-    // atomic counter so that nothing idles while a queue remains.  The waves of a workgroup
-    // deliberately stay in step (one barrier per block): fp32 matrix and vector instructions
-    // share the issue path, and waves that drift into different phases (one multiplying, one
-    // reducing) interleave them finely, which measurably costs throughput.
+    // Blocks of SMALLD_WAVES units (PT*32 points per wave).  While chunks have to be staged (or
+    // faults are listed per block) the waves of a workgroup walk the blocks in step and draw them
+    // from an atomic counter, one draw per block.  With every tile resident nothing ties the
+    // waves together: each then takes every gridDim-th block on its own, without barriers, so the
+    // memory latencies at the start and the end of a block (point rows, exact re-evaluation) of
+    // one wave run under the matrix work of the others.  (A counter drawn per wave instead would
+    // put one device-wide atomic on the same word per 64 points, which costs more than it saves.)
     int blk = blockIdx.x;
     while (blk < a.nblocks) {
         const int64_t p0 = ((int64_t)blk * SMALLD_WAVES + wave) * (PT * 32);
@@ -430,6 +432,10 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
             }
             // NaN scores, a third candidate, or a failed repair: exact recomputation
             worklist_push(live && g == 0 && (!(thr == thr) || over || forced), (int32_t)p, a.wl, a.wl_count);
+        }
+        if (resident && a.n_faults == 0) {
+            blk += (int)gridDim.x;
+            continue;
         }
         __syncthreads();
         if (tid == 0) sh_next = (int)gridDim.x + atomicAdd(a.wl_count + 1, 1);
