@@ -872,9 +872,13 @@ static UpdateLaunch plan_update_launch(ftk_dtype dtype, const void *X, int64_t N
     UpdateLaunch L;
     L.u = plan_update(dtype, X, N, D, K);
     const size_t esz = dtype == FTK_F32 ? 4 : 8;
-    // rows of at least half a cache line gather efficiently; small problems are launch bound and
-    // take the two-kernel LDS path instead of the six-kernel sorted one
-    L.sorted_path = (size_t)D * esz >= 64 && N >= 65536;
+    // Rows of at least half a cache line gather efficiently, and the label-sorted path streams
+    // them at nearly the HBM rate - but it is six kernels with a fixed cost of about 45 us.
+    // The two-kernel LDS path is taken for short rows, for small problems, and wherever the
+    // table is at most four 64 KB slices and X at most 256 MB (measured crossover: it reads every
+    // row once per slice-wide piece and pays LDS atomics per element, which the sorted path does not).
+    const bool small_table = (int64_t)K * D <= 4 * UPD_CELLS && (double)N * D * esz <= 268435456.0;
+    L.sorted_path = (size_t)D * esz >= 64 && N >= 65536 && !small_table;
     L.E = L.u.aligned ? (dtype == FTK_F32 ? 4 : 2) : 1;
     L.pieces = (int)ceil_div(D, L.E);
     L.lpr_log2 = 0;

@@ -54,7 +54,10 @@ def test_assign_offset_data_needs_the_exact_tie_break():
 
 @pytest.mark.parametrize("dtype", ["f32", "f64"])
 @pytest.mark.parametrize("N,D,K", [(1, 1, 1), (1000, 8, 16), (5000, 128, 256), (3001, 17, 700),
-                                   (4096, 512, 64), (20000, 32, 4096), (999, 3, 5)])
+                                   (4096, 512, 64), (20000, 32, 4096), (999, 3, 5),
+                                   # N >= 65536 with rows of a cache line or more: LDS tables while K*D
+                                   # fits four of them, the label-sorted path beyond
+                                   (70000, 64, 100), (70000, 64, 600), (66000, 40, 900)])
 def test_update_matches_oracle(dtype, N, D, K):
     X, C = synth.random_problem(N + D + K, N, D, K, dtype)
     rng = np.random.default_rng(N)

@@ -22,9 +22,10 @@ SHAPES = [
     ("tables f32 unaligned", 3000, 33, 50, "f32"),
     ("tables f64", 3000, 6, 40, "f64"),
     ("tables f32 sliced (K*D > one table)", 30000, 40, 300, "f32"),
-    ("sorted f32", 70000, 64, 100, "f32"),
-    ("sorted f32 unaligned", 70000, 33, 50, "f32"),
-    ("sorted f64", 66000, 16, 30, "f64"),
+    ("tables f32, long rows", 70000, 64, 100, "f32"),
+    ("sorted f32 (K*D beyond four tables)", 70000, 64, 600, "f32"),
+    ("sorted f32 unaligned", 70000, 33, 1000, "f32"),
+    ("sorted f64", 66000, 16, 2100, "f64"),
 ]
 
 
