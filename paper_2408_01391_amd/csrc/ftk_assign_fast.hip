@@ -59,14 +59,12 @@ struct FastArgs {
 // 16-byte units per centroid row in the LDS image: 3 pieces of NQ blocks, padded to an odd count
 // so that the 32 rows of a tile spread over the banks
 static constexpr int fast_row_units(int nq) { return (3 * nq + 1) % 2 ? 3 * nq + 1 : 3 * nq + 2; }
-#ifndef FAST_NQ1_WAVES
-#define FAST_NQ1_WAVES 16
-#define FAST_NQ1_WPS 4
-#define FAST_NQ1_PT 2
-#endif
-static constexpr int fast_waves(int nq) { return nq == 1 ? FAST_NQ1_WAVES : 8; }
-static constexpr int fast_waves_per_simd(int nq) { return nq == 1 ? FAST_NQ1_WPS : 2; }
-static constexpr int fast_pt(int nq) { return nq == 1 ? FAST_NQ1_PT : 2; }
+// One workgroup per CU: 16 waves (4 per SIMD, 128 registers) for D <= 8, else 8 waves (2 per SIMD,
+// 256 registers for the point fragments); two point tiles per wave.  Measured alternatives for
+// D = 8 (8 waves, four point tiles per wave) came out within 5 %.
+static constexpr int fast_waves(int nq) { return nq == 1 ? 16 : 8; }
+static constexpr int fast_waves_per_simd(int nq) { return nq == 1 ? 4 : 2; }
+static constexpr int fast_pt(int nq) { (void)nq; return 2; }
 
 __device__ __forceinline__ void split3(float x, __bf16 &p0, __bf16 &p1, __bf16 &p2)
 {

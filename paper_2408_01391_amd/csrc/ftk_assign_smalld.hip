@@ -63,16 +63,12 @@ struct SmallArgs {
     float widen;          // 1 in strict mode (the ambiguity band grows by the threshold), else 0
 };
 
-#ifndef SMALLD_FT1_WAVES
-#define SMALLD_FT1_WAVES 8
-#define SMALLD_FT1_MINW 4
-#endif
 // waves per workgroup sharing one staged centroid chunk (measured: 8 beats 4 for every D <= 32,
 // even where the exact re-evaluation then spills a few registers)
-static constexpr int smalld_waves(int nq, bool ft) { return (nq == 1 && ft) ? SMALLD_FT1_WAVES : (nq <= 4 ? 8 : 4); }
+static constexpr int smalld_waves(int nq, bool ft) { return nq <= 4 ? 8 : 4; }
 // waves per SIMD the register budget is sized for (the second launch-bound is waves per
 // execution unit): two resident workgroups of eight waves need four
-static constexpr int smalld_min_wgs(int nq, bool ft) { return (nq == 1 && ft) ? SMALLD_FT1_MINW : (nq <= 1 ? 4 : 2); }
+static constexpr int smalld_min_wgs(int nq, bool ft) { return nq <= 1 ? 4 : 2; }
 constexpr int SMALLD_MAX_FAULTS = 4;  // injected faults honoured per point block
 
 // Sum of the 15 scores of one lane group, added pairwise: partial sums stay small, which roughly
