@@ -202,6 +202,17 @@ ftk_status ftk_seeded_indices(uint64_t seed, int64_t N, int32_t K, int64_t *idx_
 ftk_status ftk_profile_enable(int32_t on);
 ftk_status ftk_profile_read(double *total_ms, int64_t *launches);
 
+/* Hook for the shape-sweep / tuning tool (the counterpart of the paper's kernel selection,
+ * Section 3.2: measure the candidates per problem shape, keep the fastest).  Forces, for every
+ * later call of this process, the choices the library otherwise makes by rule; -1 restores a
+ * rule.  Every forced choice computes the same results.
+ *   assign_variant : 0 = generic kernel, 1 = small-D kernel where it applies (fp32, D <= 32)
+ *   generic_tiles  : centroid tiles per chunk of the generic kernel, 1, 2 or 4
+ *   update_path    : 0 = per-workgroup LDS tables, 1 = label-sorted gather
+ * Process-wide and not synchronised: set it while no call is in flight.  The workspace size
+ * does not depend on it. */
+ftk_status ftk_tuning_override(int32_t assign_variant, int32_t generic_tiles, int32_t update_path);
+
 const char *ftk_last_error(void);
 const char *ftk_version(void);
 

@@ -67,6 +67,8 @@ def load():
     L.ftk_profile_enable.restype = i32
     L.ftk_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     L.ftk_profile_read.restype = i32
+    L.ftk_tuning_override.argtypes = [i32, i32, i32]
+    L.ftk_tuning_override.restype = i32
     L.ftk_last_error.restype = ctypes.c_char_p
     L.ftk_version.restype = ctypes.c_char_p
     _lib = L
@@ -75,7 +77,7 @@ def load():
 
 EXPORTS = ("ftk_workspace_bytes", "ftk_assign_geometry", "ftk_kmeans_assign", "ftk_kmeans_assign_fast", "ftk_absmax",
            "ftk_kmeans_update", "ftk_kmeans_update_ft", "ftk_update_geometry", "ftk_kmeans_fit", "ftk_seeded_indices", "ftk_profile_enable",
-           "ftk_profile_read", "ftk_last_error", "ftk_version")
+           "ftk_profile_read", "ftk_tuning_override", "ftk_last_error", "ftk_version")
 
 
 def _check(rc):
@@ -184,6 +186,11 @@ def kmeans_assign_fast(X, C, labels=None, mindist=None, workspace=None, want_min
     _check(load().ftk_kmeans_assign_fast(_dtype_code(X), X.data_ptr(), C.data_ptr(), N, D, K,
                                          labels.data_ptr(), _ptr(mindist), wp, wn, _stream()))
     return labels, mindist
+
+
+def tuning_override(assign_variant: int = -1, generic_tiles: int = -1, update_path: int = -1):
+    """Force kernel choices for later calls (-1 = built-in rule); for the shape-sweep tool and tests."""
+    _check(load().ftk_tuning_override(assign_variant, generic_tiles, update_path))
 
 
 def absmax(X: torch.Tensor) -> torch.Tensor:

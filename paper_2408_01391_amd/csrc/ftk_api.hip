@@ -11,6 +11,7 @@
 namespace ftk {
 
 static thread_local char g_err[512] = "";
+Tuning g_tuning = {-1, -1, -1};
 
 void set_error(const char *fmt, ...)
 {
@@ -38,7 +39,13 @@ AssignPlan plan_assign(ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft,
 {
     AssignPlan p;
     memset(&p, 0, sizeof(p));
-    if (aligned16 && smalld_supported(dtype, D, K))
+    // The small-D kernel keeps the point fragments in registers and wins wherever there are enough
+    // centroids to sweep; with few of them (K <= 128) and rows beyond 8 features the generic kernel
+    // with its one- and two-tile blockings is faster (measured with the shape sweep's --tune: e.g.
+    // D = 32, K = 32: 52 against 85 us for 2^20 points).
+    const bool few_centroids = D > 8 && K <= 128;
+    const bool want_smalld = g_tuning.assign_variant == 1 || (g_tuning.assign_variant == -1 && !few_centroids);
+    if (aligned16 && smalld_supported(dtype, D, K) && want_smalld)
         plan_smalld(N, D, K, ft, p);
     else
         plan_generic(dtype, N, D, K, p);
@@ -228,6 +235,17 @@ ftk_status ftk_profile_read(double *total_ms, int64_t *launches)
     g_profile_events.clear();
     *total_ms = sum;
     *launches = n;
+    return FTK_OK;
+}
+
+ftk_status ftk_tuning_override(int32_t assign_variant, int32_t generic_tiles, int32_t update_path)
+{
+    if (assign_variant < -1 || assign_variant > 1 || update_path < -1 || update_path > 1 ||
+        !(generic_tiles == -1 || generic_tiles == 1 || generic_tiles == 2 || generic_tiles == 4)) {
+        set_error("tuning override out of range (%d, %d, %d)", assign_variant, generic_tiles, update_path);
+        return FTK_EINVAL;
+    }
+    g_tuning = Tuning{assign_variant, generic_tiles, update_path};
     return FTK_OK;
 }
 

@@ -770,6 +770,7 @@ void plan_generic(ftk_dtype dtype, int64_t N, int D, int K, AssignPlan &p)
     p.TN = f32 ? Mma<float>::TN : Mma<double>::TN;
     p.PT = 2;
     p.KT = f32 ? generic_kt<float>(K) : generic_kt<double>(K);
+    if (g_tuning.kt > 0) p.KT = g_tuning.kt;
     p.waves = 4;
     p.KC = p.KT * p.TM;
     p.nkc = (int)ceil_div(K, p.KC);

@@ -538,8 +538,9 @@ void plan_smalld(int64_t N, int D, int K, ftk_ft_mode ft, AssignPlan &p)
     const int tiles_total = (int)ceil_div(K, FT ? 30 : 32);
     // chunk: as many tiles as fit the LDS share of a workgroup, all of them if possible.  D <= 8
     // runs two workgroups per CU (72 KB each); wider rows need more than 128 registers per lane,
-    // so one workgroup has the CU to itself and can stage twice as much
-    int tpc = ((p.D8 <= 8 ? 72 : 144) * 1024) / tile_bytes;
+    // so one workgroup has the CU to itself and can stage nearly all of its 160 KB (156 KB: 1024
+    // centroids of 32 features stay resident)
+    int tpc = ((p.D8 <= 8 ? 72 : 156) * 1024) / tile_bytes;
     if (tpc > tiles_total) tpc = tiles_total;
     // equal chunks: the same number of passes, but no short last chunk paying a full stage
     tpc = (int)ceil_div(tiles_total, ceil_div(tiles_total, tpc));

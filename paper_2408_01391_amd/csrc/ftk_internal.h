@@ -27,6 +27,14 @@ ftk_status hip_failed(hipError_t e, const char *what);
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// ---- kernel-selection overrides (ftk_tuning_override; -1 = built-in rule) ------------------
+struct Tuning {
+    int assign_variant;  // 0 generic, 1 small-D where it applies
+    int kt;              // centroid tiles per chunk of the generic kernel: 1, 2 or 4
+    int update_path;     // 0 LDS tables, 1 label-sorted
+};
+extern Tuning g_tuning;
+
 // ---- assignment kernel geometry ----------------------------------------------------------
 // One output tile of the matrix instruction covers TM centroids (rows, register axis) by TN
 // points (columns, lane axis).  A wave owns PT point tiles and keeps KT centroid tiles of

@@ -31,12 +31,12 @@ struct UpdatePlan {
     bool aligned;
 };
 
-// Row chunks of the LDS path never exceed UPD_TARGET_WGS or one per UPD_THREADS rows; with S
+// Row chunks of the LDS path never exceed UPD_TARGET_WGS or one per 64 rows; with S
 // slices of at most UPD_CELLS cells covering the K*D table, chunks <= UPD_TARGET_WGS / S, hence
 // chunks * K * D <= UPD_TARGET_WGS * UPD_CELLS whenever more than one chunk is used.
 int64_t update_slab_chunks_max(int64_t N)
 {
-    const int64_t by_rows = ceil_div(N, UPD_THREADS);
+    const int64_t by_rows = ceil_div(N, 64);
     return by_rows < UPD_TARGET_WGS ? (by_rows < 1 ? 1 : by_rows) : UPD_TARGET_WGS;
 }
 // walkers of the label-sorted path: one per RED_ROWS_PER_LANE_MIN rows at most
@@ -72,15 +72,20 @@ static UpdatePlan plan_update(ftk_dtype dtype, const void *X, int64_t N, int D, 
     u.nds = (int)ceil_div(D, u.Ds);
     u.nks = (int)ceil_div(K, u.Ks);
     const int slices = u.nds * u.nks;
-    int chunks = UPD_TARGET_WGS / slices;
-    if (chunks < 1) chunks = 1;
-    if (chunks > ceil_div(N, UPD_THREADS)) chunks = (int)ceil_div(N, UPD_THREADS);
-    u.chunks = chunks;
-    u.rows_per_chunk = ceil_div(N, chunks);
     const int ppr = u.aligned ? (u.Ds + E - 1) / E : u.Ds;  // pieces per row slice
     int l2 = 0;
     while ((1 << l2) < ppr && l2 < 8) ++l2;
     u.tx_log2 = l2;
+    // a workgroup takes UPD_THREADS >> tx_log2 rows per pass; at least 16 passes (and 64 rows) per
+    // chunk, so that long rows of a mid-sized problem still spread over all CUs
+    int64_t min_rows = (int64_t)16 * (UPD_THREADS >> l2);
+    if (min_rows > UPD_THREADS) min_rows = UPD_THREADS;
+    if (min_rows < 64) min_rows = 64;
+    int chunks = UPD_TARGET_WGS / slices;
+    if (chunks < 1) chunks = 1;
+    if (chunks > ceil_div(N, min_rows)) chunks = (int)ceil_div(N, min_rows);
+    u.chunks = chunks;
+    u.rows_per_chunk = ceil_div(N, chunks);
     return u;
 }
 
@@ -875,10 +880,11 @@ static UpdateLaunch plan_update_launch(ftk_dtype dtype, const void *X, int64_t N
     // Rows of at least half a cache line gather efficiently, and the label-sorted path streams
     // them at nearly the HBM rate - but it is six kernels with a fixed cost of about 45 us.
     // The two-kernel LDS path is taken for short rows, for small problems, and wherever the
-    // table is at most four 64 KB slices and X at most 256 MB (measured crossover: it reads every
+    // table is at most four 64 KB slices and X below 256 MB (measured crossover: it reads every
     // row once per slice-wide piece and pays LDS atomics per element, which the sorted path does not).
-    const bool small_table = (int64_t)K * D <= 4 * UPD_CELLS && (double)N * D * esz <= 268435456.0;
+    const bool small_table = (int64_t)K * D <= 4 * UPD_CELLS && (double)N * D * esz < 268435456.0;
     L.sorted_path = (size_t)D * esz >= 64 && N >= 65536 && !small_table;
+    if (g_tuning.update_path >= 0) L.sorted_path = g_tuning.update_path == 1;
     L.E = L.u.aligned ? (dtype == FTK_F32 ? 4 : 2) : 1;
     L.pieces = (int)ceil_div(D, L.E);
     L.lpr_log2 = 0;
