@@ -190,6 +190,16 @@ ftk_status ftk_kmeans_fit(ftk_dtype dtype, const void *X, int64_t N, int32_t D, 
                           ftk_ft_mode ft, ftk_ft_stats *stats, void *workspace,
                           size_t workspace_bytes, void *hip_stream);
 
+/* The same loop with the assignment on the split-bf16 matrix path (ftk_kmeans_assign_fast) and
+ * the plain update: fp32 data with D <= 32, D a multiple of 4, X 16-byte aligned; no fault
+ * tolerance on this path.  Arguments as for ftk_kmeans_fit; workspace of
+ * ftk_workspace_bytes(dtype, N, D, K, FTK_FT_OFF) bytes. */
+ftk_status ftk_kmeans_fit_fast(ftk_dtype dtype, const void *X, int64_t N, int32_t D, int32_t K,
+                               int32_t iters, uint64_t seed, const void *C_init /* nullable */,
+                               void *C_out, int32_t *labels_out, int32_t *counts_out,
+                               double *inertia_per_iter /* (host) nullable */, void *workspace,
+                               size_t workspace_bytes, void *hip_stream);
+
 /* (host) K distinct indices in [0, N) by the seeded procedure ftk_kmeans_fit uses. */
 ftk_status ftk_seeded_indices(uint64_t seed, int64_t N, int32_t K, int64_t *idx_host);
 

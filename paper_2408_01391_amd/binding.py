@@ -61,6 +61,8 @@ def load():
     L.ftk_update_geometry.restype = i32
     L.ftk_kmeans_fit.argtypes = [i32, vp, i64, i32, i32, i32, u64, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
     L.ftk_kmeans_fit.restype = i32
+    L.ftk_kmeans_fit_fast.argtypes = [i32, vp, i64, i32, i32, i32, u64, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.ftk_kmeans_fit_fast.restype = i32
     L.ftk_seeded_indices.argtypes = [u64, i64, i32, vp]
     L.ftk_seeded_indices.restype = i32
     L.ftk_profile_enable.argtypes = [i32]
@@ -76,7 +78,7 @@ def load():
 
 
 EXPORTS = ("ftk_workspace_bytes", "ftk_assign_geometry", "ftk_kmeans_assign", "ftk_kmeans_assign_fast", "ftk_absmax",
-           "ftk_kmeans_update", "ftk_kmeans_update_ft", "ftk_update_geometry", "ftk_kmeans_fit", "ftk_seeded_indices", "ftk_profile_enable",
+           "ftk_kmeans_update", "ftk_kmeans_update_ft", "ftk_update_geometry", "ftk_kmeans_fit", "ftk_kmeans_fit_fast", "ftk_seeded_indices", "ftk_profile_enable",
            "ftk_profile_read", "ftk_tuning_override", "ftk_last_error", "ftk_version")
 
 
@@ -249,8 +251,9 @@ def profile_read():
 
 
 def kmeans_fit(X, K, iters, seed=0, C_init=None, ft_mode=FT_OFF, stats=None, workspace=None,
-               want_inertia=True):
-    """Lloyd loop.  Returns dict(C, labels, counts, inertia (numpy, host) or None)."""
+               want_inertia=True, fast=False):
+    """Lloyd loop.  Returns dict(C, labels, counts, inertia (numpy, host) or None).
+    fast=True runs the assignment on the split-bf16 matrix path (fp32, D <= 32, FT off)."""
     import numpy as np
     _dev2d(X, "X")
     N, D = X.shape
@@ -265,6 +268,13 @@ def kmeans_fit(X, K, iters, seed=0, C_init=None, ft_mode=FT_OFF, stats=None, wor
     if workspace is None:
         workspace = new_workspace(X, K, ft_mode)
     wp, wn = _ws_args(workspace)
+    if fast:
+        if ft_mode != FT_OFF or stats is not None:
+            raise ValueError("the fast path carries no fault tolerance")
+        _check(load().ftk_kmeans_fit_fast(_dtype_code(X), X.data_ptr(), N, D, K, iters, seed & (2**64 - 1),
+                                          _ptr(C_init), C.data_ptr(), labels.data_ptr(), counts.data_ptr(),
+                                          None if inertia is None else inertia.ctypes.data, wp, wn, _stream()))
+        return dict(C=C, labels=labels, counts=counts, inertia=inertia)
     _check(load().ftk_kmeans_fit(_dtype_code(X), X.data_ptr(), N, D, K, iters, seed & (2**64 - 1),
                                  _ptr(C_init), C.data_ptr(), labels.data_ptr(), counts.data_ptr(),
                                  None if inertia is None else inertia.ctypes.data, ft_mode,

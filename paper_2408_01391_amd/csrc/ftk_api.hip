@@ -407,13 +407,21 @@ ftk_status ftk_seeded_indices(uint64_t seed, int64_t N, int32_t K, int64_t *idx_
     return FTK_OK;
 }
 
-ftk_status ftk_kmeans_fit(ftk_dtype dtype, const void *X, int64_t N, int32_t D, int32_t K,
-                          int32_t iters, uint64_t seed, const void *C_init, void *C_out,
-                          int32_t *labels_out, int32_t *counts_out, double *inertia_per_iter,
-                          ftk_ft_mode ft, ftk_ft_stats *stats, void *workspace,
-                          size_t workspace_bytes, void *hip_stream)
+static ftk_status fit_impl(ftk_dtype dtype, const void *X, int64_t N, int32_t D, int32_t K,
+                           int32_t iters, uint64_t seed, const void *C_init, void *C_out,
+                           int32_t *labels_out, int32_t *counts_out, double *inertia_per_iter,
+                           ftk_ft_mode ft, ftk_ft_stats *stats, void *workspace,
+                           size_t workspace_bytes, void *hip_stream, bool fast)
 {
     FTK_TRY(check_problem(dtype, N, D, K, ft));
+    if (fast) {
+        if (!fast_supported(dtype, D)) {
+            set_error("the fast assignment covers fp32 data with D <= 32 and D a multiple of 4 (got dtype=%d D=%d)",
+                      (int)dtype, D);
+            return FTK_EINVAL;
+        }
+        FTK_TRY(check_ptr(X, 16, "X"));
+    }
     if (iters < 0 || iters > FIT_MAX_ITERS_IN_WS) {
         set_error("iters must be in [0, %d]", FIT_MAX_ITERS_IN_WS);
         return FTK_EINVAL;
@@ -446,7 +454,7 @@ ftk_status ftk_kmeans_fit(ftk_dtype dtype, const void *X, int64_t N, int32_t D, 
     FTK_TRY(launch_absmax(dtype, X, N * (int64_t)D, w.absmax, st));
     for (int t = 0; t < iters; ++t) {
         AssignCall c{dtype, X, w.C_cur, N, D, K, labels_out, w.mindist, ft, nullptr, 0, stats};
-        FTK_TRY(assign_impl(c, workspace, st));
+        FTK_TRY(assign_impl(c, workspace, st, fast));
         if (inertia_per_iter)
             FTK_TRY(launch_sum_to_double(dtype, w.mindist, N, w.partials, w.inertia + t, st));
         FTK_TRY(launch_update(dtype, X, labels_out, N, D, K, w.C_cur, counts_out, w.absmax, w, ft, nullptr, 0,
@@ -459,6 +467,25 @@ ftk_status ftk_kmeans_fit(ftk_dtype dtype, const void *X, int64_t N, int32_t D, 
         FTK_TRY_HIP(hipStreamSynchronize(st));
     }
     return FTK_OK;
+}
+
+ftk_status ftk_kmeans_fit(ftk_dtype dtype, const void *X, int64_t N, int32_t D, int32_t K,
+                          int32_t iters, uint64_t seed, const void *C_init, void *C_out,
+                          int32_t *labels_out, int32_t *counts_out, double *inertia_per_iter,
+                          ftk_ft_mode ft, ftk_ft_stats *stats, void *workspace,
+                          size_t workspace_bytes, void *hip_stream)
+{
+    return fit_impl(dtype, X, N, D, K, iters, seed, C_init, C_out, labels_out, counts_out, inertia_per_iter, ft,
+                    stats, workspace, workspace_bytes, hip_stream, false);
+}
+
+ftk_status ftk_kmeans_fit_fast(ftk_dtype dtype, const void *X, int64_t N, int32_t D, int32_t K,
+                               int32_t iters, uint64_t seed, const void *C_init, void *C_out,
+                               int32_t *labels_out, int32_t *counts_out, double *inertia_per_iter,
+                               void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return fit_impl(dtype, X, N, D, K, iters, seed, C_init, C_out, labels_out, counts_out, inertia_per_iter,
+                    FTK_FT_OFF, nullptr, workspace, workspace_bytes, hip_stream, true);
 }
 
 }  // extern "C"

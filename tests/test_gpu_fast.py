@@ -90,3 +90,24 @@ def test_fast_assign_rejects_what_it_does_not_cover():
         ftk.kmeans_assign_fast(Xd, torch.zeros(4, 8, dtype=torch.float64, device="cuda:0"))
     with pytest.raises(ftk.FtkError):
         ftk.kmeans_assign_fast(torch.zeros(64, 6, device="cuda:0"), torch.zeros(4, 6, device="cuda:0"))
+
+
+@pytest.mark.parametrize("name,iters", [("c1", 10), ("c2", 3)])
+def test_fit_on_the_fast_path_matches_the_fp32_fit(name, iters):
+    """Same seeded start, same iteration count: labels identical and centroids bit-identical to the
+    fp32 Lloyd loop (the update is the same integer accumulation, so identical labels give
+    identical centroids), the objective equal to rounding; c1 also against the oracle."""
+    w = synth.WORKLOADS[name]
+    X, _ = synth.make_points(w)
+    C0 = X[synth.init_indices(w, w.N)].copy()
+    Xd, C0d = to_dev(X), to_dev(C0)
+    ref = ftk.kmeans_fit(Xd, w.K, iters, C_init=C0d)
+    out = ftk.kmeans_fit(Xd, w.K, iters, C_init=C0d, fast=True)
+    torch.cuda.synchronize()
+    assert torch.equal(out["labels"], ref["labels"])
+    assert torch.equal(out["C"], ref["C"]) and torch.equal(out["counts"], ref["counts"])
+    assert np.allclose(out["inertia"], ref["inertia"], rtol=1e-6)
+    if name == "c1":
+        o = oracle.fit(X, C0, iters)
+        assert np.array_equal(out["labels"].cpu().numpy(), o["labels"])
+        assert np.allclose(out["C"].cpu().numpy(), o["C"], rtol=1e-4, atol=1e-5)
