@@ -39,7 +39,8 @@ int ftk_abl_naive_assign(int dtype, const void *X, const void *C, int64_t N, int
 size_t ftk_abl_gemm_workspace_bytes(int dtype, int64_t N, int32_t K);
 
 /* The first call creates a rocBLAS handle for the calling process (this allocates and may take
- * seconds); later calls reuse it. */
+ * seconds); later calls reuse it.  One handle is shared: do not call from several threads at
+ * once.  The GEMM interface takes 32-bit extents, so N must be below 2^31. */
 int ftk_abl_gemm_assign(int dtype, const void *X, const void *C, int64_t N, int32_t D, int32_t K,
                         int32_t *labels, void *mindist, void *workspace, size_t workspace_bytes,
                         void *hip_stream);
