@@ -241,7 +241,7 @@ ftk_status ftk_profile_read(double *total_ms, int64_t *launches)
 ftk_status ftk_tuning_override(int32_t assign_variant, int32_t generic_tiles, int32_t update_path)
 {
     if (assign_variant < -1 || assign_variant > 1 || update_path < -1 || update_path > 1 ||
-        !(generic_tiles == -1 || generic_tiles == 1 || generic_tiles == 2 || generic_tiles == 4)) {
+        !(generic_tiles == -1 || generic_tiles == 1 || generic_tiles == 2 || generic_tiles == 4 || generic_tiles == 8)) {
         set_error("tuning override out of range (%d, %d, %d)", assign_variant, generic_tiles, update_path);
         return FTK_EINVAL;
     }

@@ -68,7 +68,8 @@ static double generic_ft_coef(int n, int D)
     return 0.3 * dn * (std::sqrt(dn) + dd);
 }
 
-// Blocking per wave: PT = 2 point tiles by KT centroid tiles of accumulators, DQ quads per LDS
+// Blocking per wave: PT = 2 point tiles by KT centroid tiles of accumulators (KT = 8: one point
+// tile by eight centroid tiles, fp64 only), DQ quads per LDS
 // stage, and the waves per SIMD the register budget is sized for.  KT = 4 is the workhorse (fp64
 // tiles are 16x16, so it leaves room for a third resident wave).  For K of at most one or two
 // tiles the stages hold little matrix work and the kernel is bound by the latency of the point
@@ -76,8 +77,8 @@ static double generic_ft_coef(int n, int D)
 // flight.
 template <typename T, int KT_>
 struct GenericCfg {
-    static constexpr int PT = 2, KT = KT_, WAVES = 4, DQ = 2;
-    static constexpr int WAVES_PER_SIMD = KT_ == 4 ? (sizeof(T) == 4 ? 2 : 3) : (KT_ == 2 ? 3 : 4);
+    static constexpr int PT = KT_ == 8 ? 1 : 2, KT = KT_, WAVES = 4, DQ = 2;
+    static constexpr int WAVES_PER_SIMD = KT_ == 8 ? 2 : (KT_ == 4 ? (sizeof(T) == 4 ? 2 : 3) : (KT_ == 2 ? 3 : 4));
 };
 // number of accumulator tiles used for a problem with K centroids
 template <typename T>
@@ -713,7 +714,15 @@ static ftk_status launch_generic_t(const AssignCall &c, const AssignPlan &p, con
         else if (ft) FTK_LAUNCH_GEN(KV, false, true);          \
         else FTK_LAUNCH_GEN(KV, false, false);                 \
     } while (0)
-    if (p.KT == 4) FTK_LAUNCH_GEN_K(4);
+    bool wide = false;
+    if constexpr (sizeof(T) == 8) {
+        if (p.KT == 8) {
+            FTK_LAUNCH_GEN_K(8);
+            wide = true;
+        }
+    }
+    if (wide) {
+    } else if (p.KT == 4) FTK_LAUNCH_GEN_K(4);
     else if (p.KT == 2) FTK_LAUNCH_GEN_K(2);
     else FTK_LAUNCH_GEN_K(1);
 #undef FTK_LAUNCH_GEN_K
@@ -768,9 +777,16 @@ void plan_generic(ftk_dtype dtype, int64_t N, int D, int K, AssignPlan &p)
     p.variant = VAR_GENERIC;
     p.TM = f32 ? Mma<float>::TM : Mma<double>::TM;
     p.TN = f32 ? Mma<float>::TN : Mma<double>::TN;
-    p.PT = 2;
     p.KT = f32 ? generic_kt<float>(K) : generic_kt<double>(K);
+    // fp64, long rows, more than one chunk of centroids: eight tiles of ONE point tile per wave sweep
+    // twice as many centroids per pass over X, which is what these shapes wait for (X is re-read
+    // once per chunk and 16x16 tiles make chunks small); measured 3-14 % faster from D = 512 on,
+    // slower below (the point fragments are reused half as often).  fp32 tiles are 32 wide and
+    // the same layout measured slower there.
+    if (!f32 && D >= 512 && K > 4 * Mma<double>::TM) p.KT = 8;
     if (g_tuning.kt > 0) p.KT = g_tuning.kt;
+    if (f32 && p.KT == 8) p.KT = 4;
+    p.PT = p.KT == 8 ? 1 : 2;
     p.waves = 4;
     p.KC = p.KT * p.TM;
     p.nkc = (int)ceil_div(K, p.KC);

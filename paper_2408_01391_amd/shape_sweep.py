@@ -65,6 +65,8 @@ def tune(args):
             cands = {"g1": (0, 1), "g2": (0, 2), "g4": (0, 4)}
             if args.dtype == "f32" and D <= 32 and D % 4 == 0:
                 cands["s"] = (1, -1)
+            if args.dtype == "f64":
+                cands["g8"] = (0, 8)  # eight centroid tiles of one point tile (fp64 only)
             times = {}
             for name, (variant, tiles) in cands.items():
                 ftk.tuning_override(variant, tiles, -1)

@@ -26,6 +26,8 @@ SHAPES = [
     ("generic f32 one tile of centroids", 5000, 96, 24, "f32"),
     ("generic f32 two tiles of centroids", 5000, 96, 50, "f32"),
     ("generic f64 two tiles of centroids", 3000, 64, 20, "f64"),
+    ("generic f64 eight tiles of one point tile", 1200, 512, 200, "f64"),
+    ("small-D with few centroids goes generic", 9000, 16, 40, "f32"),
 ]
 
 

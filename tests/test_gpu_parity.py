@@ -17,6 +17,8 @@ SHAPES = [
     (3000, 8, 3000), (1111, 32, 900), (450000, 8, 40), (2500, 12, 77), (9000, 20, 2049),
     # few centroids, many features: the one- and two-tile blockings of the generic kernel
     (4000, 72, 40), (3000, 40, 20), (2000, 100, 64), (70000, 256, 12),
+    # long rows with several chunks of centroids (fp64: eight centroid tiles of one point tile)
+    (1500, 512, 130), (700, 640, 300),
 ]
 
 

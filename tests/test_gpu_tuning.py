@@ -18,7 +18,7 @@ def _restore_rules():
 
 
 @pytest.mark.parametrize("dtype", ["f32", "f64"])
-@pytest.mark.parametrize("variant,tiles", [(0, 1), (0, 2), (0, 4), (1, -1)])
+@pytest.mark.parametrize("variant,tiles", [(0, 1), (0, 2), (0, 4), (0, 8), (1, -1)])
 @pytest.mark.parametrize("N,D,K", [(3000, 8, 70), (2500, 32, 300), (1500, 64, 129), (70000, 16, 20)])
 def test_assign_parity_under_every_forced_kernel(dtype, variant, tiles, N, D, K):
     X, C = synth.random_problem(N + 3 * D + K, N, D, K, dtype)
