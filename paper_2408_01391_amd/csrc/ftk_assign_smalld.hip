@@ -530,7 +530,10 @@ void plan_smalld(int64_t N, int D, int K, ftk_ft_mode ft, AssignPlan &p)
     p.TM = 32;
     p.TN = 32;
     p.D8 = (int)ceil_div(D, 8) * 8;
-    p.PT = 2;
+    // point tiles per wave: two; four for wide rows when there are points enough to keep every
+    // workgroup busy with blocks of 1024 (each centroid fragment then feeds twice the matrix work:
+    // c5 -2 %)
+    p.PT = (p.D8 >= 24 && N >= (1 << 19)) ? 4 : 2;
     p.KT = 1;
     p.waves = smalld_waves(p.D8 / 8, FT);
     const int SW = p.D8 + 4;
@@ -564,6 +567,15 @@ void plan_smalld(int64_t N, int D, int K, ftk_ft_mode ft, AssignPlan &p)
 template <int NQ>
 static void launch_smalld_t(const SmallArgs &a, const AssignPlan &p, bool ft, hipStream_t st)
 {
+    if constexpr (NQ >= 3) {
+        if (p.PT == 4) {
+            if (ft)
+                hipLaunchKernelGGL((assign_smalld_kernel<NQ, 4, true>), dim3(p.grid), dim3(smalld_waves(NQ, true) * 64), p.lds_bytes, st, a);
+            else
+                hipLaunchKernelGGL((assign_smalld_kernel<NQ, 4, false>), dim3(p.grid), dim3(smalld_waves(NQ, false) * 64), p.lds_bytes, st, a);
+            return;
+        }
+    }
     if (ft)
         hipLaunchKernelGGL((assign_smalld_kernel<NQ, 2, true>), dim3(p.grid), dim3(smalld_waves(NQ, true) * 64), p.lds_bytes, st, a);
     else
