@@ -96,6 +96,14 @@ size_t ftk_workspace_bytes(ftk_dtype dtype, int64_t N, int32_t D, int32_t K, ftk
 ftk_status ftk_assign_geometry(ftk_dtype dtype, int64_t N, int32_t D, int32_t K, ftk_ft_mode ft,
                                ftk_geometry *out /* (host) */);
 
+/* (host) Consistency probe of the workspace layout: the kernels pad the K centroid rows up to
+ * whole chunks of their own blocking (Section 3.2: several tile shapes per problem), and the
+ * prologue writes -||c||^2/2 for every padded row.  Reports the largest padded row count over
+ * every kernel variant and fault-tolerance mode that can be dispatched or forced for the problem,
+ * and the rows the workspace reserves; planned_max <= reserved must hold. */
+ftk_status ftk_plan_padded_rows(ftk_dtype dtype, int64_t N, int32_t D, int32_t K,
+                                int64_t *planned_max /* (host) */, int64_t *reserved /* (host) */);
+
 /* Assignment step, Eq. (1), Sections 3.1.2-3.1.5 and 4.
  *   X [N x D], C [K x D]  in  : read only.
  *   labels [N] int32      out : index of the nearest centroid.

@@ -47,6 +47,8 @@ def load():
     L.ftk_workspace_bytes.restype = sz
     L.ftk_assign_geometry.argtypes = [i32, i64, i32, i32, i32, ctypes.POINTER(Geometry)]
     L.ftk_assign_geometry.restype = i32
+    L.ftk_plan_padded_rows.argtypes = [i32, i64, i32, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    L.ftk_plan_padded_rows.restype = i32
     L.ftk_kmeans_assign.argtypes = [i32, vp, vp, i64, i32, i32, vp, vp, i32, vp, i32, vp, vp, sz, vp]
     L.ftk_kmeans_assign.restype = i32
     L.ftk_kmeans_assign_fast.argtypes = [i32, vp, vp, i64, i32, i32, vp, vp, vp, sz, vp]
@@ -77,7 +79,7 @@ def load():
     return L
 
 
-EXPORTS = ("ftk_workspace_bytes", "ftk_assign_geometry", "ftk_kmeans_assign", "ftk_kmeans_assign_fast", "ftk_absmax",
+EXPORTS = ("ftk_workspace_bytes", "ftk_assign_geometry", "ftk_plan_padded_rows", "ftk_kmeans_assign", "ftk_kmeans_assign_fast", "ftk_absmax",
            "ftk_kmeans_update", "ftk_kmeans_update_ft", "ftk_update_geometry", "ftk_kmeans_fit", "ftk_kmeans_fit_fast", "ftk_seeded_indices", "ftk_profile_enable",
            "ftk_profile_read", "ftk_tuning_override", "ftk_last_error", "ftk_version")
 
@@ -109,6 +111,13 @@ def _stream() -> int:
 
 def _ptr(t):
     return None if t is None else t.data_ptr()
+
+
+def plan_padded_rows(dtype_code: int, N: int, D: int, K: int):
+    """(largest padded centroid-row count over all kernel variants, rows the workspace reserves)"""
+    a, b = ctypes.c_int64(0), ctypes.c_int64(0)
+    _check(load().ftk_plan_padded_rows(dtype_code, N, D, K, ctypes.byref(a), ctypes.byref(b)))
+    return a.value, b.value
 
 
 def workspace_bytes(dtype_code: int, N: int, D: int, K: int, ft_mode: int = FT_OFF) -> int:

@@ -58,6 +58,29 @@ ftk_status launch_assign(const AssignCall &c, const AssignPlan &p, const Workspa
                                    : launch_assign_generic(c, p, w, st);
 }
 
+// Entries of the half-norm vector: every kernel variant pads K up to whole chunks of its own
+// size (the small-D kernel to equal LDS chunks of 32-row tiles holding 30 or 32 centroids, the
+// generic one to 1, 2, 4 or 8 tiles), and the prologue writes all of them.  The largest padding
+// over all plans the dispatcher can choose, rounded up to 512, plus one block of slack.
+size_t hcn_entries_max(ftk_dtype dtype, int64_t N, int D, int K)
+{
+    size_t need = (size_t)ceil_div(K, 128) * 128;  // generic: chunks of at most 128 centroids
+    if (smalld_supported(dtype, D, K)) {
+        for (ftk_ft_mode ft : {FTK_FT_OFF, FTK_FT_CORRECT}) {
+            AssignPlan p;
+            memset(&p, 0, sizeof(p));
+            plan_smalld(N, D, K, ft, p);
+            const size_t e = (size_t)p.nkc * p.KC;
+            if (e > need) need = e;
+        }
+    }
+    if (fast_supported(dtype, D)) {
+        const size_t e = (size_t)ceil_div(K, 32) * 32;
+        if (e > need) need = e;
+    }
+    return (size_t)ceil_div((int64_t)need, 512) * 512 + 512;
+}
+
 // The workspace is carved for the larger of the two kernel variants so that its size does not
 // depend on which one the dispatcher picks.
 Workspace carve_workspace(void *base, ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft)
@@ -65,7 +88,7 @@ Workspace carve_workspace(void *base, ftk_dtype dtype, int64_t N, int D, int K, 
     (void)ft;
     const size_t esz = dtype == FTK_F32 ? 4 : 8;
     const size_t D8 = (size_t)ceil_div(D, 8) * 8;
-    const size_t Kpad = (size_t)ceil_div(K, 512) * 512 + 512;   // multiple of every chunk size
+    const size_t Kpad = hcn_entries_max(dtype, N, D, K);        // padded rows of the widest plan
     const size_t ntiles = Kpad / 8;                             // generous: checksum rows per lane group
     char *p = (char *)base;
     size_t off = 0;
@@ -76,6 +99,7 @@ Workspace carve_workspace(void *base, ftk_dtype dtype, int64_t N, int D, int K, 
     };
     Workspace w;
     w.hcn = take(Kpad * esz);
+    w.hcn_entries = Kpad;
     w.scal = (double *)take(8 * sizeof(double));
     w.chk_v1 = take(ntiles * D8 * esz);
     w.chk_v2 = take(ntiles * D8 * esz);
@@ -273,6 +297,38 @@ ftk_status ftk_assign_geometry(ftk_dtype dtype, int64_t N, int32_t D, int32_t K,
     out->regs_per_tile = (uint32_t)p.regs_per_tile;
     out->lanes = 64;
     out->bits = dtype == FTK_F32 ? 32 : 64;
+    return FTK_OK;
+}
+
+ftk_status ftk_plan_padded_rows(ftk_dtype dtype, int64_t N, int32_t D, int32_t K, int64_t *planned_max,
+                                int64_t *reserved)
+{
+    FTK_TRY(check_problem(dtype, N, D, K, FTK_FT_OFF));
+    if (!planned_max || !reserved) {
+        set_error("NULL output");
+        return FTK_EINVAL;
+    }
+    // every plan the dispatcher or a tuning override can produce
+    int64_t worst = 0;
+    const Tuning saved = g_tuning;
+    for (int variant = 0; variant <= 1; ++variant)
+        for (int kt : {1, 2, 4, 8})
+            for (ftk_ft_mode ft : {FTK_FT_OFF, FTK_FT_DETECT, FTK_FT_CORRECT, FTK_FT_STRICT}) {
+                g_tuning = Tuning{variant, kt, -1};
+                const AssignPlan p = plan_assign(dtype, N, D, K, ft, true);
+                const int64_t rows = (int64_t)p.nkc * p.KC;
+                if (rows > worst) worst = rows;
+            }
+    g_tuning = saved;
+    if (fast_supported(dtype, D)) {
+        AssignPlan p;
+        memset(&p, 0, sizeof(p));
+        plan_fast_prologue(D, K, p);
+        const int64_t rows = (int64_t)p.nkc * p.KC;
+        if (rows > worst) worst = rows;
+    }
+    *planned_max = worst;
+    *reserved = (int64_t)hcn_entries_max(dtype, N, D, K);
     return FTK_OK;
 }
 

@@ -66,6 +66,7 @@ AssignPlan plan_assign(ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft,
 struct Workspace {
     // assignment
     void *hcn;          // [Kpad] half squared centroid norms (dtype), zero padded
+    size_t hcn_entries; // Kpad: entries reserved for hcn
     double *scal;       // [8]   0: max_j ||c_j||^2 (as double bits, atomically maximised)
     void *chk_v1;       // [nkc*KT][D8] per-tile plain checksum rows (dtype)
     void *chk_v2;       // [nkc*KT][D8] per-tile weighted checksum rows (dtype)
@@ -93,6 +94,7 @@ struct Workspace {
     size_t total;
 };
 constexpr int FIT_MAX_ITERS_IN_WS = 4096;
+size_t hcn_entries_max(ftk_dtype dtype, int64_t N, int D, int K);
 Workspace carve_workspace(void *base, ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft);
 // upper bounds of the update step's per-workgroup tables, independent of pointer alignment
 int64_t update_slab_chunks_max(int64_t N);

@@ -133,6 +133,10 @@ ftk_status launch_centroid_prologue(const AssignCall &c, const AssignPlan &p, co
                                     hipStream_t st)
 {
     const int Kpad = p.nkc * p.KC;
+    if ((size_t)Kpad > w.hcn_entries) {
+        set_error("internal: plan pads K=%d to %d rows, workspace reserves %zu", c.K, Kpad, w.hcn_entries);
+        return FTK_EWORKSPACE;
+    }
     // lanes per row: 1 for rows up to 32 features, 8 up to 256, else the whole wave
     const int lpr_log2 = c.D <= 32 ? 0 : (c.D <= 256 ? 3 : 6);
     const bool single = (int64_t)Kpad * c.D <= 65536;

@@ -41,3 +41,17 @@ def test_host_only_entry_points_work_without_a_gpu():
     assert g.lanes == 64 and g.bits == 64 and g.workgroups >= 1
     with pytest.raises(binding.FtkError):
         binding.workspace_bytes(binding.F32, 0, 8, 4)
+
+
+def test_workspace_reserves_every_padded_centroid_row():
+    """The prologue writes one half-norm per padded centroid row of the chosen kernel variant; the
+    reservation must cover the widest padding for every K, D, dtype and fault-tolerance mode."""
+    if not binding._LIB_PATH.exists():
+        pytest.skip("libftkmeans.so not built")
+    ks = sorted(set(list(range(1, 200, 7)) + [2 ** e + d for e in range(5, 18) for d in (-1, 0, 1, 29)]
+                    + [6090, 6091, 7560, 7561, 25536, 25537, 100000, 1000003]))
+    for dtype in (binding.F32, binding.F64):
+        for D in (4, 8, 12, 16, 24, 32, 33, 128, 512):
+            for K in ks:
+                planned, reserved = binding.plan_padded_rows(dtype, max(K, 1 << 20), D, K)
+                assert K <= planned <= reserved, (dtype, D, K, planned, reserved)
