@@ -119,6 +119,23 @@ ftk_status ftk_kmeans_assign(ftk_dtype dtype, const void *X, const void *C, int6
                              const ftk_fault *faults, int32_t n_faults, ftk_ft_stats *stats,
                              void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* ftk_kmeans_assign for callers that cannot allocate device memory or size a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * kernels and results as ftk_kmeans_assign, but the scratch (half norms, checksum rows, the
+ * refine work-list and its counters) lives in a static device array inside the library:
+ * ftk_static_scratch_bytes() = 16 MiB per GPU the library runs on, held until the process ends.
+ * The call allocates nothing (no hipMalloc / hipFree, no events; the profiling aid below does
+ * not apply to it).  A problem whose scratch exceeds the array (roughly N > 4 million points, or
+ * K*D beyond a few million) is rejected with FTK_EWORKSPACE and nothing is enqueued.  Every call
+ * on a GPU shares that GPU's array: calls must be ordered on one stream; calls that overlap on
+ * one GPU race.  The buffer keeps the last call's contents; everything that must start at zero
+ * is cleared by the call itself. */
+size_t ftk_static_scratch_bytes(void);
+ftk_status ftk_kmeans_assign_static(ftk_dtype dtype, const void *X, const void *C, int64_t N, int32_t D,
+                                    int32_t K, int32_t *labels, void *mindist /* nullable */,
+                                    ftk_ft_mode ft, const ftk_fault *faults, int32_t n_faults,
+                                    ftk_ft_stats *stats /* nullable */, void *hip_stream);
+
 /* Assignment step on the reduced-precision matrix path - the counterpart of the paper's TF32
  * tensor-core variant (Section 3.1.5; gfx950 has no TF32 format, its fast matrix format is bf16).
  * Same outputs and tie rule as ftk_kmeans_assign with fault tolerance off.  fp32 operands are

@@ -51,6 +51,10 @@ def load():
     L.ftk_plan_padded_rows.restype = i32
     L.ftk_kmeans_assign.argtypes = [i32, vp, vp, i64, i32, i32, vp, vp, i32, vp, i32, vp, vp, sz, vp]
     L.ftk_kmeans_assign.restype = i32
+    L.ftk_kmeans_assign_static.argtypes = [i32, vp, vp, i64, i32, i32, vp, vp, i32, vp, i32, vp, vp]
+    L.ftk_kmeans_assign_static.restype = i32
+    L.ftk_static_scratch_bytes.argtypes = []
+    L.ftk_static_scratch_bytes.restype = sz
     L.ftk_kmeans_assign_fast.argtypes = [i32, vp, vp, i64, i32, i32, vp, vp, vp, sz, vp]
     L.ftk_kmeans_assign_fast.restype = i32
     L.ftk_absmax.argtypes = [i32, vp, i64, vp, vp]
@@ -79,7 +83,7 @@ def load():
     return L
 
 
-EXPORTS = ("ftk_workspace_bytes", "ftk_assign_geometry", "ftk_plan_padded_rows", "ftk_kmeans_assign", "ftk_kmeans_assign_fast", "ftk_absmax",
+EXPORTS = ("ftk_workspace_bytes", "ftk_assign_geometry", "ftk_plan_padded_rows", "ftk_kmeans_assign_static", "ftk_static_scratch_bytes", "ftk_kmeans_assign", "ftk_kmeans_assign_fast", "ftk_absmax",
            "ftk_kmeans_update", "ftk_kmeans_update_ft", "ftk_update_geometry", "ftk_kmeans_fit", "ftk_kmeans_fit_fast", "ftk_seeded_indices", "ftk_profile_enable",
            "ftk_profile_read", "ftk_tuning_override", "ftk_last_error", "ftk_version")
 
@@ -177,6 +181,25 @@ def kmeans_assign(X, C, labels=None, mindist=None, ft_mode=FT_OFF, faults=None, 
     _check(load().ftk_kmeans_assign(_dtype_code(X), X.data_ptr(), C.data_ptr(), N, D, K,
                                     labels.data_ptr(), _ptr(mindist), ft_mode, _ptr(faults), nf,
                                     _ptr(stats), wp, wn, _stream()))
+    return labels, mindist
+
+
+def static_scratch_bytes() -> int:
+    return load().ftk_static_scratch_bytes()
+
+
+def kmeans_assign_static(X, C, labels, mindist=None, ft_mode=FT_OFF, faults=None, stats=None):
+    """Assignment step through the entry point that allocates nothing: outputs are the caller's
+    tensors, scratch is the library's static device array.  Returns (labels, mindist)."""
+    _dev2d(X, "X"), _dev2d(C, "C")
+    if X.dtype != C.dtype or X.shape[1] != C.shape[1]:
+        raise ValueError("X [N,D] and C [K,D] must share dtype and D")
+    N, D = X.shape
+    K = C.shape[0]
+    nf = 0 if faults is None else faults.shape[0]
+    _check(load().ftk_kmeans_assign_static(_dtype_code(X), X.data_ptr(), C.data_ptr(), N, D, K,
+                                           labels.data_ptr(), _ptr(mindist), ft_mode, _ptr(faults), nf,
+                                           _ptr(stats), _stream()))
     return labels, mindist
 
 

@@ -3,6 +3,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <utility>
 #include <vector>
 
@@ -83,7 +84,8 @@ size_t hcn_entries_max(ftk_dtype dtype, int64_t N, int D, int K)
 
 // The workspace is carved for the larger of the two kernel variants so that its size does not
 // depend on which one the dispatcher picks.
-Workspace carve_workspace(void *base, ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft)
+Workspace carve_workspace(void *base, ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft,
+                          bool assign_only)
 {
     (void)ft;
     const size_t esz = dtype == FTK_F32 ? 4 : 8;
@@ -107,6 +109,19 @@ Workspace carve_workspace(void *base, ftk_dtype dtype, int64_t N, int D, int K, 
     w.chk_sd = (double *)take(ntiles * 2 * sizeof(double));
     w.wl_count = (int32_t *)take(4 * sizeof(int32_t));
     w.wl = (int32_t *)take((size_t)N * sizeof(int32_t));
+    if (assign_only) {  // the assignment step touches nothing beyond this point
+        w.fx_sums = nullptr;
+        w.upd_slab = nullptr;
+        w.upd_cslab = nullptr;
+        w.absmax = nullptr;
+        w.sort_idx = w.sort_lab = w.sort_cursor = nullptr;
+        w.C_cur = w.mindist = nullptr;
+        w.inertia = w.partials = nullptr;
+        w.idx = nullptr;
+        w.csplit = nullptr;
+        w.total = off;
+        return w;
+    }
     w.fx_sums = (int64_t *)take((size_t)K * D * 2 * sizeof(int64_t));  // two limbs per cell
     {   // shared by the two update paths: per-workgroup tables, or two tagged slots per walker
         const size_t slab_cells = (size_t)update_slab_cells_max(N, D, K);
@@ -197,7 +212,8 @@ static ftk_status check_device()
 static bool g_profile = false;
 static std::vector<std::pair<hipEvent_t, hipEvent_t>> g_profile_events;
 
-static ftk_status assign_impl(const AssignCall &c, void *workspace, hipStream_t st, bool fast = false)
+static ftk_status assign_impl(const AssignCall &c, void *workspace, hipStream_t st, bool fast = false,
+                              bool allow_profile = true)
 {
     const bool aligned16 = ((uintptr_t)c.X % 16 == 0) && ((uintptr_t)c.C % 16 == 0);
     AssignPlan p;
@@ -207,26 +223,66 @@ static ftk_status assign_impl(const AssignCall &c, void *workspace, hipStream_t 
     } else {
         p = plan_assign(c.dtype, c.N, c.D, c.K, c.ft, aligned16);
     }
-    const Workspace w = carve_workspace(workspace, c.dtype, c.N, c.D, c.K, c.ft);
+    // the carve is a prefix of the full one, so the assignment-only layout serves both callers
+    const Workspace w = carve_workspace(workspace, c.dtype, c.N, c.D, c.K, c.ft, !fast);
     FTK_TRY(launch_centroid_prologue(c, p, w, st));
     hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (g_profile) {
+    const bool profile = g_profile && allow_profile;
+    if (profile) {
         FTK_TRY_HIP(hipEventCreate(&e0));
-        FTK_TRY_HIP(hipEventCreate(&e1));
+        if (hipError_t e = hipEventCreate(&e1); e != hipSuccess) {
+            (void)hipEventDestroy(e0);
+            return hip_failed(e, "hipEventCreate");
+        }
         FTK_TRY_HIP(hipEventRecord(e0, st));
     }
     if (fast)
         FTK_TRY(launch_assign_fast(c, w, st));
     else
         FTK_TRY(launch_assign(c, p, w, st));
-    if (g_profile) {
+    if (profile) {
+        g_profile_events.emplace_back(e0, e1);  // owned by the list from here on
         FTK_TRY_HIP(hipEventRecord(e1, st));
-        g_profile_events.emplace_back(e0, e1);
     }
     FTK_TRY(launch_refine(c, w, st));
     return FTK_OK;
 }
 
+}  // namespace ftk
+
+// ---- scratch of the entry point that allocates nothing ------------------------------------
+// One array per GPU, part of the loaded code object, held until the process ends.  In host code
+// its name is only a handle: the device address is looked up once per device and that pointer is
+// what the kernels get.
+#define FTK_STATIC_SCRATCH_BYTES (16u << 20)
+static __device__ __align__(256) unsigned char ftk_static_scratch[FTK_STATIC_SCRATCH_BYTES];
+
+namespace ftk {
+constexpr int STATIC_MAX_DEVICES = 64;
+static std::mutex g_static_mutex;
+static void *g_static_ptr[STATIC_MAX_DEVICES] = {};
+
+static ftk_status static_scratch_of_current_device(void **out)
+{
+    int dev = 0;
+    FTK_TRY_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= STATIC_MAX_DEVICES) {
+        set_error("device ordinal %d beyond the %d this library keeps scratch for", dev, STATIC_MAX_DEVICES);
+        return FTK_EDEVICE;
+    }
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[dev]) {
+        void *ptr = nullptr;
+        FTK_TRY_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(ftk_static_scratch)));
+        if (!ptr || (uintptr_t)ptr % 256) {
+            set_error("static scratch of device %d resolved to %p", dev, ptr);
+            return FTK_EDEVICE;
+        }
+        g_static_ptr[dev] = ptr;
+    }
+    *out = g_static_ptr[dev];
+    return FTK_OK;
+}
 }  // namespace ftk
 
 using namespace ftk;
@@ -352,6 +408,38 @@ ftk_status ftk_kmeans_assign(ftk_dtype dtype, const void *X, const void *C, int6
     FTK_TRY(check_device());
     AssignCall c{dtype, X, C, N, D, K, labels, mindist, ft, faults, n_faults, stats};
     return assign_impl(c, workspace, (hipStream_t)hip_stream);
+}
+
+size_t ftk_static_scratch_bytes(void) { return FTK_STATIC_SCRATCH_BYTES; }
+
+ftk_status ftk_kmeans_assign_static(ftk_dtype dtype, const void *X, const void *C, int64_t N, int32_t D,
+                                    int32_t K, int32_t *labels, void *mindist, ftk_ft_mode ft,
+                                    const ftk_fault *faults, int32_t n_faults, ftk_ft_stats *stats,
+                                    void *hip_stream)
+{
+    FTK_TRY(check_problem(dtype, N, D, K, ft));
+    const size_t esz = dtype == FTK_F32 ? 4 : 8;
+    FTK_TRY(check_ptr(X, esz, "X"));
+    FTK_TRY(check_ptr(C, esz, "C"));
+    FTK_TRY(check_ptr(labels, 4, "labels"));
+    if (mindist) FTK_TRY(check_ptr(mindist, esz, "mindist"));
+    if (n_faults < 0 || (n_faults > 0 && !faults)) {
+        set_error("n_faults=%d with faults=%p", n_faults, (const void *)faults);
+        return FTK_EINVAL;
+    }
+    if (stats) FTK_TRY(check_ptr(stats, 8, "stats"));
+    const size_t need = carve_workspace(nullptr, dtype, N, D, K, ft, true).total;
+    if (need > FTK_STATIC_SCRATCH_BYTES) {
+        set_error("problem needs %zu bytes of scratch, the static buffer holds %zu (N=%lld D=%d K=%d): "
+                  "use ftk_kmeans_assign with a caller workspace", need, (size_t)FTK_STATIC_SCRATCH_BYTES,
+                  (long long)N, D, K);
+        return FTK_EWORKSPACE;
+    }
+    FTK_TRY(check_device());
+    void *scratch = nullptr;
+    FTK_TRY(static_scratch_of_current_device(&scratch));
+    AssignCall c{dtype, X, C, N, D, K, labels, mindist, ft, faults, n_faults, stats};
+    return assign_impl(c, scratch, (hipStream_t)hip_stream, false, false);
 }
 
 ftk_status ftk_kmeans_assign_fast(ftk_dtype dtype, const void *X, const void *C, int64_t N, int32_t D,

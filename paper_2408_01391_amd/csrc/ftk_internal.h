@@ -95,7 +95,9 @@ struct Workspace {
 };
 constexpr int FIT_MAX_ITERS_IN_WS = 4096;
 size_t hcn_entries_max(ftk_dtype dtype, int64_t N, int D, int K);
-Workspace carve_workspace(void *base, ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft);
+// assign_only: stop after the assignment step's buffers (a prefix of the full layout)
+Workspace carve_workspace(void *base, ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft,
+                          bool assign_only = false);
 // upper bounds of the update step's per-workgroup tables, independent of pointer alignment
 int64_t update_slab_chunks_max(int64_t N);
 int64_t update_slab_cells_max(int64_t N, int D, int K);
