@@ -96,6 +96,19 @@ size_t ftk_workspace_bytes(ftk_dtype dtype, int64_t N, int32_t D, int32_t K, ftk
 ftk_status ftk_assign_geometry(ftk_dtype dtype, int64_t N, int32_t D, int32_t K, ftk_ft_mode ft,
                                ftk_geometry *out /* (host) */);
 
+/* (host) The two error scales of the assignment kernel chosen for a problem (16-byte aligned X
+ * and C assumed), both as multiples of B_i = ||x_i|| max_j||c_j|| + max_j||c_j||^2 / 2, in units
+ * of the score s_ij = x_i.c_j - ||c_j||^2/2 (half a squared distance):
+ *   detect_coef : checksum detection threshold of Section 2.3 / 4.1 ("a defined threshold"): a
+ *                 corrupted score is noticed when the error exceeds detect_coef * B_i; 0 with
+ *                 fault tolerance off.  In FTK_FT_CORRECT a smaller error passes and can move
+ *                 point i only between centroids whose squared distances differ by less than
+ *                 2 * detect_coef * B_i; in FTK_FT_STRICT it cannot move it at all.
+ *   band_coef   : scores closer than band_coef * B_i are not ordered by the matrix path but
+ *                 settled by exact re-evaluation. */
+ftk_status ftk_ft_thresholds(ftk_dtype dtype, int64_t N, int32_t D, int32_t K, ftk_ft_mode ft,
+                             double *detect_coef /* (host) */, double *band_coef /* (host) */);
+
 /* (host) Consistency probe of the workspace layout: the kernels pad the K centroid rows up to
  * whole chunks of their own blocking (Section 3.2: several tile shapes per problem), and the
  * prologue writes -||c||^2/2 for every padded row.  Reports the largest padded row count over
@@ -151,8 +164,9 @@ ftk_status ftk_kmeans_assign_fast(ftk_dtype dtype, const void *X, const void *C,
                                   int32_t K, int32_t *labels, void *mindist /* nullable */,
                                   void *workspace, size_t workspace_bytes, void *hip_stream);
 
-/* Largest |x| over `count` elements, written as one double to out_absmax (device).
- * ftk_kmeans_update needs it to fix the scale of its order-independent accumulation. */
+/* Largest finite |x| over `count` elements, written as one double to out_absmax (device); NaN and
+ * Inf elements are skipped.  ftk_kmeans_update needs it to fix the scale of its
+ * order-independent accumulation. */
 ftk_status ftk_absmax(ftk_dtype dtype, const void *X, int64_t count, double *out_absmax,
                       void *hip_stream);
 
@@ -164,7 +178,17 @@ ftk_status ftk_absmax(ftk_dtype dtype, const void *X, int64_t count, double *out
  *   x_absmax              in  : device scalar from ftk_absmax over X, or NULL to have it
  *                               computed here (one more pass over X).
  * The result is bitwise reproducible from run to run: sums are accumulated in 64-bit fixed
- * point, which does not depend on the order of additions. */
+ * point, which does not depend on the order of additions.
+ * Accuracy: every coordinate is quantised once to a multiple of q = x_absmax * 2^-(61 - ceil(log2 N))
+ * (fp32; at least 2^-50 x_absmax) or x_absmax * 2^-50 (fp64) before it is added, so a centroid
+ * coordinate is off by at most q / 2 plus the final rounding to dtype, whatever its own
+ * magnitude: one scale serves all features, and a feature whose values are many orders of
+ * magnitude below the largest |x| of X keeps correspondingly fewer significant bits (for fp32
+ * data and N = 2^20 the full 24 bits down to 2^-17 of the largest; for fp64 a feature 10^6
+ * times smaller than the largest keeps about 31 bits).
+ * X must be finite.  A NaN or Inf coordinate makes the centroid of the cluster its point is
+ * labelled with unspecified (and, in the assignment, gives that point label 0 or any label in
+ * range); all other clusters and points are unaffected, and nothing faults. */
 ftk_status ftk_kmeans_update(ftk_dtype dtype, const void *X, const int32_t *labels, int64_t N,
                              int32_t D, int32_t K, void *C, int32_t *counts,
                              const double *x_absmax, void *workspace, size_t workspace_bytes,

@@ -47,6 +47,9 @@ def load():
     L.ftk_workspace_bytes.restype = sz
     L.ftk_assign_geometry.argtypes = [i32, i64, i32, i32, i32, ctypes.POINTER(Geometry)]
     L.ftk_assign_geometry.restype = i32
+    L.ftk_ft_thresholds.argtypes = [i32, i64, i32, i32, i32, ctypes.POINTER(ctypes.c_double),
+                                    ctypes.POINTER(ctypes.c_double)]
+    L.ftk_ft_thresholds.restype = i32
     L.ftk_plan_padded_rows.argtypes = [i32, i64, i32, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)]
     L.ftk_plan_padded_rows.restype = i32
     L.ftk_kmeans_assign.argtypes = [i32, vp, vp, i64, i32, i32, vp, vp, i32, vp, i32, vp, vp, sz, vp]
@@ -83,7 +86,7 @@ def load():
     return L
 
 
-EXPORTS = ("ftk_workspace_bytes", "ftk_assign_geometry", "ftk_plan_padded_rows", "ftk_kmeans_assign_static", "ftk_static_scratch_bytes", "ftk_kmeans_assign", "ftk_kmeans_assign_fast", "ftk_absmax",
+EXPORTS = ("ftk_workspace_bytes", "ftk_assign_geometry", "ftk_plan_padded_rows", "ftk_ft_thresholds", "ftk_kmeans_assign_static", "ftk_static_scratch_bytes", "ftk_kmeans_assign", "ftk_kmeans_assign_fast", "ftk_absmax",
            "ftk_kmeans_update", "ftk_kmeans_update_ft", "ftk_update_geometry", "ftk_kmeans_fit", "ftk_kmeans_fit_fast", "ftk_seeded_indices", "ftk_profile_enable",
            "ftk_profile_read", "ftk_tuning_override", "ftk_last_error", "ftk_version")
 
@@ -115,6 +118,14 @@ def _stream() -> int:
 
 def _ptr(t):
     return None if t is None else t.data_ptr()
+
+
+def ft_thresholds(dtype_code: int, N: int, D: int, K: int, ft_mode: int = FT_CORRECT):
+    """(detect_coef, band_coef): detection threshold and exact-settlement band of point i are these
+    times ||x_i|| max||c|| + max||c||^2/2, in score units (half a squared distance)."""
+    a, b = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    _check(load().ftk_ft_thresholds(dtype_code, N, D, K, ft_mode, ctypes.byref(a), ctypes.byref(b)))
+    return a.value, b.value
 
 
 def plan_padded_rows(dtype_code: int, N: int, D: int, K: int):

@@ -356,6 +356,20 @@ ftk_status ftk_assign_geometry(ftk_dtype dtype, int64_t N, int32_t D, int32_t K,
     return FTK_OK;
 }
 
+ftk_status ftk_ft_thresholds(ftk_dtype dtype, int64_t N, int32_t D, int32_t K, ftk_ft_mode ft,
+                             double *detect_coef, double *band_coef)
+{
+    FTK_TRY(check_problem(dtype, N, D, K, ft));
+    if (!detect_coef || !band_coef) {
+        set_error("NULL output");
+        return FTK_EINVAL;
+    }
+    const AssignPlan p = plan_assign(dtype, N, D, K, ft, true);
+    *detect_coef = ft == FTK_FT_OFF ? 0.0 : p.ft_coef;
+    *band_coef = p.band_coef;
+    return FTK_OK;
+}
+
 ftk_status ftk_plan_padded_rows(ftk_dtype dtype, int64_t N, int32_t D, int32_t K, int64_t *planned_max,
                                 int64_t *reserved)
 {

@@ -564,105 +564,155 @@ __global__ __launch_bounds__(256, (GenericCfg<T, KTV>::WAVES_PER_SIMD)) void ass
 }
 
 // Exact settlement of the queued points: all K distances of a point in the direct-difference form
-// (double), then the arg-min with the lowest index on ties.  The work is a chain of memory
-// latencies rather than arithmetic, so the kernel spreads it as widely as the queue allows: a
-// short queue gives every point a whole workgroup, a long one gives it a wave; either way each
-// thread keeps JU centroid rows with DU fragments of each in flight, and all loads are clamped
-// into their rows instead of branched around.  Every row is summed in feature order into one
-// accumulator, so identical centroids tie exactly.
-template <typename T, bool ALIGNED, int JU>
-__global__ __launch_bounds__(256) void refine_kernel(const T *X, const T *C, int D, int K,
-                                                     const int32_t *wl, const int32_t *wl_count,
-                                                     int32_t *labels, T *mindist, ftk_ft_stats *stats)
+// (double), then the arg-min with the lowest index on ties.  A workgroup settles a batch of up to
+// P queued points at a time: thread t owns centroid rows t, t + 256, ... and evaluates each of
+// them against all points of the batch, so a centroid row is fetched once per batch instead of
+// once per point (with thousands of queued points the kernel was bound by re-reading C from L2:
+// K*D bytes per point).  The batch size adapts to the queue: one point per workgroup while the
+// queue is shorter than the grid (the work is then a chain of memory latencies and is spread as
+// widely as possible), up to P = 8 beyond.  Point rows are read with wave-uniform addresses (one
+// cache line broadcast per load).  Every (point, centroid) sum adds the features in index order
+// into one accumulator, so identical centroids tie exactly whatever the batch size.
+template <typename T, bool ALIGNED, int JU, int P>
+__device__ __forceinline__ void refine_batch(const T *__restrict__ X, const T *__restrict__ C, int D, int K,
+                                             const int32_t *__restrict__ wl, int first, int np,
+                                             int32_t *labels, T *mindist, double (*sh_best)[8], int (*sh_j)[8])
 {
     constexpr int E = Mma<T>::E;
-    constexpr int DU = 16 / JU;
+    // about sixteen 16-byte loads in flight per thread (centroid rows and point rows together)
+    constexpr int DU_RAW = 16 / (JU + P - 1);
+    constexpr int DU = DU_RAW >= 16 ? 16 : (DU_RAW >= 8 ? 8 : (DU_RAW >= 4 ? 4 : (DU_RAW >= 2 ? 2 : 1)));
     using F = typename Mma<T>::frag_t;
-    __shared__ double sh_best[4];
-    __shared__ int sh_j[4];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int count = *wl_count;
-    const bool wide = count <= (int)gridDim.x;     // a workgroup per point (else a wave per point)
-    const int tpp = wide ? 256 : 64;               // threads per point
-    const int tg = wide ? tid : lane;              // this thread's rank among them
-    const int first = wide ? (int)blockIdx.x : (int)blockIdx.x * 4 + wave;
-    const int stride = wide ? (int)gridDim.x : (int)gridDim.x * 4;
-    for (int w = first; w < count; w += stride) {
-        const int64_t p = wl[w];
-        const T *x = X + p * D;
-        double best = __builtin_huge_val();
-        int bj = 0x7fffffff;
-        for (int j0 = tg; j0 < K; j0 += tpp * JU) {
-            const T *c[JU];
-            double s[JU];
+    const T *x[P];
+    int64_t pidx[P];
 #pragma unroll
-            for (int u = 0; u < JU; ++u) {
-                c[u] = C + (int64_t)min(j0 + tpp * u, K - 1) * D;
-                s[u] = 0.0;
-            }
-            for (int d0 = 0; d0 < D; d0 += E * DU) {
-                F xf[DU], cf[JU][DU];
+    for (int u = 0; u < P; ++u) {  // slots beyond the batch repeat its last point
+        pidx[u] = wl[first + min(u, np - 1)];
+        x[u] = X + pidx[u] * D;
+    }
+    double best[P];
+    int bj[P];
 #pragma unroll
-                for (int v = 0; v < DU; ++v) xf[v] = load_frag_clamped<T, ALIGNED>(x, d0 + v * E, D);
+    for (int u = 0; u < P; ++u) {
+        best[u] = __builtin_huge_val();
+        bj[u] = 0x7fffffff;
+    }
+    for (int j0 = tid; j0 < K; j0 += 256 * JU) {
+        const T *c[JU];
+        double s[JU][P];
 #pragma unroll
-                for (int u = 0; u < JU; ++u)
+        for (int r = 0; r < JU; ++r) {
+            c[r] = C + (int64_t)min(j0 + 256 * r, K - 1) * D;
 #pragma unroll
-                    for (int v = 0; v < DU; ++v) cf[u][v] = load_frag_clamped<T, ALIGNED>(c[u], d0 + v * E, D);
+            for (int u = 0; u < P; ++u) s[r][u] = 0.0;
+        }
+        for (int d0 = 0; d0 < D; d0 += E * DU) {
+            F cf[JU][DU], xf[P][DU];
 #pragma unroll
-                for (int v = 0; v < DU; ++v)
+            for (int r = 0; r < JU; ++r)
 #pragma unroll
-                    for (int e = 0; e < E; ++e) {
-                        const bool keep = d0 + v * E + e < D;
+                for (int v = 0; v < DU; ++v) cf[r][v] = load_frag_clamped<T, ALIGNED>(c[r], d0 + v * E, D);
 #pragma unroll
-                        for (int u = 0; u < JU; ++u) {
-                            const double diff = keep ? (double)xf[v][e] - (double)cf[u][v][e] : 0.0;
-                            s[u] = fma(diff, diff, s[u]);
+            for (int u = 0; u < P; ++u)
+#pragma unroll
+                for (int v = 0; v < DU; ++v) xf[u][v] = load_frag_clamped<T, ALIGNED>(x[u], d0 + v * E, D);
+#pragma unroll
+            for (int v = 0; v < DU; ++v) {
+                // aligned rows hold whole fragments: a fragment is inside the row or (clamped copy)
+                // skipped as a whole, a wave-uniform decision; otherwise elements are masked one by one
+                if (ALIGNED && d0 + v * E >= D) continue;
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    const bool keep = ALIGNED || d0 + v * E + e < D;
+                    double cd[JU];
+#pragma unroll
+                    for (int r = 0; r < JU; ++r) cd[r] = (double)cf[r][v][e];
+#pragma unroll
+                    for (int u = 0; u < P; ++u) {
+                        const double xd = (double)xf[u][v][e];
+#pragma unroll
+                        for (int r = 0; r < JU; ++r) {
+                            const double diff = keep ? xd - cd[r] : 0.0;
+                            s[r][u] = fma(diff, diff, s[r][u]);
                         }
                     }
-            }
-#pragma unroll
-            for (int u = 0; u < JU; ++u) {  // j increases within a thread: first minimum kept
-                const int j = j0 + tpp * u;
-                if (j < K && s[u] < best) {
-                    best = s[u];
-                    bj = j;
                 }
             }
         }
 #pragma unroll
-        for (int mask = 1; mask < 64; mask <<= 1) {
-            const double ob = __shfl_xor(best, mask, 64);
-            const int oj = __shfl_xor(bj, mask, 64);
-            if (ob < best || (ob == best && oj < bj)) {
-                best = ob;
-                bj = oj;
-            }
-        }
-        if (wide) {  // uniform over the workgroup, which walks the queue in step
-            if (lane == 0) {
-                sh_best[wave] = best;
-                sh_j[wave] = bj;
-            }
-            __syncthreads();
+        for (int r = 0; r < JU; ++r) {  // j increases within a thread: first minimum kept
+            const int j = j0 + 256 * r;
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const double ob = sh_best[v];
-                const int oj = sh_j[v];
-                if (ob < best || (ob == best && oj < bj)) {
-                    best = ob;
-                    bj = oj;
-                }
+            for (int u = 0; u < P; ++u) {
+                const bool better = j < K && s[r][u] < best[u];
+                best[u] = better ? s[r][u] : best[u];
+                bj[u] = better ? j : bj[u];
             }
-            __syncthreads();  // the slots are rewritten for the next point
-        }
-        if (tg == 0) {
-            labels[p] = bj == 0x7fffffff ? 0 : bj;
-            if (mindist) mindist[p] = (T)best;
         }
     }
-    if (stats && blockIdx.x == 0 && tid == 0 && count > 0)
+#pragma unroll
+    for (int u = 0; u < P; ++u) {
+#pragma unroll
+        for (int mask = 1; mask < 64; mask <<= 1) {
+            const double ob = __shfl_xor(best[u], mask, 64);
+            const int oj = __shfl_xor(bj[u], mask, 64);
+            const bool take = ob < best[u] || (ob == best[u] && oj < bj[u]);
+            best[u] = take ? ob : best[u];
+            bj[u] = take ? oj : bj[u];
+        }
+        if (lane == 0) {
+            sh_best[wave][u] = best[u];
+            sh_j[wave][u] = bj[u];
+        }
+    }
+    __syncthreads();
+    if (tid < np) {
+        double b = sh_best[0][tid];
+        int j = sh_j[0][tid];
+#pragma unroll
+        for (int v = 1; v < 4; ++v) {
+            const double ob = sh_best[v][tid];
+            const int oj = sh_j[v][tid];
+            if (ob < b || (ob == b && oj < j)) {
+                b = ob;
+                j = oj;
+            }
+        }
+        const int64_t p = wl[first + tid];
+        labels[p] = j == 0x7fffffff ? 0 : j;
+        if (mindist) mindist[p] = (T)b;
+    }
+    __syncthreads();  // the slots are rewritten for the next batch
+}
+
+template <typename T, bool ALIGNED, int JU>
+__global__ __launch_bounds__(256) void refine_kernel(const T *__restrict__ X, const T *__restrict__ C, int D, int K,
+                                                     const int32_t *__restrict__ wl, const int32_t *__restrict__ wl_count,
+                                                     int32_t *labels, T *mindist, ftk_ft_stats *stats)
+{
+    __shared__ double sh_best[4][8];
+    __shared__ int sh_j[4][8];
+    const int count = *wl_count;
+    // batch size: the smallest power of two that lets the grid cover the queue in one round, at most 8
+    const int per_wg = (count + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int bs = per_wg <= 1 ? 1 : (per_wg <= 2 ? 2 : (per_wg <= 4 ? 4 : 8));
+    const int nbatch = (count + bs - 1) / bs;
+    for (int b = blockIdx.x; b < nbatch; b += gridDim.x) {
+        const int first = b * bs;
+        const int np = min(bs, count - first);
+        if (bs == 1)
+            refine_batch<T, ALIGNED, JU, 1>(X, C, D, K, wl, first, np, labels, mindist, sh_best, sh_j);
+        else if (bs == 2)
+            refine_batch<T, ALIGNED, (JU > 4 ? 4 : JU), 2>(X, C, D, K, wl, first, np, labels, mindist, sh_best, sh_j);
+        else if (bs == 4)
+            refine_batch<T, ALIGNED, (JU > 2 ? 2 : JU), 4>(X, C, D, K, wl, first, np, labels, mindist, sh_best, sh_j);
+        else
+            refine_batch<T, ALIGNED, (JU > 2 ? 2 : JU), 8>(X, C, D, K, wl, first, np, labels, mindist, sh_best, sh_j);
+    }
+    if (stats && blockIdx.x == 0 && threadIdx.x == 0 && count > 0)
         atomicAdd((unsigned long long *)&stats->refined, (unsigned long long)count);
 }
 
@@ -685,7 +735,7 @@ static ftk_status launch_generic_t(const AssignCall &c, const AssignPlan &p, con
     a.wl = w.wl;
     a.wl_count = w.wl_count;
     a.stats = c.stats;
-    // Rounding bound of one score.  On this hardware the matrix instructions (fp32 and fp64) return
+    // Rounding bound of one score (band_coef, set by plan_generic).  On this hardware the matrix instructions (fp32 and fp64) return
     // exactly the chain of fused multiply-adds over the contraction index in order, each rounded to
     // nearest even (checked against fmaf/fma chains on several hundred thousand random operands).
     // A score is therefore a chain of D8 fused steps started from the rounded -||c||^2/2; every
@@ -693,14 +743,14 @@ static ftk_status launch_generic_t(const AssignCall &c, const AssignPlan &p, con
     // B = |x|.|c| + ||c||^2/2 (up to 1 + D8 u), so |fl(s) - s| <= (D8 + 1) u B (1 + D8 u).
     // Two scores are compared: twice that, with D8 + 4 absorbing the second-order factor and the
     // fp32 evaluation of B itself.
-    a.band_coef = 2.0 * (p.D8 + 4) * Mma<T>::kEps;
+    a.band_coef = p.band_coef;
     a.chk_v1 = (const T *)w.chk_v1;
     a.chk_v2 = (const T *)w.chk_v2;
     a.chk_s = w.chk_sd;
     a.faults = c.faults;
     a.n_faults = c.n_faults;
     a.ft_mode = (int)c.ft;
-    a.ft_coef = generic_ft_coef<T>(p.KC, c.D) * Mma<T>::kEps;
+    a.ft_coef = p.ft_coef;
     a.widen_coef = c.ft == FTK_FT_STRICT ? a.ft_coef : 0.0;
     const bool aligned = (c.D % Mma<T>::E == 0) && ((uintptr_t)c.X % 16 == 0) && ((uintptr_t)c.C % 16 == 0);
     const bool ft = c.ft != FTK_FT_OFF;
@@ -803,6 +853,9 @@ void plan_generic(ftk_dtype dtype, int64_t N, int D, int K, AssignPlan &p)
     p.hcn_pad_inf = false;
     p.grid = (int)p.workgroups;
     p.kch = p.KC;
+    p.ft_coef = f32 ? generic_ft_coef<float>(p.KC, D) * Mma<float>::kEps
+                    : generic_ft_coef<double>(p.KC, D) * Mma<double>::kEps;
+    p.band_coef = 2.0 * (p.D8 + 4) * (f32 ? Mma<float>::kEps : Mma<double>::kEps);
 }
 
 }  // namespace ftk

@@ -113,7 +113,7 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
     // per-lane event counters, reduced over the wave at the end
     // wave-uniform event counters (scalar registers: counted with ballots)
     int n_injected = 0, n_detected = 0, n_corrected = 0, n_recomputed = 0;
-    float worst_resid = 0.f;
+    float worst_resid = 0.f;  // largest fault-free residual seen by this lane, in units of its threshold
 
     // operand fetch of one centroid tile: A fragments and the accumulator start values
     auto load_tile = [&](int t, floatx4 (&av)[NQ], floatx16 &ci) {
@@ -186,6 +186,7 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
         float inv_tau[PT];
         int force_refine[PT];   // a tile of this point failed correction (int, not bool: a bool
                                 // array updated inside the rare branch lost its value when compiled)
+        float rmax[PT];         // largest |residual| below the threshold over this point's tiles
         TileBest best[PT];
 #pragma unroll
         for (int pt = 0; pt < PT; ++pt) {
@@ -203,6 +204,7 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
             tau[pt] = (float)a.ft_coef * (sqrtf(xn[pt]) * cmax + 0.5f * cmax2);
             inv_tau[pt] = 1.0f / tau[pt];
             force_refine[pt] = 0;
+            rmax[pt] = 0.f;
             best[pt].m1 = best[pt].m2 = M::neg_inf();
             best[pt].t1 = 0;
         }
@@ -261,7 +263,7 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
                 if constexpr (FT) {
                     // verify: the 15 scores of this lane must add up to the carried checksum
                     float resid = sum15(acc) - acc[15];
-                    const bool bad = !(fabsf(resid) <= tau[pt]);
+                    bool bad = !(fabsf(resid) <= tau[pt]);
                     if (__builtin_expect(__any(bad), 0)) {
                         n_detected += (int)__popcll(__ballot(bad));
                         if (a.ft_mode >= FTK_FT_CORRECT) {
@@ -308,8 +310,9 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
                             n_recomputed += (int)__popcll(__ballot(bad && !ok));
                             force_refine[pt] |= (bad && !ok) ? 1 : 0;
                         }
+                        resid = bad ? 0.f : resid;  // statistics: fault-free residuals only
                     }
-                    worst_resid = fmaxf(worst_resid, bad ? 0.f : fabsf(resid) * inv_tau[pt]);
+                    rmax[pt] = max2f(rmax[pt], fabsf(resid));  // one instruction; NaN went the branch above
                     if (__builtin_expect(30 * (T + 1) > a.K, 0)) {  // last tile: rows beyond K carried zeros, now drop them
 #pragma unroll
                         for (int r = 0; r < RG; ++r)
@@ -367,6 +370,7 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
         // ---- exact evaluation of the winning group; the two lanes of a point share its rows ----
 #pragma unroll
         for (int pt = 0; pt < PT; ++pt) {
+            if (FT) worst_resid = fmaxf(worst_resid, rmax[pt] * inv_tau[pt]);
             const int64_t p = p0 + pt * 32 + col;
             const bool live = p < a.N;
             floatx4 xlo[NQ], xhi[NQ];
@@ -562,6 +566,9 @@ void plan_smalld(int64_t N, int D, int K, ftk_ft_mode ft, AssignPlan &p)
     p.tiles_per_wave = tiles_total * p.PT;
     p.regs_per_tile = 16;
     p.hcn_pad_inf = !FT;
+    p.ft_coef = smalld_ft_coef(D);
+    // two scores, each a chain of D8 fused multiply-adds rounded to nearest (see the generic variant)
+    p.band_coef = 2.0 * (p.D8 + 4) * Mma<float>::kEps;
 }
 
 template <int NQ>
@@ -606,15 +613,14 @@ ftk_status launch_assign_smalld(const AssignCall &c, const AssignPlan &p, const 
     a.wl = w.wl;
     a.wl_count = w.wl_count;
     a.stats = c.stats;
-    // two scores, each a chain of D8 fused multiply-adds rounded to nearest (see the generic variant)
-    a.band_coef = 2.0 * (p.D8 + 4) * Mma<float>::kEps;
+    a.band_coef = p.band_coef;
     a.chk_v1 = (const float *)w.chk_v1;
     a.chk_v2 = (const float *)w.chk_v2;
     a.chk_s = (const float *)w.chk_s;
     a.faults = c.faults;
     a.n_faults = c.n_faults;
     a.ft_mode = (int)c.ft;
-    a.ft_coef = smalld_ft_coef(c.D);
+    a.ft_coef = p.ft_coef;
     a.widen = c.ft == FTK_FT_STRICT ? 1.0f : 0.0f;
     switch (p.D8 / 8) {
     case 1: launch_smalld_t<1>(a, p, FT, st); break;

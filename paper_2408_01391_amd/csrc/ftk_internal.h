@@ -59,6 +59,8 @@ struct AssignPlan {
     bool hcn_pad_inf;           // padding rows of the half-norm vector hold +inf (never win)
     int grid;                   // workgroups launched (persistent variants launch fewer)
     int kch;                    // centroids staged in LDS at a time (small-D variant)
+    double ft_coef;             // checksum detection threshold = ft_coef * (||x|| max||c|| + max||c||^2/2)
+    double band_coef;           // rounding band of a score comparison, same scale
 };
 AssignPlan plan_assign(ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft, bool aligned16);
 

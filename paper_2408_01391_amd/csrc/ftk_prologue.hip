@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256) void absmax_kernel(const T *X, int64_t count, 
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
         const double v = fabs((double)X[i]);
-        m = v > m ? v : m;  // NaN never raises the maximum
+        m = (v > m && v < __builtin_huge_val()) ? v : m;  // NaN and Inf never raise the maximum
     }
 #pragma unroll
     for (int mask = 32; mask >= 1; mask >>= 1) {
@@ -215,7 +215,7 @@ __global__ __launch_bounds__(256) void absmax_vec_kernel(const T *X, int64_t nve
 #pragma unroll
         for (int e = 0; e < E; ++e) {
             const T v = fabs(f[e]);
-            m = v > m ? v : m;
+            m = (v > m && v < Mma<T>::huge()) ? v : m;  // NaN and Inf never raise the maximum
         }
     }
     double md = (double)m;

@@ -27,13 +27,15 @@ def exact_dist_to(X, C, rows, labels):
     return (diff * diff).sum(1)
 
 
-def check_assign(X: np.ndarray, C: np.ndarray, labels_g: np.ndarray, mindist_g=None, rows=None):
+def check_assign(X: np.ndarray, C: np.ndarray, labels_g: np.ndarray, mindist_g=None, rows=None, ref=None):
     """Compare GPU labels (for all points, or for the listed rows) with the oracle.
 
+    ``ref`` = (labels, best, second) of an earlier oracle.assign over the same rows, to compare
+    several GPU runs against one oracle pass.
     Returns (number of label differences inside the tie band, number of points checked).
     Raises AssertionError on any difference outside the band.
     """
-    lab_o, d1, d2 = oracle.assign(X, C, rows)
+    lab_o, d1, d2 = oracle.assign(X, C, rows) if ref is None else ref
     idx = np.arange(X.shape[0]) if rows is None else np.asarray(rows)
     lab_g = labels_g[idx]
     assert lab_g.min() >= 0 and lab_g.max() < C.shape[0], "label out of range"
@@ -60,6 +62,33 @@ def check_assign(X: np.ndarray, C: np.ndarray, labels_g: np.ndarray, mindist_g=N
         err = np.abs(md - d1)
         assert np.all(err <= 1e-5 * d1 + atol), "mindist off: max err %g" % err.max()
     return int(diff.size), int(idx.size)
+
+
+def check_moved_labels_within_detection_threshold(X, C, lab, lab_clean, ft_mode):
+    """Labels under injected faults against the fault-free labels of the same mode.
+
+    STRICT: identical.  CORRECT (the paper's scheme): an error below the detection threshold of
+    Section 2.3 passes unnoticed and may move the point whose score it hit, but only to a centroid
+    whose exact squared distance exceeds the oracle's best by less than twice (scores are half
+    distances) the threshold plus the settlement band of THAT point, as the library reports them.
+    Returns the number of moved labels."""
+    diff = np.flatnonzero(lab != lab_clean)
+    if ft_mode == ftk.FT_STRICT:
+        assert diff.size == 0, "%d labels changed under injection in strict mode" % diff.size
+        return 0
+    if diff.size == 0:
+        return 0
+    code = ftk.F32 if X.dtype == np.float32 else ftk.F64
+    detect, band = ftk.ft_thresholds(code, X.shape[0], X.shape[1], C.shape[0], ft_mode)
+    _, d1, _ = oracle.assign(X, C, diff)
+    d_new = exact_dist_to(X, C, diff, lab[diff])
+    cmax2 = (C.astype(np.float64) ** 2).sum(1).max()
+    B = np.sqrt((X[diff].astype(np.float64) ** 2).sum(1) * cmax2) + 0.5 * cmax2
+    tol = 2.0 * (detect + band) * B
+    worst = ((d_new - d1) / tol).max()
+    assert worst <= 1.0, ("%d labels moved, the worst by %.3g of the detection threshold of its point"
+                          % (diff.size, worst))
+    return int(diff.size)
 
 
 def check_centroids(C_g: np.ndarray, C_o: np.ndarray):

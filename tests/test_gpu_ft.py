@@ -2,15 +2,16 @@
 
 With FT on and single-bit flips injected into the accumulators of the matrix instructions,
 the labels must equal those of the fault-free run; without FT the same flips corrupt them.
-STRICT mode guarantees the equality for every point; CORRECT mode (the paper's scheme) lets an
-error below the detection threshold through, which may only move a point between two centroids
-whose distances differ by less than that threshold."""
+STRICT mode guarantees the equality for every point and is asserted as such; CORRECT mode (the
+paper's scheme) lets an error below the detection threshold through, which may only move the
+point it hit, and only to a centroid whose exact distance is within that point's own threshold
+(as reported by ftk_ft_thresholds) of the oracle's best."""
 import numpy as np
 import pytest
 import torch
 
 from paper_2408_01391_amd import binding as ftk, synth
-from tests.gpu_util import DEV, check_assign, to_dev
+from tests.gpu_util import DEV, check_assign, check_moved_labels_within_detection_threshold, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -45,23 +46,7 @@ def _run(X, C, ft_mode, faults=None):
 
 
 def _assert_same_or_within_threshold(X, C, lab, lab_clean, mode):
-    """Equal labels; in CORRECT mode a differing label must be a near-tie inside the (generously
-    modelled) detection threshold 2 u n (sqrt n + sqrt(D+4)) (|x| max|c| + max|c|^2/2), n = 128."""
-    diff = np.nonzero(lab != lab_clean)[0]
-    if mode == ftk.FT_STRICT:
-        assert diff.size == 0, "%d labels changed under injection in strict mode" % diff.size
-        return
-    if diff.size == 0:
-        return
-    Xd, Cd = X[diff].astype(np.float64), C.astype(np.float64)
-    d_new = ((Xd - Cd[lab[diff]]) ** 2).sum(1)
-    d_ref = ((Xd - Cd[lab_clean[diff]]) ** 2).sum(1)
-    u = 2.0 ** -24 if X.dtype == np.float32 else 2.0 ** -53
-    cmax2 = (Cd ** 2).sum(1).max()
-    B = np.sqrt((Xd ** 2).sum(1) * cmax2) + 0.5 * cmax2
-    n, D = 128.0, X.shape[1]
-    tol = 2.0 * u * n * (np.sqrt(n) + np.sqrt(D + 4.0)) * B
-    assert np.all(np.abs(d_new - d_ref) <= tol), "%d labels changed beyond the detection threshold" % diff.size
+    check_moved_labels_within_detection_threshold(X, C, lab, lab_clean, mode)
 
 
 MODES = [ftk.FT_CORRECT, ftk.FT_STRICT]
@@ -126,9 +111,12 @@ def test_high_bit_flips_corrupt_labels_without_ft_and_not_with_it():
     lab_bad, _, st_off = _run(X, C, ftk.FT_OFF, faults)
     assert st_off["injected"] > 0
     assert (lab_bad != lab_clean).sum() > 0, "injection had no visible effect with FT off"
-    lab_ft, _, st = _run(X, C, ftk.FT_CORRECT, faults)
-    assert np.array_equal(lab_ft, lab_clean)
-    assert st["detected"] > 0.9 * st["injected"] > 0    # a flip of a score near zero can stay below the threshold
+    for mode in MODES:
+        lab_ft_clean, _, _ = _run(X, C, mode)
+        lab_ft, _, st = _run(X, C, mode, faults)
+        _assert_same_or_within_threshold(X, C, lab_ft, lab_ft_clean, mode)
+        assert (lab_ft != lab_clean).sum() <= 1e-4 * N          # FT on/off: only near-exact ties may differ
+        assert st["detected"] > 0.9 * st["injected"] > 0    # a flip of a score near zero can stay below the threshold
 
 
 @pytest.mark.parametrize("mode", MODES)

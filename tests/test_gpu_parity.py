@@ -73,6 +73,60 @@ def test_update_matches_oracle(dtype, N, D, K):
         assert np.array_equal(C_g[K - 1], C[K - 1])       # empty cluster keeps its centroid
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f64"])
+def test_update_with_feature_scales_spanning_six_orders_of_magnitude(dtype):
+    """One fixed-point scale serves all features: a feature far below the largest |x| keeps
+    fewer bits.  The documented bound - half a quantum of max|x| 2^-(61 - ceil(log2 N)) (fp32) or
+    max|x| 2^-50 (fp64) plus the final rounding - must hold for every coordinate, and the
+    centroid tolerance of the workloads with it."""
+    N, D, K = 200000, 16, 37
+    X, C = synth.random_problem(99, N, D, K, dtype)
+    scales = np.logspace(-3, 3, D).astype(X.dtype)
+    X = np.ascontiguousarray(X * scales)
+    C = np.ascontiguousarray(C * scales)
+    labels = np.random.default_rng(4).integers(0, K, size=N).astype(np.int32)
+    C_g, counts_g = gpu_update(X, labels, C)
+    C_o, counts_o = oracle.update(X, labels, C)
+    assert np.array_equal(counts_g, counts_o)
+    check_centroids(C_g, C_o)
+    absmax = np.abs(X).max()
+    q = absmax * (2.0 ** -(61 - 18) if dtype == "f32" else 2.0 ** -50)
+    u = 2.0 ** -24 if dtype == "f32" else 2.0 ** -53
+    err = np.abs(C_g.astype(np.float64) - C_o.astype(np.float64))
+    assert np.all(err <= 0.5 * q + 2 * u * np.abs(C_o)), (err / (0.5 * q + 2 * u * np.abs(C_o))).max()
+    # per-feature relative accuracy actually reached (smallest features are 10^6 below the largest)
+    rel = np.median(err / np.maximum(np.abs(C_o), np.finfo(np.float64).tiny), axis=0)
+    print("update, feature scales 1e-3..1e3,", dtype, "median relative error per feature:", rel)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f64"])
+def test_nonfinite_points_only_spoil_their_own_cluster(dtype):
+    """Inputs are required to be finite; a NaN or Inf coordinate must not fault, must leave the
+    labels in range, and must not disturb points and clusters it does not belong to."""
+    N, D, K = 20000, 12, 30
+    X, C = synth.random_problem(123, N, D, K, dtype)
+    bad_rows = np.array([5, 777, 19999])
+    Xb = X.copy()
+    Xb[5, 3] = np.nan
+    Xb[777, 0] = np.inf
+    Xb[19999, 11] = -np.inf
+    for mode in (ftk.FT_OFF, ftk.FT_STRICT):
+        lab_clean, _ = gpu_assign(X, C, ft_mode=mode)
+        lab, _ = gpu_assign(Xb, C, ft_mode=mode)
+        assert lab.min() >= 0 and lab.max() < K
+        keep = np.ones(N, dtype=bool)
+        keep[bad_rows] = False
+        assert np.array_equal(lab[keep], lab_clean[keep])
+    assert float(ftk.absmax(to_dev(Xb)).cpu()[0]) == np.abs(Xb[np.isfinite(Xb)]).max()
+    labels = lab_clean.astype(np.int32)
+    C_g, counts_g = gpu_update(Xb, labels, C)
+    C_o, _ = oracle.update(X, labels, C)
+    spoiled = np.unique(labels[bad_rows])
+    fine = np.setdiff1d(np.arange(K), spoiled)
+    check_centroids(C_g[fine], C_o[fine])
+    assert np.array_equal(counts_g, np.bincount(labels, minlength=K))
+
+
 def test_update_is_bitwise_reproducible():
     X, C = synth.random_problem(77, 50000, 24, 300, "f32")
     labels = np.random.default_rng(0).integers(0, 300, size=50000).astype(np.int32)
