@@ -109,6 +109,7 @@ Workspace carve_workspace(void *base, ftk_dtype dtype, int64_t N, int D, int K, 
     w.chk_sd = (double *)take(ntiles * 2 * sizeof(double));
     w.wl_count = (int32_t *)take(4 * sizeof(int32_t));
     w.wl = (int32_t *)take((size_t)N * sizeof(int32_t));
+    w.wg_refined = (int32_t *)take(((size_t)N / 64 + 2) * sizeof(int32_t));
     if (assign_only) {  // the assignment step touches nothing beyond this point
         w.fx_sums = nullptr;
         w.upd_slab = nullptr;
@@ -244,7 +245,8 @@ static ftk_status assign_impl(const AssignCall &c, void *workspace, hipStream_t 
         g_profile_events.emplace_back(e0, e1);  // owned by the list from here on
         FTK_TRY_HIP(hipEventRecord(e1, st));
     }
-    FTK_TRY(launch_refine(c, w, st));
+    const int n_wg = (!fast && c.stats && p.variant == VAR_GENERIC) ? (int)p.workgroups : 0;
+    FTK_TRY(launch_refine(c, w, n_wg, st));
     return FTK_OK;
 }
 

@@ -33,6 +33,7 @@ struct GenericArgs {
     T *mindist;  // may be null
     int32_t *wl;
     int32_t *wl_count;
+    int32_t *wg_refined;  // [gridDim.x] points this workgroup settled in place (read by the refine kernel)
     ftk_ft_stats *stats;
     double band_coef;  // ambiguity band = band_coef * (||x|| * max||c|| + max||c||^2 / 2)
     // fault tolerance / injection
@@ -556,10 +557,17 @@ __global__ __launch_bounds__(256, (GenericCfg<T, KTV>::WAVES_PER_SIMD)) void ass
         }
     }
     if (a.stats) {
+        // points settled in place: one plain store per workgroup, summed by the refine kernel
+        // (an atomic per wave on the one counter kept the dispatch open for tens of microseconds)
+        __shared__ int sh_refined;
         int n = (int)n_refined;
 #pragma unroll
         for (int mask = 1; mask < 64; mask <<= 1) n += __shfl_xor(n, mask, 64);
-        if (lane == 0 && n) atomicAdd((unsigned long long *)&a.stats->refined, (unsigned long long)n);
+        if (tid == 0) sh_refined = 0;
+        __syncthreads();
+        if (lane == 0 && n) atomicAdd(&sh_refined, n);
+        __syncthreads();
+        if (tid == 0) a.wg_refined[blockIdx.x] = sh_refined;
     }
 }
 
@@ -691,7 +699,8 @@ __device__ __forceinline__ void refine_batch(const T *__restrict__ X, const T *_
 template <typename T, bool ALIGNED, int JU>
 __global__ __launch_bounds__(256) void refine_kernel(const T *__restrict__ X, const T *__restrict__ C, int D, int K,
                                                      const int32_t *__restrict__ wl, const int32_t *__restrict__ wl_count,
-                                                     int32_t *labels, T *mindist, ftk_ft_stats *stats)
+                                                     int32_t *labels, T *mindist, ftk_ft_stats *stats,
+                                                     const int32_t *__restrict__ wg_refined, int n_wg)
 {
     __shared__ double sh_best[4][8];
     __shared__ int sh_j[4][8];
@@ -712,8 +721,20 @@ __global__ __launch_bounds__(256) void refine_kernel(const T *__restrict__ X, co
         else
             refine_batch<T, ALIGNED, (JU > 2 ? 2 : JU), 8>(X, C, D, K, wl, first, np, labels, mindist, sh_best, sh_j);
     }
-    if (stats && blockIdx.x == 0 && threadIdx.x == 0 && count > 0)
-        atomicAdd((unsigned long long *)&stats->refined, (unsigned long long)count);
+    if (stats && blockIdx.x == 0) {
+        // statistics: queued points plus those the main kernel's workgroups settled in place
+        __shared__ int sh_total;
+        if (threadIdx.x == 0) sh_total = count;
+        __syncthreads();
+        int n = 0;
+        for (int i = threadIdx.x; i < n_wg; i += 256) n += wg_refined[i];
+#pragma unroll
+        for (int mask = 1; mask < 64; mask <<= 1) n += __shfl_xor(n, mask, 64);
+        if ((threadIdx.x & 63) == 0 && n) atomicAdd(&sh_total, n);
+        __syncthreads();
+        if (threadIdx.x == 0 && sh_total > 0)
+            atomicAdd((unsigned long long *)&stats->refined, (unsigned long long)sh_total);
+    }
 }
 
 template <typename T>
@@ -734,6 +755,7 @@ static ftk_status launch_generic_t(const AssignCall &c, const AssignPlan &p, con
     a.mindist = (T *)c.mindist;
     a.wl = w.wl;
     a.wl_count = w.wl_count;
+    a.wg_refined = w.wg_refined;
     a.stats = c.stats;
     // Rounding bound of one score (band_coef, set by plan_generic).  On this hardware the matrix instructions (fp32 and fp64) return
     // exactly the chain of fused multiply-adds over the contraction index in order, each rounded to
@@ -789,13 +811,13 @@ ftk_status launch_assign_generic(const AssignCall &c, const AssignPlan &p, const
 }
 
 template <typename T>
-static void launch_refine_t(const AssignCall &c, const Workspace &w, hipStream_t st)
+static void launch_refine_t(const AssignCall &c, const Workspace &w, int n_wg, hipStream_t st)
 {
     const bool aligned = (c.D % Mma<T>::E == 0) && ((uintptr_t)c.X % 16 == 0) && ((uintptr_t)c.C % 16 == 0);
     dim3 grid(1024), block(256);
 #define FTK_LAUNCH_REFINE(AL, JU)                                                                      \
     hipLaunchKernelGGL((refine_kernel<T, AL, JU>), grid, block, 0, st, (const T *)c.X, (const T *)c.C, \
-                       c.D, c.K, w.wl, w.wl_count, c.labels, (T *)c.mindist, c.stats)
+                       c.D, c.K, w.wl, w.wl_count, c.labels, (T *)c.mindist, c.stats, w.wg_refined, n_wg)
 #define FTK_LAUNCH_REFINE_J(JU)                   \
     do {                                          \
         if (aligned) FTK_LAUNCH_REFINE(true, JU); \
@@ -811,12 +833,12 @@ static void launch_refine_t(const AssignCall &c, const Workspace &w, hipStream_t
 #undef FTK_LAUNCH_REFINE
 }
 
-ftk_status launch_refine(const AssignCall &c, const Workspace &w, hipStream_t st)
+ftk_status launch_refine(const AssignCall &c, const Workspace &w, int n_wg, hipStream_t st)
 {
     if (c.dtype == FTK_F32)
-        launch_refine_t<float>(c, w, st);
+        launch_refine_t<float>(c, w, n_wg, st);
     else
-        launch_refine_t<double>(c, w, st);
+        launch_refine_t<double>(c, w, n_wg, st);
     FTK_TRY_HIP(hipGetLastError());
     return FTK_OK;
 }

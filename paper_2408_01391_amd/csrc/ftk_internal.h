@@ -76,6 +76,7 @@ struct Workspace {
     double *chk_sd;     // [nkc][2]     the same per K-chunk, in double (generic variant)
     int32_t *wl_count;  // [4]   refine work-list length (+ padding)
     int32_t *wl;        // [N]   refine work-list (point indices)
+    int32_t *wg_refined;  // [N/64 + 2] points each workgroup of the generic kernel settled in place
     // update
     int64_t *fx_sums;   // [K*D][2] fixed-point sums, two limbs (label-sorted path)
     int64_t *upd_slab;  // [chunks][K*D] per-workgroup fixed-point tables (LDS path), or
@@ -123,7 +124,9 @@ ftk_status launch_centroid_prologue(const AssignCall &c, const AssignPlan &p, co
 ftk_status launch_smalld_checksums(const AssignCall &c, const AssignPlan &p, const Workspace &w,
                                    hipStream_t st);
 ftk_status launch_assign(const AssignCall &c, const AssignPlan &p, const Workspace &w, hipStream_t st);
-ftk_status launch_refine(const AssignCall &c, const Workspace &w, hipStream_t st);
+// n_wg: workgroups of the preceding main kernel that left a settled-in-place count (generic
+// kernel with statistics requested), else 0
+ftk_status launch_refine(const AssignCall &c, const Workspace &w, int n_wg, hipStream_t st);
 bool fast_supported(ftk_dtype dtype, int D);
 size_t fast_split_bytes(ftk_dtype dtype, int D, int K);
 void plan_fast_prologue(int D, int K, AssignPlan &p);
