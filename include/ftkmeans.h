@@ -24,7 +24,9 @@
  *   - Distances are SQUARED Euclidean distances (the square root is dropped, Section 3.1.2).
  *   - Exact ties go to the lowest centroid index.  An empty cluster keeps its centroid.
  *   - Errors are reported by return code, never by abort; ftk_last_error() gives the text of
- *     the last failure on the calling thread.  On error nothing has been enqueued.
+ *     the last failure on the calling thread.  Argument, alignment and workspace errors are
+ *     found before anything is enqueued; a HIP runtime failure (FTK_EDEVICE) may leave kernels of
+ *     the failed call on the stream, and the outputs are then undefined.
  */
 #ifndef FTKMEANS_H
 #define FTKMEANS_H
@@ -42,7 +44,7 @@ typedef enum {
     FTK_EALIGN = 2,        /* a pointer is not aligned to its element size / 256 B   */
     FTK_EWORKSPACE = 3,    /* workspace missing or too small                         */
     FTK_EDEVICE = 4,       /* a HIP runtime call failed or the device is not gfx950  */
-    FTK_EUNCORRECTABLE = 5 /* reserved: reported through ftk_ft_stats, not returned  */
+    FTK_EUNCORRECTABLE = 5 /* reserved: never returned; see ftk_ft_stats.uncorrectable   */
 } ftk_status;
 
 typedef enum { FTK_F32 = 0, FTK_F64 = 1 } ftk_dtype;
@@ -77,7 +79,9 @@ typedef struct {
     uint64_t detected;       /* checksum mismatches above the threshold                   */
     uint64_t corrected;      /* repaired from the decoded location                        */
     uint64_t recomputed;     /* location not decodable -> tile recomputed                 */
-    uint64_t uncorrectable;  /* still mismatching after recomputation                     */
+    uint64_t uncorrectable;  /* update step only: a recomputed pass mismatched again; the
+                                assignment recomputes outside the matrix path and never
+                                produces it                                               */
     uint64_t refined;        /* points whose best scores were closer than the rounding-
                                 error bound and were re-evaluated exactly by the refine
                                 kernel                                                    */
@@ -120,7 +124,15 @@ ftk_status ftk_plan_padded_rows(ftk_dtype dtype, int64_t N, int32_t D, int32_t K
 /* Assignment step, Eq. (1), Sections 3.1.2-3.1.5 and 4.
  *   X [N x D], C [K x D]  in  : read only.
  *   labels [N] int32      out : index of the nearest centroid.
- *   mindist [N] (dtype)   out : squared distance to it, >= 0; may be NULL.
+ *   mindist [N] (dtype)   out : squared distance to it, >= 0; may be NULL.  Accuracy: points whose
+ *                               decision was settled by exact re-evaluation, and every point of
+ *                               the fp32 kernel for D <= 32, get the direct-difference value
+ *                               (relative error of a few units in the last place of the
+ *                               distance).  Otherwise the value comes from the expanded form of
+ *                               Section 3.1.2, whose cancellation leaves an ABSOLUTE error of up
+ *                               to 1.5 * band_coef * (||x_i|| max||c|| + max||c||^2/2) with
+ *                               band_coef from ftk_ft_thresholds - small against the distance
+ *                               unless the data sit far from the origin.
  *   faults [n_faults]     in  : soft errors to inject; NULL / 0 for none.  Ignored when
  *                               ft == FTK_FT_OFF is combined with n_faults == 0 only; with
  *                               FT off, listed faults are still injected (and corrupt the

@@ -4,6 +4,7 @@
 #include <cstdio>
 #include <cstring>
 #include <mutex>
+#include <unordered_set>
 #include <utility>
 #include <vector>
 
@@ -228,7 +229,8 @@ static ftk_status assign_impl(const AssignCall &c, void *workspace, hipStream_t 
     const Workspace w = carve_workspace(workspace, c.dtype, c.N, c.D, c.K, c.ft, !fast);
     FTK_TRY(launch_centroid_prologue(c, p, w, st));
     hipEvent_t e0 = nullptr, e1 = nullptr;
-    const bool profile = g_profile && allow_profile;
+    // at most 65536 pending pairs: a caller that enables profiling and never reads stops recording
+    const bool profile = g_profile && allow_profile && g_profile_events.size() < 65536;
     if (profile) {
         FTK_TRY_HIP(hipEventCreate(&e0));
         if (hipError_t e = hipEventCreate(&e1); e != hipSuccess) {
@@ -557,12 +559,14 @@ ftk_status ftk_seeded_indices(uint64_t seed, int64_t N, int32_t K, int64_t *idx_
         z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
         return z ^ (z >> 31);
     };
+    std::unordered_set<int64_t> chosen;
+    chosen.reserve((size_t)K * 2);
     int filled = 0;
     for (int64_t top = N - K; top < N; ++top) {
         const int64_t pick = (int64_t)(next() % (uint64_t)(top + 1));
-        bool seen = false;
-        for (int i = 0; i < filled && !seen; ++i) seen = idx_host[i] == pick;
-        idx_host[filled++] = seen ? top : pick;
+        const int64_t take = chosen.count(pick) ? top : pick;  // `top` itself cannot have been chosen yet
+        chosen.insert(take);
+        idx_host[filled++] = take;
     }
     return FTK_OK;
 }

@@ -14,8 +14,12 @@
 //   * after the sweep re-evaluates the winning group of 16 centroids in direct-difference form
 //     (the two lanes of a point share the rows), which yields the exact arg-min inside the
 //     group, resolves near-ties the cancelling expanded form cannot order, and gives an
-//     accurate minimum distance.  A second group is evaluated when the other lane's best tile
-//     is inside the rounding bound; a third candidate sends the point to the refine kernel.
+//     accurate minimum distance;
+//   * evaluates a second group when the other lane's best tile is inside the rounding bound; a
+//     third candidate sends the point to the refine kernel.  With strict fault tolerance, where
+//     the bound is wider and a few per cent of the points are ambiguous, such points are instead
+//     collected per workgroup and swept a second time at the end of the kernel with the two best
+//     tiles of each lane on record (see the kernel).
 //
 // Fault tolerance (Sections 2.3, 4): with FT on, every tile carries its own checksum row.  A
 // tile then holds 30 centroids; register 15 of each lane group belongs to a virtual centroid
@@ -48,8 +52,11 @@ struct SmallArgs {
     int nblocks;      // point blocks (waves*PT*32 points each)
     int32_t *labels;
     float *mindist;
-    int32_t *wl;
-    int32_t *wl_count;
+    int32_t *wl;        // work-list of the refine kernel (point indices)
+    int32_t *wl_count;  // [0] its length, [1] block counter
+    int defer;          // 1 = collect ambiguous points per workgroup and sweep them a second time (when
+                        // every tile is LDS-resident); 0 = evaluate the other lane's best group where it
+                        // turns up and leave third candidates to the refine kernel
     ftk_ft_stats *stats;
     double band_coef;
     // fault tolerance / injection
@@ -82,6 +89,29 @@ __device__ __forceinline__ float sum15(const floatx16 &a)
     return (p0 + p1) + (p2 + p3);
 }
 
+// Work-list entries of a workgroup are collected in LDS: one device-wide atomic per wave of
+// entries when they are handed over, instead of one per wave and point tile (tens of thousands of
+// atomics on one word keep a dispatch open long after its last wave).  A wave that finds the
+// buffer full appends to the global list directly.
+constexpr int SMALLD_LIST_CAP = 512;
+__device__ __forceinline__ void block_list_push(bool need, int32_t point, int32_t *sh_list, int *sh_count,
+                                                int32_t *wl, int32_t *wl_count)
+{
+    const unsigned long long m = __ballot(need);
+    if (m == 0ull) return;
+    const int lane = (int)(threadIdx.x & 63);
+    const int leader = __ffsll((long long)m) - 1;
+    const int n = (int)__popcll(m);
+    int base = 0;
+    if (lane == leader) base = atomicAdd(sh_count, n);
+    base = __shfl(base, leader, 64);
+    if (base + n <= SMALLD_LIST_CAP) {
+        if (need) sh_list[base + (int)__popcll(m & ((1ull << lane) - 1ull))] = point;
+    } else {
+        worklist_push(need, point, wl, wl_count);
+    }
+}
+
 template <int NQ, int PT, bool FT>
 __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) void assign_smalld_kernel(SmallArgs a)
 {
@@ -99,6 +129,8 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
     float *ldsH = lds + (size_t)a.tpc * TS;     // [tpc*32] accumulator start values, (tile, group, register) order
     __shared__ int sh_next;
     __shared__ int sh_nf;
+    __shared__ int sh_wlcnt;
+    __shared__ int32_t sh_wl[SMALLD_LIST_CAP];
     __shared__ ftk_fault sh_faults[SMALLD_MAX_FAULTS];
 
     const int tid = threadIdx.x;
@@ -110,10 +142,16 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
     const float cmax2 = (float)a.scal[0];
     const float cmax = sqrtf(cmax2);
     const bool resident = a.nch == 1;
-    // per-lane event counters, reduced over the wave at the end
+    // deferred mode (every tile resident): ambiguous points are not settled where they turn up but
+    // collected per workgroup and swept once more at the end, see below
+    const bool defer = a.defer != 0 && resident;
     // wave-uniform event counters (scalar registers: counted with ballots)
     int n_injected = 0, n_detected = 0, n_corrected = 0, n_recomputed = 0;
     float worst_resid = 0.f;  // largest fault-free residual seen by this lane, in units of its threshold
+
+    // slots a wave reserved but could not use stay marked
+    for (int i = tid; i < SMALLD_LIST_CAP; i += SMALLD_THREADS) sh_wl[i] = -1;
+    if (tid == 0) sh_wlcnt = 0;
 
     // operand fetch of one centroid tile: A fragments and the accumulator start values
     auto load_tile = [&](int t, floatx4 (&av)[NQ], floatx16 &ci) {
@@ -165,10 +203,8 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
             ldsH[idx] = h;
         }
     };
-    if (resident) {
-        stage_chunk(0);
-        __syncthreads();
-    }
+    if (resident) stage_chunk(0);
+    __syncthreads();
 
     // Blocks of SMALLD_WAVES units (PT*32 points per wave).  While chunks have to be staged (or
     // faults are listed per block) the waves of a workgroup walk the blocks in step and draw them
@@ -177,9 +213,28 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
     // memory latencies at the start and the end of a block (point rows, exact re-evaluation) of
     // one wave run under the matrix work of the others.  (A counter drawn per wave instead would
     // put one device-wide atomic on the same word per 64 points, which costs more than it saves.)
+    //
+    // Deferred mode adds a SECOND ROUND after the blocks: the points the workgroup's waves found
+    // ambiguous (another tile maximum inside the rounding bound - with strict fault tolerance a
+    // few per cent of all points) sit in the LDS list; wave w takes entries [w*PT*32, (w+1)*PT*32)
+    // and sweeps the resident tiles once more for them, this time also recording which tiles held
+    // the two best maxima of each lane, and evaluates up to four candidate groups exactly.  The
+    // extra record costs four vector instructions per tile, which is why the first round does not
+    // keep it; evaluating a second group where it turns up would make a whole wave pay for one
+    // lane, and sending every such point to the refine kernel (all K distances) costs far more.
     int blk = blockIdx.x;
-    while (blk < a.nblocks) {
-        const int64_t p0 = ((int64_t)blk * SMALLD_WAVES + wave) * (PT * 32);
+    bool second_round = false;
+    int nlist = 0;
+    while (true) {
+        if (!second_round && blk >= a.nblocks) {
+            if (!defer) break;
+            __syncthreads();  // every wave is through its blocks: the list is complete
+            second_round = true;
+            nlist = min(sh_wlcnt, SMALLD_LIST_CAP);
+            if (wave * (PT * 32) >= nlist) break;
+        }
+        const int64_t p0 = second_round ? (int64_t)wave * (PT * 32) : ((int64_t)blk * SMALLD_WAVES + wave) * (PT * 32);
+        const int64_t npoints = second_round ? (int64_t)nlist : a.N;
         floatx4 xf[PT][NQ];
         float xn[PT];
         float tau[PT];          // checksum detection threshold of this lane's point
@@ -188,11 +243,16 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
                                 // array updated inside the rare branch lost its value when compiled)
         float rmax[PT];         // largest |residual| below the threshold over this point's tiles
         TileBest best[PT];
+        float m3[PT];           // second round: third-best tile maximum and the runner-up's tile
+        int t2[PT];
+        int64_t pidx[PT];       // the point this lane works on (-1: none)
 #pragma unroll
         for (int pt = 0; pt < PT; ++pt) {
             int64_t p = p0 + pt * 32 + col;
-            if (p >= a.N) p = a.N - 1;
-            const float *xrow = a.X + p * D;
+            if (p >= npoints) p = npoints - 1;
+            if (second_round) p = sh_wl[p];
+            pidx[pt] = p;
+            const float *xrow = a.X + (p < 0 ? 0 : p) * D;
             float s = 0.f;
 #pragma unroll
             for (int q = 0; q < NQ; ++q) {
@@ -205,13 +265,13 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
             inv_tau[pt] = 1.0f / tau[pt];
             force_refine[pt] = 0;
             rmax[pt] = 0.f;
-            best[pt].m1 = best[pt].m2 = M::neg_inf();
-            best[pt].t1 = 0;
+            best[pt].m1 = best[pt].m2 = m3[pt] = M::neg_inf();
+            best[pt].t1 = t2[pt] = 0;
         }
 
-        // faults aimed at this point block
+        // faults aimed at this point block (descriptors address the blocks of the first round)
         int nf = 0;
-        if (a.n_faults > 0) {
+        if (a.n_faults > 0 && !second_round) {
             if (tid == 0) sh_nf = 0;
             __syncthreads();
             for (int i = tid; i < a.n_faults; i += SMALLD_THREADS) {
@@ -225,8 +285,9 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
         }
 
         // one output tile: contraction, (injection, verification,) tile maximum, running best
-        auto compute_tile = [&](auto inj_tag, const floatx4 (&av)[NQ], const floatx16 &ci, int T) {
+        auto compute_tile = [&](auto inj_tag, auto round2_tag, const floatx4 (&av)[NQ], const floatx16 &ci, int T) {
             constexpr bool INJ = decltype(inj_tag)::value;
+            constexpr bool ROUND2 = decltype(round2_tag)::value;
             // all matrix instructions of the tile first: the PT accumulator chains are independent
             // and interleave on the matrix pipe; verification and reduction follow per point tile
             floatx16 accs[PT];
@@ -333,6 +394,12 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
                 const float m1 = best[pt].m1, m2 = best[pt].m2;
                 const int t1 = best[pt].t1;
                 const bool c = tm > m1;
+                if constexpr (ROUND2) {  // sorted insert into (m1 >= m2 >= m3), tiles of the first two
+                    const bool c2 = tm > m2;
+                    m3[pt] = __builtin_amdgcn_fmed3f(m2, m3[pt], tm);
+                    const int t2n = c2 ? T : t2[pt];
+                    t2[pt] = c ? t1 : t2n;
+                }
                 best[pt].m2 = __builtin_amdgcn_fmed3f(m1, m2, tm);
                 best[pt].t1 = c ? T : t1;
                 best[pt].m1 = max2f(m1, tm);
@@ -350,29 +417,32 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
             // two operand register sets: the fetch of the next tile is in flight while the
             // current one is multiplied; the injection hook is compiled in only when faults are
             // listed for this block, so the common sweep has no per-tile branch for it
-            auto sweep = [&](auto inj_tag) {
+            auto sweep = [&](auto inj_tag, auto round2_tag) {
                 floatx4 avA[NQ], avB[NQ];
                 floatx16 ciA, ciB;
                 load_tile(0, avA, ciA);
                 for (int t = 0; t < ntile; t += 2) {
                     load_tile(min(t + 1, ntile - 1), avB, ciB);
-                    compute_tile(inj_tag, avA, ciA, tile0 + t);
+                    compute_tile(inj_tag, round2_tag, avA, ciA, tile0 + t);
                     load_tile(min(t + 2, ntile - 1), avA, ciA);
-                    if (t + 1 < ntile) compute_tile(inj_tag, avB, ciB, tile0 + t + 1);
+                    if (t + 1 < ntile) compute_tile(inj_tag, round2_tag, avB, ciB, tile0 + t + 1);
                 }
             };
-            if (nf > 0)
-                sweep(std::true_type{});
+            if (second_round)
+                sweep(std::false_type{}, std::true_type{});
+            else if (nf > 0)
+                sweep(std::true_type{}, std::false_type{});
             else
-                sweep(std::false_type{});
+                sweep(std::false_type{}, std::false_type{});
         }
 
         // ---- exact evaluation of the winning group; the two lanes of a point share its rows ----
 #pragma unroll
         for (int pt = 0; pt < PT; ++pt) {
             if (FT) worst_resid = fmaxf(worst_resid, rmax[pt] * inv_tau[pt]);
-            const int64_t p = p0 + pt * 32 + col;
-            const bool live = p < a.N;
+            const int64_t slot = p0 + pt * 32 + col;
+            const int64_t p = pidx[pt];
+            const bool live = slot < npoints && p >= 0;
             floatx4 xlo[NQ], xhi[NQ];
 #pragma unroll
             for (int q = 0; q < NQ; ++q)
@@ -391,35 +461,46 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
             const int ot1 = __shfl_xor(best[pt].t1, 32, 64);
             const bool mine_wins = best[pt].m1 > om1 || (best[pt].m1 == om1 && g == 0);
             const float thr = fmaxf(best[pt].m1, om1) - bound;
-            // first round: the group holding the best tile maximum (gw = its lane group)
+            // the group holding the best tile maximum (gw = its lane group)
             const int gw = mine_wins ? g : 1 - g;
             const int Tw = mine_wins ? best[pt].t1 : ot1;
-            // second round (rare): the other group's best tile is inside the bound as well
-            const bool second = fminf(best[pt].m1, om1) >= thr;
-            const int Ts = mine_wins ? ot1 : best[pt].t1;
-            // a third candidate tile anywhere: left to the refine kernel
-            const bool over = fmaxf(best[pt].m2, om2) >= thr;
             const bool forced = (force_refine[pt] | __shfl_xor(force_refine[pt], 32, 64)) != 0;
             float dbest = __builtin_huge_valf();
             int jbest = 0x7fffffff;
-            if (resident) {
-                eval_rows<NQ, FT, true>(xlo, xhi, ldsC + Tw * TS, SW, Tw, a.K, D, gw, 8 * g, dbest, jbest);
-                if (__any(second)) {
-                    float d2 = dbest;
-                    int j2 = jbest;
-                    eval_rows<NQ, FT, true>(xlo, xhi, ldsC + Ts * TS, SW, Ts, a.K, D, 1 - gw, 8 * g, d2, j2);
-                    dbest = second ? d2 : dbest;
-                    jbest = second ? j2 : jbest;
-                }
+            // one group of 16 (15) rows, split between the two lanes of the point; `take` = whether
+            // this point counts the group (the evaluation itself runs for the whole wave)
+            auto eval_group = [&](int T, int gsel, bool take) {
+                float d2 = dbest;
+                int j2 = jbest;
+                if (resident)
+                    eval_rows<NQ, FT, true>(xlo, xhi, ldsC + T * TS, SW, T, a.K, D, gsel, 8 * g, d2, j2);
+                else
+                    eval_rows<NQ, FT, false>(xlo, xhi, a.C, D, T, a.K, D, gsel, 8 * g, d2, j2);
+                dbest = take ? d2 : dbest;
+                jbest = take ? j2 : jbest;
+            };
+            eval_group(Tw, gw, true);
+            // another tile maximum inside the bound: the best tile of the losing lane ...
+            const bool cand_b = fminf(best[pt].m1, om1) >= thr;
+            const int Tb = mine_wins ? ot1 : best[pt].t1;
+            bool unsettled;
+            if (!second_round) {
+                // ... evaluated here unless ambiguous points are deferred; a runner-up tile of either
+                // lane is not on record in this round
+                if (!defer && __any(cand_b)) eval_group(Tb, 1 - gw, cand_b);
+                unsettled = (defer && cand_b) || fmaxf(best[pt].m2, om2) >= thr;
             } else {
-                eval_rows<NQ, FT, false>(xlo, xhi, a.C, D, Tw, a.K, D, gw, 8 * g, dbest, jbest);
-                if (__any(second)) {
-                    float d2 = dbest;
-                    int j2 = jbest;
-                    eval_rows<NQ, FT, false>(xlo, xhi, a.C, D, Ts, a.K, D, 1 - gw, 8 * g, d2, j2);
-                    dbest = second ? d2 : dbest;
-                    jbest = second ? j2 : jbest;
-                }
+                // ... and the runner-up tiles of the winning and of the losing lane, each only if
+                // some point of the wave needs it
+                const int ot2 = __shfl_xor(t2[pt], 32, 64);
+                const float wm2 = mine_wins ? best[pt].m2 : om2, lm2 = mine_wins ? om2 : best[pt].m2;
+                const bool cand_c = wm2 >= thr, cand_d = lm2 >= thr;
+                const int Tc = mine_wins ? t2[pt] : ot2, Td = mine_wins ? ot2 : t2[pt];
+                if (__any(cand_b)) eval_group(Tb, 1 - gw, cand_b);
+                if (__any(cand_c)) eval_group(Tc, gw, cand_c);
+                if (__any(cand_d)) eval_group(Td, 1 - gw, cand_d);
+                // a third tile of either lane inside the bound: left to the refine kernel
+                unsettled = fmaxf(m3[pt], __shfl_xor(m3[pt], 32, 64)) >= thr;
             }
             const float od = __shfl_xor(dbest, 32, 64);
             const int oj = __shfl_xor(jbest, 32, 64);
@@ -430,9 +511,14 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
                 a.labels[p] = jbest == 0x7fffffff ? 0 : jbest;
                 if (a.mindist) a.mindist[p] = dbest;
             }
-            // NaN scores, a third candidate, or a failed repair: exact recomputation
-            worklist_push(live && g == 0 && (!(thr == thr) || over || forced), (int32_t)p, a.wl, a.wl_count);
+            // NaN scores, more candidates than are on record, or a failed repair: exact recomputation
+            const bool need = live && g == 0 && (!(thr == thr) || unsettled || forced);
+            if (second_round)
+                worklist_push(need, (int32_t)p, a.wl, a.wl_count);
+            else
+                block_list_push(need, (int32_t)p, sh_wl, &sh_wlcnt, a.wl, a.wl_count);
         }
+        if (second_round) break;
         if (resident && a.n_faults == 0) {
             blk += (int)gridDim.x;
             continue;
@@ -441,6 +527,16 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
         if (tid == 0) sh_next = (int)gridDim.x + atomicAdd(a.wl_count + 1, 1);
         __syncthreads();
         blk = sh_next;
+    }
+
+    if (!defer) {  // hand the collected work-list entries over to the refine kernel
+        __syncthreads();
+        const int n = min(sh_wlcnt, SMALLD_LIST_CAP);
+        for (int i0 = 0; i0 < n; i0 += SMALLD_THREADS) {
+            const int i = i0 + tid;
+            const int32_t v = i < n ? sh_wl[i] : -1;
+            worklist_push(v >= 0, v, a.wl, a.wl_count);
+        }
     }
 
     // Statistics.  Thousands of waves adding to the same few words would keep the memory system
@@ -612,6 +708,7 @@ ftk_status launch_assign_smalld(const AssignCall &c, const AssignPlan &p, const 
     a.mindist = (float *)c.mindist;
     a.wl = w.wl;
     a.wl_count = w.wl_count;
+    a.defer = c.ft == FTK_FT_STRICT ? 1 : 0;
     a.stats = c.stats;
     a.band_coef = p.band_coef;
     a.chk_v1 = (const float *)w.chk_v1;

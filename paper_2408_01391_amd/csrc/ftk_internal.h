@@ -74,7 +74,7 @@ struct Workspace {
     void *chk_v2;       // [nkc*KT][D8] per-tile weighted checksum rows (dtype)
     void *chk_s;        // [nkc*KT][2]  their half-norm terms (dtype; small-D variant)
     double *chk_sd;     // [nkc][2]     the same per K-chunk, in double (generic variant)
-    int32_t *wl_count;  // [4]   refine work-list length (+ padding)
+    int32_t *wl_count;  // [4]   0: refine work-list length, 1: block counter (small-D / fast kernels)
     int32_t *wl;        // [N]   refine work-list (point indices)
     int32_t *wg_refined;  // [N/64 + 2] points each workgroup of the generic kernel settled in place
     // update

@@ -54,11 +54,13 @@ def check_assign(X: np.ndarray, C: np.ndarray, labels_g: np.ndarray, mindist_g=N
     if mindist_g is not None:
         md = mindist_g[idx].astype(np.float64)
         assert np.all(md >= 0)
-        eps = 6e-8 if X.dtype == np.float32 else 1.2e-16
         xn = (X[idx].astype(np.float64) ** 2).sum(1)
         cn = (C.astype(np.float64) ** 2).sum(1).max()
-        # the expanded form cancels: absolute error scales with the norms, not with the distance
-        atol = 64 * eps * np.sqrt(X.shape[1] + 4.0) * (xn + cn)
+        # the expanded form cancels: absolute error scales with the norms, not with the distance;
+        # the bound is the one the header documents, from the library's own rounding band
+        code = ftk.F32 if X.dtype == np.float32 else ftk.F64
+        _, band = ftk.ft_thresholds(code, X.shape[0], X.shape[1], C.shape[0], ftk.FT_OFF)
+        atol = 1.5 * band * (np.sqrt(xn * cn) + 0.5 * cn)
         err = np.abs(md - d1)
         assert np.all(err <= 1e-5 * d1 + atol), "mindist off: max err %g" % err.max()
     return int(diff.size), int(idx.size)
