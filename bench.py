@@ -53,6 +53,9 @@ def parse():
     ap.add_argument("--ablation", action="store_true",
                     help="also time the naive and the unfused GEMM + arg-min variants of the assignment "
                          "(Section 3.1.1 / 3.1.2) of the headline workload")
+    ap.add_argument("--batched", action="store_true",
+                    help="also time the batched Lloyd step (ftk_kmeans_step_batched: assign a batch of rows, add "
+                         "it to the sums while cache-resident) of the headline workload at several batch sizes")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--inject-seconds", type=float, default=1.5,
                     help="run time of the bit-flip injection leg (workloads with a flip rate; 0 = skip)")
@@ -263,6 +266,36 @@ def ablation_times(ftk, torch, s, esz):
     return res
 
 
+def batched_step_times(torch, ftk, s, steps, warmup, repeats, sec_per_step):
+    """The single-pass idea of Section 2.2 as batches: milliseconds per Lloyd step of
+    ftk_kmeans_step_batched by batch size, next to the two-call step."""
+    w = s.w
+    esz = 4 if w.dtype == "f32" else 8
+    rows_out = []
+    for mb in (32, 64, 128, 256, 512, 1024):
+        rows = int(mb * 2 ** 20 // (w.D * esz))
+        if rows >= w.N:
+            break
+        C = s.C0d.clone()
+
+        def run(n):
+            for _ in range(n):
+                ftk.kmeans_step_batched(s.Xd, C, rows, labels=s.labels, mindist=s.mind, counts=s.counts,
+                                        x_absmax=s.absmax, workspace=s.ws)
+        run(warmup)
+        times = []
+        for _ in range(repeats):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            run(steps)
+            torch.cuda.synchronize()
+            times.append((time.perf_counter() - t0) / steps)
+        sec = statistics.median(times)
+        rows_out.append({"batch_MB": mb, "batch_rows": rows, "batches": -(-w.N // rows), "ms_per_step": 1e3 * sec,
+                         "vs_two_call_step": sec / sec_per_step - 1.0})
+    return {"two_call_ms_per_step": 1e3 * sec_per_step, "by_batch_size": rows_out}
+
+
 def cpu_baseline(w, X, C0, seconds, gpu_labels0):
     """The oracle as it stands, timed on the host cores for about `seconds`.
 
@@ -389,6 +422,9 @@ def measure(name, args, torch, ftk, synth, np, headline):
             out["fast_mode"] = fast_mode_times(torch, ftk, s, steps, args.warmup, args.repeats, off["sec"])
         if args.ablation:
             out["ablation"] = ablation_times(ftk, torch, s, esz)
+        if args.batched:
+            out["batched_step"] = batched_step_times(torch, ftk, s, steps, args.warmup, max(3, args.repeats // 2),
+                                                     off["sec"])
     return out, s
 
 

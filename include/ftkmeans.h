@@ -206,6 +206,23 @@ ftk_status ftk_kmeans_update(ftk_dtype dtype, const void *X, const int32_t *labe
                              const double *x_absmax, void *workspace, size_t workspace_bytes,
                              void *hip_stream);
 
+/* One Lloyd iteration (assignment, then update) carried out batch by batch: the single-pass idea of
+ * Section 2.2 in the form this hardware allows.  The rows of X are taken in batches of `batch_rows`
+ * points; each batch is assigned and, while it is still in the memory-side cache, added to the
+ * running fixed-point sums; the centroids are averaged once after the last batch.  X is then read
+ * from HBM once per iteration instead of twice, at the price of several launches per batch and of
+ * a thinner grid per launch.  Results: labels and mindist as from ftk_kmeans_assign against the
+ * incoming C; C and counts as from ftk_kmeans_update within its stated accuracy (the update always
+ * runs on the per-workgroup table path here, so the last bits may differ from ftk_kmeans_update's).
+ *   C [K x D]            i/o : centroids in, updated centroids out.
+ *   x_absmax             in  : device scalar from ftk_absmax over X (required).
+ *   batch_rows               : points per batch, at least N / 4096.
+ * No fault tolerance on this path.  workspace: ftk_workspace_bytes(dtype, N, D, K, FTK_FT_OFF). */
+ftk_status ftk_kmeans_step_batched(ftk_dtype dtype, const void *X, int64_t N, int32_t D, int32_t K, void *C,
+                                   int32_t *labels, void *mindist /* nullable */, int32_t *counts,
+                                   const double *x_absmax, int64_t batch_rows, void *workspace,
+                                   size_t workspace_bytes, void *hip_stream);
+
 /* The same update step protected by dual modular redundancy (Sections 2.3 and 4: the
  * memory-bound update is covered by duplicating its arithmetic and comparing).  With
  * ft != FTK_FT_OFF every arithmetic result of the step - conversion to fixed point, running

@@ -64,6 +64,8 @@ def load():
     L.ftk_absmax.restype = i32
     L.ftk_kmeans_update.argtypes = [i32, vp, vp, i64, i32, i32, vp, vp, vp, vp, sz, vp]
     L.ftk_kmeans_update.restype = i32
+    L.ftk_kmeans_step_batched.argtypes = [i32, vp, i64, i32, i32, vp, vp, vp, vp, vp, i64, vp, sz, vp]
+    L.ftk_kmeans_step_batched.restype = i32
     L.ftk_kmeans_update_ft.argtypes = [i32, vp, vp, i64, i32, i32, vp, vp, vp, i32, vp, i32, vp, vp, sz, vp]
     L.ftk_kmeans_update_ft.restype = i32
     L.ftk_update_geometry.argtypes = [i32, i64, i32, i32, i32, ctypes.POINTER(Geometry)]
@@ -87,7 +89,7 @@ def load():
 
 
 EXPORTS = ("ftk_workspace_bytes", "ftk_assign_geometry", "ftk_plan_padded_rows", "ftk_ft_thresholds", "ftk_kmeans_assign_static", "ftk_static_scratch_bytes", "ftk_kmeans_assign", "ftk_kmeans_assign_fast", "ftk_absmax",
-           "ftk_kmeans_update", "ftk_kmeans_update_ft", "ftk_update_geometry", "ftk_kmeans_fit", "ftk_kmeans_fit_fast", "ftk_seeded_indices", "ftk_profile_enable",
+           "ftk_kmeans_update", "ftk_kmeans_update_ft", "ftk_kmeans_step_batched", "ftk_update_geometry", "ftk_kmeans_fit", "ftk_kmeans_fit_fast", "ftk_seeded_indices", "ftk_profile_enable",
            "ftk_profile_read", "ftk_tuning_override", "ftk_last_error", "ftk_version")
 
 
@@ -273,6 +275,29 @@ def kmeans_update(X, labels, C, counts=None, x_absmax=None, workspace=None, ft_m
                                            C.data_ptr(), counts.data_ptr(), _ptr(x_absmax), ft_mode,
                                            _ptr(faults), nf, _ptr(stats), wp, wn, _stream()))
     return C, counts
+
+
+def kmeans_step_batched(X, C, batch_rows, labels=None, mindist=None, counts=None, x_absmax=None, workspace=None):
+    """One Lloyd iteration in batches of `batch_rows` points (assign a batch, add it to the sums while
+    it is cache-resident); C is updated in place.  Returns (labels, mindist, counts)."""
+    _dev2d(X, "X"), _dev2d(C, "C")
+    N, D = X.shape
+    K = C.shape[0]
+    if labels is None:
+        labels = torch.empty(N, dtype=torch.int32, device=X.device)
+    if mindist is None:
+        mindist = torch.empty(N, dtype=X.dtype, device=X.device)
+    if counts is None:
+        counts = torch.empty(K, dtype=torch.int32, device=X.device)
+    if x_absmax is None:
+        x_absmax = absmax(X)
+    if workspace is None:
+        workspace = new_workspace(X, K, FT_OFF)
+    wp, wn = _ws_args(workspace)
+    _check(load().ftk_kmeans_step_batched(_dtype_code(X), X.data_ptr(), N, D, K, C.data_ptr(), labels.data_ptr(),
+                                          _ptr(mindist), counts.data_ptr(), x_absmax.data_ptr(), int(batch_rows),
+                                          wp, wn, _stream()))
+    return labels, mindist, counts
 
 
 def seeded_indices(seed: int, N: int, K: int):

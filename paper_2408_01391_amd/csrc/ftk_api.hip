@@ -121,6 +121,7 @@ Workspace carve_workspace(void *base, ftk_dtype dtype, int64_t N, int D, int K, 
         w.inertia = w.partials = nullptr;
         w.idx = nullptr;
         w.csplit = nullptr;
+        w.batch_counters = nullptr;
         w.total = off;
         return w;
     }
@@ -143,6 +144,7 @@ Workspace carve_workspace(void *base, ftk_dtype dtype, int64_t N, int D, int K, 
     w.partials = (double *)take(1024 * sizeof(double));
     w.idx = (int64_t *)take((size_t)K * sizeof(int64_t));
     w.csplit = take(fast_split_bytes(dtype, D, K));
+    w.batch_counters = (int32_t *)take((size_t)4 * MAX_BATCHES * sizeof(int32_t));
     w.total = off;
     return w;
 }
@@ -531,6 +533,60 @@ ftk_status ftk_kmeans_update(ftk_dtype dtype, const void *X, const int32_t *labe
 {
     return ftk_kmeans_update_ft(dtype, X, labels, N, D, K, C, counts, x_absmax, FTK_FT_OFF, nullptr, 0,
                                 nullptr, workspace, workspace_bytes, hip_stream);
+}
+
+ftk_status ftk_kmeans_step_batched(ftk_dtype dtype, const void *X, int64_t N, int32_t D, int32_t K, void *C,
+                                   int32_t *labels, void *mindist, int32_t *counts, const double *x_absmax,
+                                   int64_t batch_rows, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    FTK_TRY(check_problem(dtype, N, D, K, FTK_FT_OFF));
+    const size_t esz = dtype == FTK_F32 ? 4 : 8;
+    FTK_TRY(check_ptr(X, esz, "X"));
+    FTK_TRY(check_ptr(C, esz, "C"));
+    FTK_TRY(check_ptr(labels, 4, "labels"));
+    if (mindist) FTK_TRY(check_ptr(mindist, esz, "mindist"));
+    FTK_TRY(check_ptr(counts, 4, "counts"));
+    FTK_TRY(check_ptr(x_absmax, 8, "x_absmax"));
+    if (batch_rows < 1 || ceil_div(N, batch_rows) > MAX_BATCHES) {
+        set_error("batch_rows = %lld gives %lld batches (allowed: 1 .. %d)", (long long)batch_rows,
+                  batch_rows < 1 ? 0ll : (long long)ceil_div(N, batch_rows), MAX_BATCHES);
+        return FTK_EINVAL;
+    }
+    FTK_TRY(check_workspace(workspace, workspace_bytes, ftk_workspace_bytes(dtype, N, D, K, FTK_FT_OFF)));
+    FTK_TRY(check_device());
+    hipStream_t st = (hipStream_t)hip_stream;
+    const Workspace w = carve_workspace(workspace, dtype, N, D, K, FTK_FT_OFF);
+    // whole rows of 16 bytes keep every batch as aligned as X itself
+    const bool aligned16 = ((uintptr_t)X % 16 == 0) && ((uintptr_t)C % 16 == 0) && ((size_t)D * esz) % 16 == 0;
+    const BatchedUpdatePlan ub = plan_update_batched(dtype, aligned16 ? X : (const void *)1, N, batch_rows, D, K);
+    if (!ub.ok) {
+        set_error("internal: update tables of a batch exceed the workspace bound (chunks %d)", ub.chunks);
+        return FTK_EINVAL;
+    }
+    const int64_t nbatch = ceil_div(N, batch_rows);
+    FTK_TRY(launch_zero_ints(w.batch_counters, (int)(4 * nbatch), st));
+    // norms of the centroids once: they do not change inside the iteration
+    AssignCall whole{dtype, X, C, batch_rows < N ? batch_rows : N, D, K, labels, mindist, FTK_FT_OFF, nullptr, 0, nullptr};
+    const AssignPlan p0 = plan_assign(dtype, whole.N, D, K, FTK_FT_OFF, aligned16);
+    FTK_TRY(launch_centroid_prologue(whole, p0, w, st));
+    for (int64_t b = 0; b < nbatch; ++b) {
+        const int64_t r0 = b * batch_rows;
+        const int64_t nb = N - r0 < batch_rows ? N - r0 : batch_rows;
+        const char *Xb = (const char *)X + (size_t)r0 * D * esz;
+        AssignCall c{dtype, Xb, C, nb, D, K, labels + r0, mindist ? (void *)((char *)mindist + (size_t)r0 * esz) : nullptr,
+                     FTK_FT_OFF, nullptr, 0, nullptr};
+        AssignPlan p = plan_assign(dtype, nb, D, K, FTK_FT_OFF, aligned16);
+        if (p.variant != p0.variant || p.nkc * p.KC != p0.nkc * p0.KC) {
+            set_error("internal: the last batch plans a different kernel layout than the first");
+            return FTK_EINVAL;
+        }
+        Workspace wb = w;
+        wb.wl_count = w.batch_counters + 4 * b;  // fresh work-list counters per batch
+        FTK_TRY(launch_assign(c, p, wb, st));
+        FTK_TRY(launch_refine(c, wb, 0, st));
+        FTK_TRY(launch_update_batch(dtype, Xb, labels + r0, nb, D, K, x_absmax, w, ub, b == 0, st));
+    }
+    return launch_update_batched_finalize(dtype, D, K, x_absmax, C, counts, w, ub, st);
 }
 
 ftk_status ftk_update_geometry(ftk_dtype dtype, int64_t N, int32_t D, int32_t K, int32_t rows_aligned16,

@@ -172,17 +172,25 @@ __global__ __launch_bounds__(256, (GenericCfg<T, KTV>::WAVES_PER_SIMD)) void ass
     unsigned char *const lds_best = lds_hcn + 2 * KC * (int)sizeof(T);
     const int ndc = (nq + DQ - 1) / DQ;  // stages per K-chunk
 
+    // Rows and pieces this thread stages are fixed; only the chunk and the feature offset move.
+    int st_row[NP], st_pc[NP];
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        const int idx = min(tid + 256 * i, NPIECES - 1);  // surplus threads repeat the last piece (not stored)
+        st_row[i] = idx / PPR;
+        st_pc[i] = idx % PPR;
+    }
     frag_t pf[NP], pfx;
+    // fetch only issues the loads (clamped into the matrix, so always valid); rows beyond K and
+    // features beyond D are cleared when the stage is committed to LDS, i.e. after the matrix work
+    // of the stage in between - a select right behind the load would make the wave wait for it here
     auto fetch = [&](int kc, int dc) {
         const int q0 = dc * DQ;
 #pragma unroll
         for (int i = 0; i < NP; ++i) {
-            const int idx = min(tid + 256 * i, NPIECES - 1);  // surplus threads repeat the last piece (not stored)
-            const int rrow = idx / PPR, pc = idx % PPR;
-            const int j = kc * KC + rrow;
-            const int d0 = q0 * 8 + pc * E;
-            pf[i] = frag_keep<T>(load_frag_clamped<T, ALIGNED>(a.C + (int64_t)min(j, a.K - 1) * D, d0, D),
-                                 d0, D, j < a.K);
+            const int j = kc * KC + st_row[i];
+            const int d0 = q0 * 8 + st_pc[i] * E;
+            pf[i] = load_frag_clamped<T, ALIGNED>(a.C + (int64_t)min(j, a.K - 1) * D, d0, D);
         }
 #pragma unroll
         for (int e = 0; e < E; ++e) pfx[e] = T(0);
@@ -193,11 +201,16 @@ __global__ __launch_bounds__(256, (GenericCfg<T, KTV>::WAVES_PER_SIMD)) void ass
     };
     auto commit = [&](int kc, int dc, int buf) {
         unsigned char *const base = lds_raw + buf * STAGE_BYTES;
+        const int q0 = dc * DQ;
 #pragma unroll
         for (int i = 0; i < NP; ++i) {
             const int idx = tid + 256 * i;
-            if (NPIECES % 256 == 0 || idx < NPIECES)
-                *reinterpret_cast<frag_t *>(base + (idx / PPR) * SB + (idx % PPR) * 16) = pf[i];
+            if (NPIECES % 256 == 0 || idx < NPIECES) {
+                const int j = kc * KC + st_row[i];
+                const int d0 = q0 * 8 + st_pc[i] * E;
+                *reinterpret_cast<frag_t *>(base + st_row[i] * SB + st_pc[i] * 16) =
+                    frag_keep<T>(pf[i], d0, D, j < a.K);
+            }
         }
         if (dc == 0 && tid < KC / E)
             *reinterpret_cast<frag_t *>(lds_hcn + ((kc & 1) * KC + tid * E) * (int)sizeof(T)) = pfx;

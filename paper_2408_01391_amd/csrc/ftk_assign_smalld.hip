@@ -224,16 +224,23 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
     // lane, and sending every such point to the refine kernel (all K distances) costs far more.
     int blk = blockIdx.x;
     bool second_round = false;
-    int nlist = 0;
+    int nlist = 0, unit = 0;
     while (true) {
         if (!second_round && blk >= a.nblocks) {
             if (!defer) break;
             __syncthreads();  // every wave is through its blocks: the list is complete
             second_round = true;
             nlist = min(sh_wlcnt, SMALLD_LIST_CAP);
-            if (wave * (PT * 32) >= nlist) break;
+            // Units of PT*32 entries go to every other wave: the even ones in workgroups of the first
+            // 256, the odd ones in the rest.  With two workgroups per CU (consecutive waves sit on
+            // consecutive SIMDs) the few sweeping waves of both then tend to land on different SIMDs
+            // instead of sharing two of the four.
+            const int parity = (int)(blockIdx.x >> 8) & 1;
+            if ((wave & 1) != parity) break;
+            unit = wave >> 1;
         }
-        const int64_t p0 = second_round ? (int64_t)wave * (PT * 32) : ((int64_t)blk * SMALLD_WAVES + wave) * (PT * 32);
+        if (second_round && unit * (PT * 32) >= nlist) break;
+        const int64_t p0 = second_round ? (int64_t)unit * (PT * 32) : ((int64_t)blk * SMALLD_WAVES + wave) * (PT * 32);
         const int64_t npoints = second_round ? (int64_t)nlist : a.N;
         floatx4 xf[PT][NQ];
         float xn[PT];
@@ -518,7 +525,10 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
             else
                 block_list_push(need, (int32_t)p, sh_wl, &sh_wlcnt, a.wl, a.wl_count);
         }
-        if (second_round) break;
+        if (second_round) {
+            unit += SMALLD_WAVES / 2;
+            continue;
+        }
         if (resident && a.n_faults == 0) {
             blk += (int)gridDim.x;
             continue;

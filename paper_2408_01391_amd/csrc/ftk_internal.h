@@ -94,9 +94,11 @@ struct Workspace {
     int64_t *idx;       // [K]   seeded initial point indices
     // fast (split-bf16) assignment
     void *csplit;       // centroid pieces in LDS image order (fp32 data with D <= 32, else empty)
+    int32_t *batch_counters;  // [4 * MAX_BATCHES] work-list counters per batch of the batched step
     size_t total;
 };
 constexpr int FIT_MAX_ITERS_IN_WS = 4096;
+constexpr int MAX_BATCHES = 4096;
 size_t hcn_entries_max(ftk_dtype dtype, int64_t N, int D, int K);
 // assign_only: stop after the assignment step's buffers (a prefix of the full layout)
 Workspace carve_workspace(void *base, ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft,
@@ -137,6 +139,20 @@ ftk_status launch_update(ftk_dtype dtype, const void *X, const int32_t *labels, 
                          int K, void *C, int32_t *counts, const double *absmax, const Workspace &w,
                          ftk_ft_mode ft_mode, const ftk_fault *faults, int n_faults, ftk_ft_stats *stats,
                          hipStream_t st);
+// update accumulated over several launches (batches of rows), finished by one averaging pass
+struct BatchedUpdatePlan {
+    int Ks, Ds, nks, nds, tx_log2, chunks;
+    bool aligned, ok;
+    int64_t scale_rows;
+};
+BatchedUpdatePlan plan_update_batched(ftk_dtype dtype, const void *X, int64_t N, int64_t batch_rows, int D, int K);
+ftk_status launch_update_batch(ftk_dtype dtype, const void *Xb, const int32_t *labels_b, int64_t nb, int D, int K,
+                               const double *absmax, const Workspace &w, const BatchedUpdatePlan &b, bool first,
+                               hipStream_t st);
+ftk_status launch_update_batched_finalize(ftk_dtype dtype, int D, int K, const double *absmax, void *C,
+                                          int32_t *counts, const Workspace &w, const BatchedUpdatePlan &b,
+                                          hipStream_t st);
+ftk_status launch_zero_ints(int32_t *p, int n, hipStream_t st);
 void update_geometry(ftk_dtype dtype, bool aligned16, int64_t N, int D, int K, ftk_geometry *out);
 ftk_status launch_gather_rows(ftk_dtype dtype, const void *X, int D, const int64_t *idx_dev, int K,
                               void *C, hipStream_t st);

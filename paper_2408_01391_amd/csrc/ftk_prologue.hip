@@ -177,6 +177,18 @@ ftk_status launch_centroid_prologue(const AssignCall &c, const AssignPlan &p, co
     return FTK_OK;
 }
 
+__global__ void zero_ints_kernel(int32_t *p, int n)
+{
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0;
+}
+
+ftk_status launch_zero_ints(int32_t *p, int n, hipStream_t st)
+{
+    hipLaunchKernelGGL(zero_ints_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, st, p, n);
+    FTK_TRY_HIP(hipGetLastError());
+    return FTK_OK;
+}
+
 // ---- |x| maximum ---------------------------------------------------------------------------
 __global__ void reset_double_kernel(double *p)
 {

@@ -183,7 +183,7 @@ template <typename T, bool ALIGNED, bool DMR>
 __global__ __launch_bounds__(UPD_THREADS) void update_accumulate_kernel(
     const T *X, const int32_t *labels, int64_t N, int D, int K, const double *absmax_p,
     long long *slabs, int32_t *cslabs, int Ks, int Ds, int nds, int tx_log2,
-    int64_t rows_per_chunk, UpdateFtArgs ft)
+    int64_t rows_per_chunk, int64_t scale_rows, int accumulate, UpdateFtArgs ft)
 {
     using F = typename Mma<T>::frag_t;
     constexpr int E = ALIGNED ? Mma<T>::E : 1;
@@ -201,9 +201,10 @@ __global__ __launch_bounds__(UPD_THREADS) void update_accumulate_kernel(
     const int dn = min(Ds, D - d0);  // features in this slice
     const int kn = min(Ks, K - k0);
     // fp32 data: 24-bit mantissas leave ample room, one limb scaled for the whole of N;
-    // fp64 data: scale for this workgroup's rows only and flush into two limbs
-    constexpr bool TWO_LIMB = sizeof(T) == 8;
-    const double scale = fixed_point_scale(*absmax_p, TWO_LIMB ? rows_per_chunk : N);
+    // fp64 data: scale for the rows that meet in this workgroup's table only (scale_rows: one
+    // chunk of rows, times the number of batches when the table is accumulated over several
+    // launches) and flush into two limbs
+    const double scale = fixed_point_scale(*absmax_p, scale_rows);
     const double scale2 = dmr_copy(scale);
     const int TX = 1 << tx_log2, TY = UPD_THREADS >> tx_log2;
     const int tx = tid & (TX - 1), ty = tid >> tx_log2;
@@ -335,13 +336,21 @@ __global__ __launch_bounds__(UPD_THREADS) void update_accumulate_kernel(
     // slice, zeros included, so the tables need no clearing).  Device-wide atomics on one shared
     // table cost a memory-side transaction per cell and workgroup; the tables are summed by the
     // averaging kernel instead, in integers, so the result is still independent of any order.
+    // (`accumulate`: a later batch of the same Lloyd iteration adds to what its predecessors left;
+    // a table cell belongs to one workgroup, so this needs no atomics either.)
     long long *slab = slabs + (int64_t)blockIdx.x * ((int64_t)K * D);
     for (int i = tid; i < kn * Ds; i += UPD_THREADS) {
         const int k = i / Ds, d = i - k * Ds;
-        if (d < dn) slab[(int64_t)(k0 + k) * D + d0 + d] = (long long)cell[i];
+        if (d < dn) {
+            long long *dst = slab + (int64_t)(k0 + k) * D + d0 + d;
+            *dst = (accumulate ? *dst : 0ll) + (long long)cell[i];
+        }
     }
     if (ds_i == 0)
-        for (int i = tid; i < kn; i += UPD_THREADS) cslabs[(int64_t)blockIdx.x * K + k0 + i] = cnt[i];
+        for (int i = tid; i < kn; i += UPD_THREADS) {
+            int32_t *dst = cslabs + (int64_t)blockIdx.x * K + k0 + i;
+            *dst = (accumulate ? *dst : 0) + cnt[i];
+        }
 }
 
 // Sum of the per-chunk tables and averaging pass ("the last kernel", Section 3.1.1) in one:
@@ -355,7 +364,7 @@ constexpr int RF_CELLS = 32, RF_GROUPS = 32;
 // mismatch is settled by a third pass.
 template <typename T, bool DMR>
 __global__ __launch_bounds__(RF_CELLS * RF_GROUPS) void update_reduce_finalize_kernel(
-    const long long *slabs, const int32_t *cslabs, int chunks, int64_t N, int64_t rows_per_chunk, int D,
+    const long long *slabs, const int32_t *cslabs, int chunks, int64_t scale_rows, int D,
     int K, const double *absmax_p, T *C, int32_t *counts, ftk_ft_stats *stats)
 {
     constexpr bool TWO_LIMB = sizeof(T) == 8;
@@ -446,7 +455,7 @@ __global__ __launch_bounds__(RF_CELLS * RF_GROUPS) void update_reduce_finalize_k
         if (cell < cells) {
             const int n = sh_cnt[0][(int)(cell / D) - row0];
             if (n > 0) {
-                const double inv = 1.0 / fixed_point_scale(*absmax_p, TWO_LIMB ? rows_per_chunk : N);
+                const double inv = 1.0 / fixed_point_scale(*absmax_p, scale_rows);
                 C[cell] = fixed_point_mean<T, DMR>(hi, lo, inv, n, &detected);
             }
         }
@@ -998,9 +1007,11 @@ ftk_status launch_update(ftk_dtype dtype, const void *X, const int32_t *labels, 
         const size_t lds = (size_t)u.Ks * u.Ds * 8 + (size_t)u.Ks * 4;
         dim3 grid(u.chunks, u.nds * u.nks), block(UPD_THREADS);
         long long *slabs = reinterpret_cast<long long *>(w.upd_slab);
+        const int64_t scale_rows = dtype == FTK_F64 ? u.rows_per_chunk : N;
 #define FTK_LAUNCH_ACC(T, AL, DM)                                                                      \
     hipLaunchKernelGGL((update_accumulate_kernel<T, AL, DM>), grid, block, lds, st, (const T *)X, labels, \
-                       N, D, K, absmax, slabs, w.upd_cslab, u.Ks, u.Ds, u.nds, u.tx_log2, u.rows_per_chunk, fa)
+                       N, D, K, absmax, slabs, w.upd_cslab, u.Ks, u.Ds, u.nds, u.tx_log2, u.rows_per_chunk, \
+                       scale_rows, 0, fa)
 #define FTK_LAUNCH_ACC_T(T)                                \
     do {                                                   \
         if (u.aligned && dmr) FTK_LAUNCH_ACC(T, true, true);       \
@@ -1015,7 +1026,7 @@ ftk_status launch_update(ftk_dtype dtype, const void *X, const int32_t *labels, 
         const int blocks = (int)ceil_div(cells, RF_CELLS);
 #define FTK_LAUNCH_RF(T, DM)                                                                                  \
     hipLaunchKernelGGL((update_reduce_finalize_kernel<T, DM>), dim3(blocks), dim3(RF_CELLS * RF_GROUPS), 0, st, \
-                       slabs, w.upd_cslab, u.chunks, N, u.rows_per_chunk, D, K, absmax, (T *)C, counts, stats)
+                       slabs, w.upd_cslab, u.chunks, scale_rows, D, K, absmax, (T *)C, counts, stats)
         if (dtype == FTK_F32) {
             if (dmr) FTK_LAUNCH_RF(float, true);
             else FTK_LAUNCH_RF(float, false);
@@ -1025,6 +1036,74 @@ ftk_status launch_update(ftk_dtype dtype, const void *X, const int32_t *labels, 
         }
 #undef FTK_LAUNCH_RF
     }
+    FTK_TRY_HIP(hipGetLastError());
+    return FTK_OK;
+}
+
+// ---- update accumulated over batches of rows (the batched Lloyd step) ------------------------
+// The per-workgroup LDS tables of one batch are added to the tables in global memory its
+// predecessors left (plain read-modify-write: a table belongs to one workgroup), and the
+// reduce-and-average kernel runs once after the last batch.  The plan is the one of a full batch;
+// a shorter last batch only changes the rows per workgroup.
+BatchedUpdatePlan plan_update_batched(ftk_dtype dtype, const void *X, int64_t N, int64_t batch_rows, int D, int K)
+{
+    const UpdatePlan u = plan_update(dtype, X, batch_rows < N ? batch_rows : N, D, K);
+    BatchedUpdatePlan b;
+    b.Ks = u.Ks;
+    b.Ds = u.Ds;
+    b.nks = u.nks;
+    b.nds = u.nds;
+    b.tx_log2 = u.tx_log2;
+    b.chunks = u.chunks;
+    b.aligned = u.aligned;
+    const int64_t nbatch = ceil_div(N, batch_rows);
+    b.scale_rows = dtype == FTK_F64 ? u.rows_per_chunk * nbatch : N;
+    b.ok = u.chunks <= update_slab_chunks_max(N) && (int64_t)u.chunks * K * D <= update_slab_cells_max(N, D, K);
+    return b;
+}
+
+ftk_status launch_update_batch(ftk_dtype dtype, const void *Xb, const int32_t *labels_b, int64_t nb, int D, int K,
+                               const double *absmax, const Workspace &w, const BatchedUpdatePlan &b, bool first,
+                               hipStream_t st)
+{
+    const size_t lds = (size_t)b.Ks * b.Ds * 8 + (size_t)b.Ks * 4;
+    dim3 grid(b.chunks, b.nds * b.nks), block(UPD_THREADS);
+    long long *slabs = reinterpret_cast<long long *>(w.upd_slab);
+    const int64_t rows_per_chunk = ceil_div(nb, b.chunks);
+    UpdateFtArgs fa;
+    fa.faults = nullptr;
+    fa.n_faults = 0;
+    fa.mode = (int)FTK_FT_OFF;
+    fa.stats = nullptr;
+#define FTK_LAUNCH_ACC(T, AL)                                                                             \
+    hipLaunchKernelGGL((update_accumulate_kernel<T, AL, false>), grid, block, lds, st, (const T *)Xb, labels_b, \
+                       nb, D, K, absmax, slabs, w.upd_cslab, b.Ks, b.Ds, b.nds, b.tx_log2, rows_per_chunk,  \
+                       b.scale_rows, first ? 0 : 1, fa)
+    if (dtype == FTK_F32) {
+        if (b.aligned) FTK_LAUNCH_ACC(float, true);
+        else FTK_LAUNCH_ACC(float, false);
+    } else {
+        if (b.aligned) FTK_LAUNCH_ACC(double, true);
+        else FTK_LAUNCH_ACC(double, false);
+    }
+#undef FTK_LAUNCH_ACC
+    FTK_TRY_HIP(hipGetLastError());
+    return FTK_OK;
+}
+
+ftk_status launch_update_batched_finalize(ftk_dtype dtype, int D, int K, const double *absmax, void *C,
+                                          int32_t *counts, const Workspace &w, const BatchedUpdatePlan &b,
+                                          hipStream_t st)
+{
+    const int64_t cells = (int64_t)K * D;
+    const int blocks = (int)ceil_div(cells, RF_CELLS);
+    const long long *slabs = reinterpret_cast<const long long *>(w.upd_slab);
+    if (dtype == FTK_F32)
+        hipLaunchKernelGGL((update_reduce_finalize_kernel<float, false>), dim3(blocks), dim3(RF_CELLS * RF_GROUPS), 0, st,
+                           slabs, w.upd_cslab, b.chunks, b.scale_rows, D, K, absmax, (float *)C, counts, nullptr);
+    else
+        hipLaunchKernelGGL((update_reduce_finalize_kernel<double, false>), dim3(blocks), dim3(RF_CELLS * RF_GROUPS), 0, st,
+                           slabs, w.upd_cslab, b.chunks, b.scale_rows, D, K, absmax, (double *)C, counts, nullptr);
     FTK_TRY_HIP(hipGetLastError());
     return FTK_OK;
 }
