@@ -295,8 +295,8 @@ ftk_status ftk_profile_read(double *total_ms, int64_t *launches);
  * later call of this process, the choices the library otherwise makes by rule; -1 restores a
  * rule.  Every forced choice computes the same results.
  *   assign_variant : 0 = generic kernel, 1 = small-D kernel where it applies (fp32, D <= 32)
- *   generic_tiles  : centroid tiles per chunk of the generic kernel, 1, 2, 4 or 8 (8: fp64
- *                    only, one point tile per wave; taken as 4 for fp32)
+ *   generic_tiles  : centroid tiles per chunk of the generic kernel, 1, 2, 4 or 8 (8: one point
+ *                    tile per wave instead of two; chosen by rule only for fp64 with long rows)
  *   update_path    : 0 = per-workgroup LDS tables, 1 = label-sorted gather
  * Process-wide and not synchronised: set it while no call is in flight.  The workspace size
  * does not depend on it. */

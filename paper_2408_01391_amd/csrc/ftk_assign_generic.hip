@@ -44,10 +44,13 @@ struct GenericArgs {
     int n_faults;
     int ft_mode;
     double ft_coef;    // detection threshold = ft_coef * (||x|| * max||c|| + max||c||^2 / 2)
-    double widen_coef; // the same in strict mode (the ambiguity band grows by the threshold), else 0
+    double widen_coef; // half of it in strict mode (the ambiguity band grows by residual + noise), else 0
 };
 
 constexpr int GENERIC_MAX_FAULTS = 4;
+#ifndef GENERIC_DQ_F32_KT4
+#define GENERIC_DQ_F32_KT4 2
+#endif
 
 // Detection threshold = coefficient * u * B, B = ||x|| max||c|| + max||c||^2/2, for a check over
 // n = KC scores of D features.  The coefficient models the rounding noise of a fault-free
@@ -76,9 +79,15 @@ static double generic_ft_coef(int n, int D)
 // tiles the stages hold little matrix work and the kernel is bound by the latency of the point
 // loads; KT = 1 / 2 free the accumulator registers for more resident waves, i.e. more loads in
 // flight.
+// quads (8 features) per LDS stage.  Two everywhere: four for the fp32 workhorse (half as many
+// barriers) needs 40 more registers for the point fragments, spills, and measured 8 % slower
+// (c3: 170 against 158 us; with checksums 211 against 168 us).
+constexpr int generic_dq(bool f32, int kt) { return (f32 && kt == 4) ? GENERIC_DQ_F32_KT4 : 2; }
+
 template <typename T, int KT_>
 struct GenericCfg {
-    static constexpr int PT = KT_ == 8 ? 1 : 2, KT = KT_, WAVES = 4, DQ = 2;
+    static constexpr int PT = KT_ == 8 ? 1 : 2, KT = KT_, WAVES = 4;
+    static constexpr int DQ = generic_dq(sizeof(T) == 4, KT_);
     static constexpr int WAVES_PER_SIMD = KT_ == 8 ? 2 : (KT_ == 4 ? (sizeof(T) == 4 ? 2 : 3) : (KT_ == 2 ? 3 : 4));
 };
 // number of accumulator tiles used for a problem with K centroids
@@ -124,6 +133,7 @@ __global__ __launch_bounds__(256, (GenericCfg<T, KTV>::WAVES_PER_SIMD)) void ass
     T bm1[PT], bm2[PT];
     int bt[PT];  // -1: no tile has produced a comparable score yet
     T xn[PT];
+    T rmax[PT];             // largest checksum residual below the threshold over this point's chunks
     int force_refine[PT];   // a chunk of this point failed checksum correction (int, not bool:
                             // a bool array updated inside the rare branch lost its value when compiled)
 #pragma unroll
@@ -131,6 +141,7 @@ __global__ __launch_bounds__(256, (GenericCfg<T, KTV>::WAVES_PER_SIMD)) void ass
         bm1[pt] = bm2[pt] = M::neg_inf();
         bt[pt] = -1;
         xn[pt] = T(0);
+        rmax[pt] = T(0);
         force_refine[pt] = 0;
     }
     const T cmax2 = (T)a.scal[0];
@@ -443,6 +454,7 @@ __global__ __launch_bounds__(256, (GenericCfg<T, KTV>::WAVES_PER_SIMD)) void ass
                     }
                 }
                 worst_resid = fmaxf(worst_resid, bad ? 0.f : (float)(fabs(resid) / tau));
+                rmax[pt] = fmax(rmax[pt], bad ? T(0) : fabs(resid));
             }
         }
 
@@ -522,7 +534,11 @@ __global__ __launch_bounds__(256, (GenericCfg<T, KTV>::WAVES_PER_SIMD)) void ass
         const bool live = p < a.N;
         // scores inside `bound` of each other cannot be ordered: rounding of the expanded form,
         // plus (strict FT) an undetected error below the detection threshold
-        const T bound = (T)(a.band_coef + (FT ? a.widen_coef : 0.0)) * (sqrt(xn[pt]) * cmax + (T)0.5 * cmax2);
+        // (strict FT: an error that stayed below the detection threshold shows in the residual of
+        // its chunk, |error| <= |residual| + rounding noise, the noise taken as at most half the
+        // threshold; widen_coef is half the threshold coefficient in strict mode, else zero)
+        T bound = (T)(a.band_coef + (FT ? a.widen_coef : 0.0)) * (sqrt(xn[pt]) * cmax + (T)0.5 * cmax2);
+        if (FT && a.widen_coef > 0.0) bound += rmax[pt];
         const bool amb2 = (m1 - m2) <= bound;
         // a runner-up whose centroid is unknown cannot be settled in place: leave it to the refine kernel
         const bool amb3 = ((m1 - m3) <= bound) || force_refine[pt] != 0 || (amb2 && i2 < 0);
@@ -786,7 +802,7 @@ static ftk_status launch_generic_t(const AssignCall &c, const AssignPlan &p, con
     a.n_faults = c.n_faults;
     a.ft_mode = (int)c.ft;
     a.ft_coef = p.ft_coef;
-    a.widen_coef = c.ft == FTK_FT_STRICT ? a.ft_coef : 0.0;
+    a.widen_coef = c.ft == FTK_FT_STRICT ? 0.5 * a.ft_coef : 0.0;
     const bool aligned = (c.D % Mma<T>::E == 0) && ((uintptr_t)c.X % 16 == 0) && ((uintptr_t)c.C % 16 == 0);
     const bool ft = c.ft != FTK_FT_OFF;
     dim3 grid((unsigned)p.workgroups), block(256);
@@ -799,15 +815,8 @@ static ftk_status launch_generic_t(const AssignCall &c, const AssignPlan &p, con
         else if (ft) FTK_LAUNCH_GEN(KV, false, true);          \
         else FTK_LAUNCH_GEN(KV, false, false);                 \
     } while (0)
-    bool wide = false;
-    if constexpr (sizeof(T) == 8) {
-        if (p.KT == 8) {
-            FTK_LAUNCH_GEN_K(8);
-            wide = true;
-        }
-    }
-    if (wide) {
-    } else if (p.KT == 4) FTK_LAUNCH_GEN_K(4);
+    if (p.KT == 8) FTK_LAUNCH_GEN_K(8);
+    else if (p.KT == 4) FTK_LAUNCH_GEN_K(4);
     else if (p.KT == 2) FTK_LAUNCH_GEN_K(2);
     else FTK_LAUNCH_GEN_K(1);
 #undef FTK_LAUNCH_GEN_K
@@ -870,13 +879,12 @@ void plan_generic(ftk_dtype dtype, int64_t N, int D, int K, AssignPlan &p)
     // the same layout measured slower there.
     if (!f32 && D >= 512 && K > 4 * Mma<double>::TM) p.KT = 8;
     if (g_tuning.kt > 0) p.KT = g_tuning.kt;
-    if (f32 && p.KT == 8) p.KT = 4;
     p.PT = p.KT == 8 ? 1 : 2;
     p.waves = 4;
     p.KC = p.KT * p.TM;
     p.nkc = (int)ceil_div(K, p.KC);
     p.D8 = (int)ceil_div(D, 8) * 8;
-    p.DQ = 2;
+    p.DQ = generic_dq(f32, p.KT);
     p.points_per_wg = p.waves * p.PT * p.TN;
     p.workgroups = ceil_div(N, p.points_per_wg);
     p.tiles_per_wave = p.nkc * p.PT * p.KT;

@@ -231,11 +231,11 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
             __syncthreads();  // every wave is through its blocks: the list is complete
             second_round = true;
             nlist = min(sh_wlcnt, SMALLD_LIST_CAP);
-            // Units of PT*32 entries go to every other wave: the even ones in workgroups of the first
-            // 256, the odd ones in the rest.  With two workgroups per CU (consecutive waves sit on
-            // consecutive SIMDs) the few sweeping waves of both then tend to land on different SIMDs
-            // instead of sharing two of the four.
-            const int parity = (int)(blockIdx.x >> 8) & 1;
+            // Units of PT*32 entries go to every other wave: the even ones in even-numbered
+            // workgroups, the odd ones in odd-numbered ones, so that the few sweeping waves of two
+            // workgroups sharing a CU (consecutive waves sit on consecutive SIMDs) tend to land on
+            // different SIMDs instead of sharing two of the four.
+            const int parity = (int)blockIdx.x & 1;
             if ((wave & 1) != parity) break;
             unit = wave >> 1;
         }
@@ -463,7 +463,11 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
             // scores inside `bound` of each other cannot be ordered: rounding of the expanded
             // form, plus (strict FT) an undetected error below the detection threshold
             float bound = (float)a.band_coef * (sqrtf(xn[pt]) * cmax + 0.5f * cmax2);
-            if (FT) bound = fmaf(a.widen, tau[pt], bound);
+            // strict FT: an error that stayed below the detection threshold left its mark in the
+            // residual of its tile, |error| <= |residual| + rounding noise; the noise is taken as at
+            // most half the threshold (fault-free residuals reach about 0.3 of it), the residual as
+            // the largest either lane of the point saw
+            if (FT) bound += a.widen * (fmaxf(rmax[pt], __shfl_xor(rmax[pt], 32, 64)) + 0.5f * tau[pt]);
             const float om1 = __shfl_xor(best[pt].m1, 32, 64), om2 = __shfl_xor(best[pt].m2, 32, 64);
             const int ot1 = __shfl_xor(best[pt].t1, 32, 64);
             const bool mine_wins = best[pt].m1 > om1 || (best[pt].m1 == om1 && g == 0);
