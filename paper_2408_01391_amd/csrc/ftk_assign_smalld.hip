@@ -222,26 +222,10 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
     // extra record costs four vector instructions per tile, which is why the first round does not
     // keep it; evaluating a second group where it turns up would make a whole wave pay for one
     // lane, and sending every such point to the refine kernel (all K distances) costs far more.
-    int blk = blockIdx.x;
-    bool second_round = false;
-    int nlist = 0, unit = 0;
-    while (true) {
-        if (!second_round && blk >= a.nblocks) {
-            if (!defer) break;
-            __syncthreads();  // every wave is through its blocks: the list is complete
-            second_round = true;
-            nlist = min(sh_wlcnt, SMALLD_LIST_CAP);
-            // Units of PT*32 entries go to every other wave: the even ones in even-numbered
-            // workgroups, the odd ones in odd-numbered ones, so that the few sweeping waves of two
-            // workgroups sharing a CU (consecutive waves sit on consecutive SIMDs) tend to land on
-            // different SIMDs instead of sharing two of the four.
-            const int parity = (int)blockIdx.x & 1;
-            if ((wave & 1) != parity) break;
-            unit = wave >> 1;
-        }
-        if (second_round && unit * (PT * 32) >= nlist) break;
-        const int64_t p0 = second_round ? (int64_t)unit * (PT * 32) : ((int64_t)blk * SMALLD_WAVES + wave) * (PT * 32);
-        const int64_t npoints = second_round ? (int64_t)nlist : a.N;
+    // one unit of work of a wave: PT*32 points starting at p0 of `npoints` (first round: points of
+    // X; second round, R2: entries of the workgroup's list), swept over all tiles and settled
+    auto process = [&](auto r2_tag, int64_t p0, int64_t npoints, int blk) {
+        constexpr bool R2 = decltype(r2_tag)::value;
         floatx4 xf[PT][NQ];
         float xn[PT];
         float tau[PT];          // checksum detection threshold of this lane's point
@@ -250,15 +234,15 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
                                 // array updated inside the rare branch lost its value when compiled)
         float rmax[PT];         // largest |residual| below the threshold over this point's tiles
         TileBest best[PT];
-        float m3[PT];           // second round: third-best tile maximum and the runner-up's tile
-        int t2[PT];
-        int64_t pidx[PT];       // the point this lane works on (-1: none)
+        float m3[R2 ? PT : 1];  // second round: third-best tile maximum and the runner-up's tile
+        int t2[R2 ? PT : 1];
+        int pidx[PT];           // the point this lane works on (-1: none)
 #pragma unroll
         for (int pt = 0; pt < PT; ++pt) {
             int64_t p = p0 + pt * 32 + col;
             if (p >= npoints) p = npoints - 1;
-            if (second_round) p = sh_wl[p];
-            pidx[pt] = p;
+            if (R2) p = sh_wl[p];
+            pidx[pt] = (int)p;
             const float *xrow = a.X + (p < 0 ? 0 : p) * D;
             float s = 0.f;
 #pragma unroll
@@ -272,13 +256,17 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
             inv_tau[pt] = 1.0f / tau[pt];
             force_refine[pt] = 0;
             rmax[pt] = 0.f;
-            best[pt].m1 = best[pt].m2 = m3[pt] = M::neg_inf();
-            best[pt].t1 = t2[pt] = 0;
+            best[pt].m1 = best[pt].m2 = M::neg_inf();
+            best[pt].t1 = 0;
+            if constexpr (R2) {
+                m3[pt] = M::neg_inf();
+                t2[pt] = 0;
+            }
         }
 
         // faults aimed at this point block (descriptors address the blocks of the first round)
         int nf = 0;
-        if (a.n_faults > 0 && !second_round) {
+        if (!R2 && a.n_faults > 0) {
             if (tid == 0) sh_nf = 0;
             __syncthreads();
             for (int i = tid; i < a.n_faults; i += SMALLD_THREADS) {
@@ -435,7 +423,7 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
                     if (t + 1 < ntile) compute_tile(inj_tag, round2_tag, avB, ciB, tile0 + t + 1);
                 }
             };
-            if (second_round)
+            if (R2)
                 sweep(std::false_type{}, std::true_type{});
             else if (nf > 0)
                 sweep(std::true_type{}, std::false_type{});
@@ -495,7 +483,7 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
             const bool cand_b = fminf(best[pt].m1, om1) >= thr;
             const int Tb = mine_wins ? ot1 : best[pt].t1;
             bool unsettled;
-            if (!second_round) {
+            if constexpr (!R2) {
                 // ... evaluated here unless ambiguous points are deferred; a runner-up tile of either
                 // lane is not on record in this round
                 if (!defer && __any(cand_b)) eval_group(Tb, 1 - gw, cand_b);
@@ -524,15 +512,16 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
             }
             // NaN scores, more candidates than are on record, or a failed repair: exact recomputation
             const bool need = live && g == 0 && (!(thr == thr) || unsettled || forced);
-            if (second_round)
+            if (R2)
                 worklist_push(need, (int32_t)p, a.wl, a.wl_count);
             else
                 block_list_push(need, (int32_t)p, sh_wl, &sh_wlcnt, a.wl, a.wl_count);
         }
-        if (second_round) {
-            unit += SMALLD_WAVES / 2;
-            continue;
-        }
+    };
+
+    int blk = blockIdx.x;
+    while (blk < a.nblocks) {
+        process(std::false_type{}, ((int64_t)blk * SMALLD_WAVES + wave) * (PT * 32), a.N, blk);
         if (resident && a.n_faults == 0) {
             blk += (int)gridDim.x;
             continue;
@@ -541,6 +530,17 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
         if (tid == 0) sh_next = (int)gridDim.x + atomicAdd(a.wl_count + 1, 1);
         __syncthreads();
         blk = sh_next;
+    }
+    if (defer) {
+        __syncthreads();  // every wave is through its blocks: the list is complete
+        const int nlist = min(sh_wlcnt, SMALLD_LIST_CAP);
+        // Units of PT*32 entries go to every other wave: the even ones in even-numbered
+        // workgroups, the odd ones in odd-numbered ones, so that the few sweeping waves of two
+        // workgroups sharing a CU (consecutive waves sit on consecutive SIMDs) tend to land on
+        // different SIMDs instead of sharing two of the four.
+        if ((wave & 1) == ((int)blockIdx.x & 1))
+            for (int unit = wave >> 1; unit * (PT * 32) < nlist; unit += SMALLD_WAVES / 2)
+                process(std::true_type{}, (int64_t)unit * (PT * 32), (int64_t)nlist, 0);
     }
 
     if (!defer) {  // hand the collected work-list entries over to the refine kernel
