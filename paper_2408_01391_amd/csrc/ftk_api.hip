@@ -68,7 +68,7 @@ size_t hcn_entries_max(ftk_dtype dtype, int64_t N, int D, int K)
 {
     size_t need = (size_t)ceil_div(K, 128) * 128;  // generic: chunks of at most 128 centroids
     if (smalld_supported(dtype, D, K)) {
-        for (ftk_ft_mode ft : {FTK_FT_OFF, FTK_FT_CORRECT}) {
+        for (ftk_ft_mode ft : {FTK_FT_OFF, FTK_FT_CORRECT, FTK_FT_STRICT}) {
             AssignPlan p;
             memset(&p, 0, sizeof(p));
             plan_smalld(N, D, K, ft, p);
