@@ -57,10 +57,12 @@ typedef enum { FTK_F32 = 0, FTK_F64 = 1 } ftk_dtype;
  *             As in the paper, an error smaller than the detection threshold (the rounding
  *             noise of the checksum comparison) passes unnoticed; it can change the label
  *             of a point only if that point's two best scores are closer than the threshold.
- *   STRICT  : CORRECT, and in addition every point whose best scores are closer than the
- *             detection threshold is settled by exact re-evaluation outside the matrix
- *             path, so the labels equal those of a fault-free run whatever single error
- *             occurred.  Costs the exact re-evaluation of those points. */
+ *   STRICT  : CORRECT, and in addition every point whose decision an error below the threshold
+ *             could have changed - its best scores are closer than the largest checksum
+ *             residual seen for that point plus half the threshold for rounding noise - is
+ *             settled by exact re-evaluation, so the labels equal those of a fault-free run
+ *             whatever single error occurred per checked tile.  Costs the exact re-evaluation
+ *             of those points.  This is the mode the benchmark reports overhead for. */
 typedef enum { FTK_FT_OFF = 0, FTK_FT_DETECT = 1, FTK_FT_CORRECT = 2, FTK_FT_STRICT = 3 } ftk_ft_mode;
 
 /* One injected soft error (fault model of Section 2.1): flip `bit` of accumulator register
