@@ -15,6 +15,8 @@
 // of the sum matrix that fits 64 KB, adds into it with LDS atomics, and flushes the non-zero
 // cells to the global matrix with one integer atomic each.  Feature slices partition the
 // columns of X and cluster slices partition its rows by label, so X is read once overall.
+#include <type_traits>
+
 #include "ftk_internal.h"
 #include "ftk_mma.h"
 
@@ -189,7 +191,12 @@ __global__ __launch_bounds__(UPD_THREADS) void update_accumulate_kernel(
     constexpr int E = ALIGNED ? Mma<T>::E : 1;
     extern __shared__ __align__(16) unsigned char lds_raw[];
     unsigned long long *cell = reinterpret_cast<unsigned long long *>(lds_raw);
-    int *cnt = reinterpret_cast<int *>(cell + (size_t)Ks * Ds);
+    // table rows are padded by one cell: a row of Ds 8-byte cells is a whole number of LDS bank
+    // rounds for the slice widths in use (8, 32, 128 features), so without the pad the lanes of a
+    // wave - several point rows with different labels, same feature offsets - would all hit the
+    // same banks
+    const int Dp = Ds + 1;
+    int *cnt = reinterpret_cast<int *>(cell + (size_t)Ks * Dp);
     __shared__ unsigned long long sh_sum[4];  // [0] table total, [1] shadow total, [2] count total, [3] shadow rows
     __shared__ int sh_nf;
     __shared__ ftk_fault sh_faults[UPD_MAX_FAULTS];
@@ -222,7 +229,7 @@ __global__ __launch_bounds__(UPD_THREADS) void update_accumulate_kernel(
     // repeated).
     constexpr int ATTEMPTS = DMR ? 2 : 1;
     for (int attempt = 0; attempt < ATTEMPTS; ++attempt) {
-        for (int i = tid; i < Ks * Ds; i += UPD_THREADS) cell[i] = 0ull;
+        for (int i = tid; i < Ks * Dp; i += UPD_THREADS) cell[i] = 0ull;
         for (int i = tid; i < Ks; i += UPD_THREADS) cnt[i] = 0;
         if (tid < 4) sh_sum[tid] = 0ull;
         __syncthreads();
@@ -233,6 +240,11 @@ __global__ __launch_bounds__(UPD_THREADS) void update_accumulate_kernel(
         // UNR rows per thread and step: the label loads, then the point loads, are issued together
         // before any LDS atomic, so several HBM requests per thread are in flight
         constexpr int UNR = 4;
+        // When the slice holds every cluster the point loads do not depend on the labels and go out
+        // together with them (ALLK); otherwise only rows whose label falls into the slice are read,
+        // one memory latency after their labels.
+        auto pass = [&](auto allk_tag) {
+        constexpr bool ALLK = decltype(allk_tag)::value;
         for (int64_t row0 = r0 + ty; row0 < r1; row0 += (int64_t)TY * UNR, ++step) {
             int lab[UNR];
             bool ok[UNR];
@@ -271,7 +283,7 @@ __global__ __launch_bounds__(UPD_THREADS) void update_accumulate_kernel(
 #pragma unroll
                 for (int u = 0; u < UNR; ++u) {
                     const int64_t row = row0 + (int64_t)u * TY;
-                    if (ok[u]) {
+                    if (ALLK ? row < r1 : ok[u]) {
                         if constexpr (ALIGNED) f[u] = *reinterpret_cast<const F *>(X + row * D + d0 + pc * E);
                         else f[u][0] = X[row * D + d0 + pc];
                     }
@@ -279,7 +291,7 @@ __global__ __launch_bounds__(UPD_THREADS) void update_accumulate_kernel(
 #pragma unroll
                 for (int u = 0; u < UNR; ++u) {
                     if (ok[u]) {
-                        unsigned long long *dst = cell + (size_t)lab[u] * Ds + pc * E;
+                        unsigned long long *dst = cell + (size_t)lab[u] * Dp + pc * E;
 #pragma unroll
                         for (int e = 0; e < E; ++e) {
                             const double x = (double)f[u][e];
@@ -303,10 +315,15 @@ __global__ __launch_bounds__(UPD_THREADS) void update_accumulate_kernel(
                 }
             }
         }
+        };
+        if (kn == K)
+            pass(std::true_type{});
+        else
+            pass(std::false_type{});
         __syncthreads();
         if constexpr (DMR) {
             unsigned long long tsum = 0ull, csum = 0ull;
-            for (int i = tid; i < Ks * Ds; i += UPD_THREADS) tsum += cell[i];
+            for (int i = tid; i < Ks * Dp; i += UPD_THREADS) tsum += cell[i];
             for (int i = tid; i < Ks; i += UPD_THREADS) csum += (unsigned long long)(unsigned)cnt[i];
             // wave totals first, then one LDS atomic per wave and word
             unsigned long long v4[4] = {tsum, shadow, csum, (unsigned long long)shadow_rows};
@@ -343,7 +360,7 @@ __global__ __launch_bounds__(UPD_THREADS) void update_accumulate_kernel(
         const int k = i / Ds, d = i - k * Ds;
         if (d < dn) {
             long long *dst = slab + (int64_t)(k0 + k) * D + d0 + d;
-            *dst = (accumulate ? *dst : 0ll) + (long long)cell[i];
+            *dst = (accumulate ? *dst : 0ll) + (long long)cell[k * Dp + d];
         }
     }
     if (ds_i == 0)
@@ -1004,7 +1021,7 @@ ftk_status launch_update(ftk_dtype dtype, const void *X, const int32_t *labels, 
             set_error("internal: update tables exceed the workspace bound (chunks %d)", u.chunks);
             return FTK_EINVAL;
         }
-        const size_t lds = (size_t)u.Ks * u.Ds * 8 + (size_t)u.Ks * 4;
+        const size_t lds = (size_t)u.Ks * (u.Ds + 1) * 8 + (size_t)u.Ks * 4;
         dim3 grid(u.chunks, u.nds * u.nks), block(UPD_THREADS);
         long long *slabs = reinterpret_cast<long long *>(w.upd_slab);
         const int64_t scale_rows = dtype == FTK_F64 ? u.rows_per_chunk : N;
@@ -1066,7 +1083,7 @@ ftk_status launch_update_batch(ftk_dtype dtype, const void *Xb, const int32_t *l
                                const double *absmax, const Workspace &w, const BatchedUpdatePlan &b, bool first,
                                hipStream_t st)
 {
-    const size_t lds = (size_t)b.Ks * b.Ds * 8 + (size_t)b.Ks * 4;
+    const size_t lds = (size_t)b.Ks * (b.Ds + 1) * 8 + (size_t)b.Ks * 4;
     dim3 grid(b.chunks, b.nds * b.nks), block(UPD_THREADS);
     long long *slabs = reinterpret_cast<long long *>(w.upd_slab);
     const int64_t rows_per_chunk = ceil_div(nb, b.chunks);
