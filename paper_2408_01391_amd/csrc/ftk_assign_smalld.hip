@@ -485,7 +485,7 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
             bool unsettled;
             if constexpr (!R2) {
                 // ... evaluated here unless ambiguous points are deferred; a runner-up tile of either
-                // lane is not on record in this round
+                // lane is not on record in the first round
                 if (!defer && __any(cand_b)) eval_group(Tb, 1 - gw, cand_b);
                 unsettled = (defer && cand_b) || fmaxf(best[pt].m2, om2) >= thr;
             } else {
