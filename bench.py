@@ -234,7 +234,7 @@ def fast_mode_times(torch, ftk, s, steps, warmup, repeats, sec_per_step_fp32):
 
 
 def ablation_times(ftk, torch, s, esz):
-    """Whole assignment (all its kernels) by the three steps of Section 3.1: milliseconds per call
+    """Whole assignment (all its kernels) by the steps of Section 3.1: milliseconds per call
     and the labels each variant changes against the fused kernel."""
     from paper_2408_01391_amd import ablation
 
@@ -263,6 +263,14 @@ def ablation_times(ftk, torch, s, esz):
         del gws
     else:
         res["gemm_unfused_ms"] = None  # the N x K product alone would take more than 48 GB
+    for variant in (2, 3):  # Sections 3.1.3 / 3.1.4: GEMM on the plain ALUs with the minimum fused in
+        if variant == 3 and esz == 8:
+            continue  # its atomic key packs an fp32 distance
+        fws = ablation.fused_alu_workspace(s.Xd, K, variant)
+        res["fused_alu_v%d_ms" % variant] = timed(
+            lambda: ablation.fused_alu_assign(s.Xd, s.C0d, variant, labels=lab, mindist=s.mind, workspace=fws), 3)
+        res["fused_alu_v%d_labels_differing" % variant] = int((lab != ref).sum().item())
+        del fws
     return res
 
 

@@ -7,7 +7,13 @@
  *                 centroids and all D features (direct-difference form) and keeps the minimum;
  *   gemm_unfused  variant V1 of Section 3.1.2: centroid norms, the product X C^T from the
  *                 vendor GEMM (rocBLAS) written to memory in full, and a separate kernel that
- *                 reads it back to take the per-point arg-min.
+ *                 reads it back to take the per-point arg-min;
+ *   fused_alu     variants V2 and V3 of Sections 3.1.3 and 3.1.4: a register-tiled GEMM on the
+ *                 plain (non-matrix-core) ALUs whose epilogue takes the minimum at thread and
+ *                 threadblock level, so the product is never stored.  V2 leaves one candidate
+ *                 per point and block of 128 centroids and reduces them in a second kernel;
+ *                 V3 merges the candidates of all centroid blocks with one device-wide atomic
+ *                 minimum per point on a packed (distance, index) word.
  *
  * These are not part of the product path (libftkmeans.so neither links nor calls them).
  * Conventions as in ftkmeans.h: device pointers owned by the caller, row-major X [N x D] and
@@ -44,6 +50,17 @@ size_t ftk_abl_gemm_workspace_bytes(int dtype, int64_t N, int32_t K);
 int ftk_abl_gemm_assign(int dtype, const void *X, const void *C, int64_t N, int32_t D, int32_t K,
                         int32_t *labels, void *mindist, void *workspace, size_t workspace_bytes,
                         void *hip_stream);
+
+/* Bytes of device scratch ftk_abl_fused_alu_assign needs: the K norms plus, for variant 2, the
+ * [N][ceil(K/128)] candidate values and indices, or, for variant 3, one 64-bit word per point. */
+size_t ftk_abl_fused_alu_workspace_bytes(int dtype, int64_t N, int32_t K, int32_t variant);
+
+/* variant: 2 (both dtypes) or 3 (fp32 only: its atomic key packs a 32-bit distance with the
+ * index; fp64 with variant 3 returns 1).  Decides from the expanded form in the working
+ * precision, like the unfused variant. */
+int ftk_abl_fused_alu_assign(int dtype, const void *X, const void *C, int64_t N, int32_t D, int32_t K,
+                             int32_t *labels, void *mindist, int32_t variant, void *workspace,
+                             size_t workspace_bytes, void *hip_stream);
 
 const char *ftk_abl_last_error(void);
 

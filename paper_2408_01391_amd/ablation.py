@@ -1,5 +1,5 @@
-"""ctypes binding of libftk_ablation (measurement-only kernels: the naive kernel and the
-unfused GEMM + arg-min variant that precede the fused kernel in the paper's Section 3.1).
+"""ctypes binding of libftk_ablation (measurement-only kernels: the naive kernel, the
+unfused GEMM + arg-min variant and the plain-ALU fused variants that precede the fused kernel in the paper's Section 3.1).
 
 Not part of the product path: nothing in ``binding.py`` imports this module.
 """
@@ -14,7 +14,7 @@ _LIB_PATH = Path(__file__).resolve().parent / "libftk_ablation.so"
 _lib = None
 
 EXPORTS = ("ftk_abl_naive_assign", "ftk_abl_gemm_workspace_bytes", "ftk_abl_gemm_assign",
-           "ftk_abl_last_error")
+           "ftk_abl_fused_alu_workspace_bytes", "ftk_abl_fused_alu_assign", "ftk_abl_last_error")
 
 
 def load():
@@ -32,6 +32,10 @@ def load():
     L.ftk_abl_gemm_workspace_bytes.restype = sz
     L.ftk_abl_gemm_assign.argtypes = [i32, vp, vp, i64, i32, i32, vp, vp, vp, sz, vp]
     L.ftk_abl_gemm_assign.restype = i32
+    L.ftk_abl_fused_alu_workspace_bytes.argtypes = [i32, i64, i32, i32]
+    L.ftk_abl_fused_alu_workspace_bytes.restype = sz
+    L.ftk_abl_fused_alu_assign.argtypes = [i32, vp, vp, i64, i32, i32, vp, vp, i32, vp, sz, vp]
+    L.ftk_abl_fused_alu_assign.restype = i32
     L.ftk_abl_last_error.restype = ctypes.c_char_p
     _lib = L
     return L
@@ -78,4 +82,23 @@ def gemm_assign(X, C, labels=None, mindist=None, workspace=None):
     workspace = workspace if workspace is not None else gemm_workspace(X, K)
     _check(load().ftk_abl_gemm_assign(code, X.data_ptr(), C.data_ptr(), N, D, K, labels.data_ptr(),
                                       mindist.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()))
+    return labels, mindist
+
+
+def fused_alu_workspace(X, K, variant):
+    code = 0 if X.dtype == torch.float32 else 1
+    nbytes = load().ftk_abl_fused_alu_workspace_bytes(code, X.shape[0], K, variant)
+    return torch.empty(nbytes, dtype=torch.uint8, device=X.device)
+
+
+def fused_alu_assign(X, C, variant, labels=None, mindist=None, workspace=None):
+    code = _prep(X, C)
+    N, D = X.shape
+    K = C.shape[0]
+    labels = labels if labels is not None else torch.empty(N, dtype=torch.int32, device=X.device)
+    mindist = mindist if mindist is not None else torch.empty(N, dtype=X.dtype, device=X.device)
+    workspace = workspace if workspace is not None else fused_alu_workspace(X, K, variant)
+    _check(load().ftk_abl_fused_alu_assign(code, X.data_ptr(), C.data_ptr(), N, D, K, labels.data_ptr(),
+                                           mindist.data_ptr(), variant, workspace.data_ptr(),
+                                           workspace.numel(), _stream()))
     return labels, mindist

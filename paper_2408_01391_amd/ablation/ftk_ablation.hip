@@ -101,6 +101,151 @@ __global__ __launch_bounds__(256) void abl_rowmin_kernel(const T *S, const T *cn
     }
 }
 
+
+// ---- Sections 3.1.3 / 3.1.4: the distance GEMM on the plain ALUs with the minimum fused in -------
+// A workgroup of 256 threads owns a 128-point by 128-centroid tile of the product; a thread
+// accumulates an 8 x 8 register block of it from operand tiles of 8 features staged in LDS
+// (transposed, so that a thread's eight points / eight centroids are contiguous).  The epilogue
+// forms cn_j - 2 S_ij, takes the minimum over the thread's eight centroids (thread level), then
+// over the sixteen threads that share a point (threadblock level), and leaves ONE candidate per
+// point and centroid block: the N x K product never reaches memory.
+//   V2 (Section 3.1.3): the candidates go to a [N][K/128] array, a second kernel reduces each row.
+//   V3 (Section 3.1.4): the candidates of all centroid blocks meet in one 64-bit word per point
+//       through a device-wide atomic minimum on (value bits, index) - the counterpart of the
+//       paper's per-row lock and broadcast - so the reduction kernel disappears (fp32 only: the
+//       key packs a 32-bit value with the index).
+constexpr int VB = 128, VK = 8;
+
+// order-preserving map of a float onto unsigned integers (negative values included)
+__device__ __forceinline__ unsigned ordered_bits(float v)
+{
+    const unsigned b = __float_as_uint(v);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float from_ordered_bits(unsigned o)
+{
+    return __uint_as_float((o & 0x80000000u) ? (o & 0x7fffffffu) : ~o);
+}
+
+template <typename T, bool ATOMIC>
+__global__ __launch_bounds__(256) void abl_fused_alu_kernel(const T *X, const T *C, const T *cn, int64_t N, int D,
+                                                            int K, T *part_val, int32_t *part_idx, int ncb,
+                                                            unsigned long long *keys)
+{
+    __shared__ T Xs[VK][VB + 4], Cs[VK][VB + 4];
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;            // centroid / point sub-blocks of 8
+    const int64_t p0 = (int64_t)blockIdx.x * VB;
+    const int j0 = blockIdx.y * VB;
+    T acc[8][8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = T(0);
+    for (int d0 = 0; d0 < D; d0 += VK) {
+        // 128 rows x 8 features of each operand: four elements per thread
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int idx = tid + 256 * e, row = idx >> 3, dd = idx & 7;
+            const int64_t p = p0 + row;
+            const int j = j0 + row;
+            Xs[dd][row] = (p < N && d0 + dd < D) ? X[p * D + d0 + dd] : T(0);
+            Cs[dd][row] = (j < K && d0 + dd < D) ? C[(int64_t)j * D + d0 + dd] : T(0);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int dd = 0; dd < VK; ++dd) {
+            T xv[8], cv[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) xv[i] = Xs[dd][ty * 8 + i];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) cv[j] = Cs[dd][tx * 8 + j];
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[i][j] += xv[i] * cv[j];
+        }
+        __syncthreads();
+    }
+    T cnv[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) cnv[j] = (j0 + tx * 8 + j < K) ? cn[j0 + tx * 8 + j] : T(0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        // thread level: the best of this thread's eight centroids (increasing index, strict "<")
+        T best = 0;
+        int bj = 0x7fffffff;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int jj = j0 + tx * 8 + j;
+            const T v = cnv[j] - 2 * acc[i][j];
+            if (jj < K && (bj == 0x7fffffff || v < best)) {
+                best = v;
+                bj = jj;
+            }
+        }
+        // threadblock level: the sixteen threads of a point sit in sixteen consecutive lanes
+#pragma unroll
+        for (int m = 1; m < 16; m <<= 1) {
+            const T ob = __shfl_xor(best, m, 64);
+            const int oj = __shfl_xor(bj, m, 64);
+            if (oj != 0x7fffffff && (bj == 0x7fffffff || ob < best || (ob == best && oj < bj))) {
+                best = ob;
+                bj = oj;
+            }
+        }
+        const int64_t p = p0 + ty * 8 + i;
+        if (tx == 0 && p < N && bj != 0x7fffffff) {
+            if constexpr (ATOMIC) {
+                const unsigned long long key = ((unsigned long long)ordered_bits((float)best) << 32) | (unsigned)bj;
+                atomicMin(keys + p, key);
+            } else {
+                part_val[p * ncb + blockIdx.y] = best;
+                part_idx[p * ncb + blockIdx.y] = bj;
+            }
+        }
+    }
+}
+
+// V2: one thread per point reduces its K/128 candidates; V3: unpacks the key.  Both add ||x||^2.
+template <typename T, bool ATOMIC>
+__global__ __launch_bounds__(256) void abl_fused_finish_kernel(const T *X, int64_t N, int D, const T *part_val,
+                                                               const int32_t *part_idx, int ncb,
+                                                               const unsigned long long *keys, int32_t *labels,
+                                                               T *mindist)
+{
+    const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (p >= N) return;
+    T best = 0;
+    int bj = 0x7fffffff;
+    if constexpr (ATOMIC) {
+        const unsigned long long key = keys[p];
+        bj = (int)(unsigned)(key & 0xffffffffu);
+        best = (T)from_ordered_bits((unsigned)(key >> 32));
+    } else {
+        for (int b = 0; b < ncb; ++b) {  // increasing centroid index: strict "<" keeps the lowest on ties
+            const T v = part_val[p * ncb + b];
+            if (bj == 0x7fffffff || v < best) {
+                best = v;
+                bj = part_idx[p * ncb + b];
+            }
+        }
+    }
+    labels[p] = bj;
+    if (mindist) {
+        T xn = 0;
+        for (int d = 0; d < D; ++d) xn += X[p * D + d] * X[p * D + d];
+        const T v = xn + best;
+        mindist[p] = v > 0 ? v : 0;
+    }
+}
+
+__global__ void abl_fill_keys_kernel(unsigned long long *keys, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) keys[i] = ~0ull;
+}
+
 rocblas_handle g_handle = nullptr;
 
 bool check_shape(const void *X, const void *C, int64_t N, int32_t D, int32_t K, const int32_t *labels, int dtype)
@@ -111,6 +256,39 @@ bool check_shape(const void *X, const void *C, int64_t N, int32_t D, int32_t K, 
         return false;
     }
     return true;
+}
+
+template <typename T>
+int fused_alu_t(const void *X, const void *C, int64_t N, int32_t D, int32_t K, int32_t *labels, void *mindist,
+                       int variant, char *ws, hipStream_t st)
+{
+    const size_t esz = sizeof(T);
+    const int ncb = (K + VB - 1) / VB;
+    T *cn = (T *)ws;
+    char *rest = ws + ((size_t)K * esz + 255) / 256 * 256;
+    hipLaunchKernelGGL((abl_norms_kernel<T>), dim3((K + 3) / 4), dim3(256), 0, st, (const T *)C, D, K, cn);
+    dim3 grid((unsigned)((N + VB - 1) / VB), (unsigned)ncb);
+    const unsigned fin = (unsigned)((N + 255) / 256);
+    if (variant == 3) {
+        unsigned long long *keys = (unsigned long long *)rest;
+        hipLaunchKernelGGL(abl_fill_keys_kernel, dim3(fin), dim3(256), 0, st, keys, N);
+        hipLaunchKernelGGL((abl_fused_alu_kernel<T, true>), grid, dim3(256), 0, st, (const T *)X, (const T *)C, cn, N, D,
+                           K, (T *)nullptr, (int32_t *)nullptr, ncb, keys);
+        hipLaunchKernelGGL((abl_fused_finish_kernel<T, true>), dim3(fin), dim3(256), 0, st, (const T *)X, N, D,
+                           (const T *)nullptr, (const int32_t *)nullptr, ncb, keys, labels, (T *)mindist);
+    } else {
+        T *pv = (T *)rest;
+        int32_t *pi = (int32_t *)(rest + ((size_t)N * ncb * esz + 255) / 256 * 256);
+        hipLaunchKernelGGL((abl_fused_alu_kernel<T, false>), grid, dim3(256), 0, st, (const T *)X, (const T *)C, cn, N,
+                           D, K, pv, pi, ncb, (unsigned long long *)nullptr);
+        hipLaunchKernelGGL((abl_fused_finish_kernel<T, false>), dim3(fin), dim3(256), 0, st, (const T *)X, N, D, pv, pi,
+                           ncb, (const unsigned long long *)nullptr, labels, (T *)mindist);
+    }
+    if (hipGetLastError() != hipSuccess) {
+        set_err("kernel launch failed");
+        return 4;
+    }
+    return 0;
 }
 
 }  // namespace
@@ -206,6 +384,34 @@ int ftk_abl_gemm_assign(int dtype, const void *X, const void *C, int64_t N, int3
         return 4;
     }
     return 0;
+}
+
+
+size_t ftk_abl_fused_alu_workspace_bytes(int dtype, int64_t N, int32_t K, int32_t variant)
+{
+    const size_t esz = dtype == 0 ? 4 : 8;
+    const size_t ncb = (size_t)(K + VB - 1) / VB;
+    const size_t cn = ((size_t)K * esz + 255) / 256 * 256;
+    if (variant == 3) return cn + (size_t)N * 8;
+    return cn + (((size_t)N * ncb * esz + 255) / 256 * 256) + (size_t)N * ncb * 4;
+}
+
+int ftk_abl_fused_alu_assign(int dtype, const void *X, const void *C, int64_t N, int32_t D, int32_t K,
+                             int32_t *labels, void *mindist, int32_t variant, void *workspace,
+                             size_t workspace_bytes, void *hip_stream)
+{
+    if (!check_shape(X, C, N, D, K, labels, dtype)) return 1;
+    if ((variant != 2 && variant != 3) || (variant == 3 && dtype != 0)) {
+        set_err("invalid argument: variant %d (2 for both dtypes, 3 for fp32 only)", variant);
+        return 1;
+    }
+    if (!workspace || workspace_bytes < ftk_abl_fused_alu_workspace_bytes(dtype, N, K, variant)) {
+        set_err("workspace too small");
+        return 3;
+    }
+    hipStream_t st = (hipStream_t)hip_stream;
+    return dtype == 0 ? fused_alu_t<float>(X, C, N, D, K, labels, mindist, variant, (char *)workspace, st)
+                      : fused_alu_t<double>(X, C, N, D, K, labels, mindist, variant, (char *)workspace, st);
 }
 
 }  // extern "C"
