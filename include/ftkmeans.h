@@ -128,7 +128,8 @@ ftk_status ftk_plan_padded_rows(ftk_dtype dtype, int64_t N, int32_t D, int32_t K
  *   labels [N] int32      out : index of the nearest centroid.
  *   mindist [N] (dtype)   out : squared distance to it, >= 0; may be NULL.  Accuracy: points whose
  *                               decision was settled by exact re-evaluation, and every point of
- *                               the fp32 kernel for D <= 32, get the direct-difference value
+ *                               the register-resident fp32 kernels (D <= 32; 32 < D <= 128 where
+ *                               that kernel is dispatched), get the direct-difference value
  *                               (relative error of a few units in the last place of the
  *                               distance).  Otherwise the value comes from the expanded form of
  *                               Section 3.1.2, whose cancellation leaves an ABSOLUTE error of up
@@ -296,7 +297,9 @@ ftk_status ftk_profile_read(double *total_ms, int64_t *launches);
  * Section 3.2: measure the candidates per problem shape, keep the fastest).  Forces, for every
  * later call of this process, the choices the library otherwise makes by rule; -1 restores a
  * rule.  Every forced choice computes the same results.
- *   assign_variant : 0 = generic kernel, 1 = small-D kernel where it applies (fp32, D <= 32)
+ *   assign_variant : 0 = generic kernel, 1 = the register-resident kernels where they apply
+ *                    (fp32, 16-byte aligned rows: the small-D kernel for D <= 32, the mid-D
+ *                    kernel for 32 < D <= 128 with D a multiple of 4)
  *   generic_tiles  : centroid tiles per chunk of the generic kernel, 1, 2, 4 or 8 (8: one point
  *                    tile per wave instead of two; chosen by rule only for fp64 with long rows)
  *   update_path    : 0 = per-workgroup LDS tables, 1 = label-sorted gather

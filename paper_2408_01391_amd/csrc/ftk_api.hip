@@ -32,6 +32,9 @@ ftk_status hip_failed(hipError_t e, const char *what)
 void plan_generic(ftk_dtype dtype, int64_t N, int D, int K, AssignPlan &p);
 void plan_smalld(int64_t N, int D, int K, ftk_ft_mode ft, AssignPlan &p);
 bool smalld_supported(ftk_dtype dtype, int D, int K);
+void plan_midd(int64_t N, int D, int K, ftk_ft_mode ft, AssignPlan &p);
+bool midd_supported(ftk_dtype dtype, int D, int K);
+ftk_status launch_assign_midd(const AssignCall &c, const AssignPlan &p, const Workspace &w, hipStream_t st);
 ftk_status launch_assign_generic(const AssignCall &c, const AssignPlan &p, const Workspace &w,
                                  hipStream_t st);
 ftk_status launch_assign_smalld(const AssignCall &c, const AssignPlan &p, const Workspace &w,
@@ -47,8 +50,28 @@ AssignPlan plan_assign(ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft,
     // D = 32, K = 32: 52 against 85 us for 2^20 points).
     const bool few_centroids = D > 8 && K <= 128;
     const bool want_smalld = g_tuning.assign_variant == 1 || (g_tuning.assign_variant == -1 && !few_centroids);
+    // The mid-D kernel (rows of 33..128 features in registers, centroids in LDS) works in blocks of
+    // 512 points, one workgroup per compute unit: it needs 2^17 points.  Measured against the
+    // generic kernel at 2^17..2^20 points (A/B in one process): 7-18 % faster for D <= 96 from 64
+    // centroids on, 6-7 % for wider rows from 1024 on (at D = 128 its 128 point registers leave the
+    // compiler no room); equal at D = 128, K = 256..512.  With checksums its tiles hold 30
+    // centroids (the generic kernel verifies 128 at a time on the vector units at a third of the
+    // cost), so it is chosen only where its lead is larger than that: D <= 64 from 512 centroids,
+    // D <= 96 from 1024, any width from 4096, and only for rows that fill the compiled width.
+    bool midd_rule = false;
+    if (N >= 131072) {
+        if (ft == FTK_FT_OFF) {
+            midd_rule = (D <= 96 && K >= 64) || K >= 1024;
+        } else {
+            const int width = D <= 48 ? 48 : (D <= 64 ? 64 : (D <= 96 ? 96 : 128));
+            midd_rule = 8 * D >= 7 * width && ((D <= 64 && K >= 512) || (D <= 96 && K >= 1024) || K >= 4096);
+        }
+    }
+    const bool want_midd = g_tuning.assign_variant == 1 || (g_tuning.assign_variant == -1 && midd_rule);
     if (aligned16 && smalld_supported(dtype, D, K) && want_smalld)
         plan_smalld(N, D, K, ft, p);
+    else if (aligned16 && midd_supported(dtype, D, K) && want_midd)
+        plan_midd(N, D, K, ft, p);
     else
         plan_generic(dtype, N, D, K, p);
     return p;
@@ -56,8 +79,9 @@ AssignPlan plan_assign(ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft,
 
 ftk_status launch_assign(const AssignCall &c, const AssignPlan &p, const Workspace &w, hipStream_t st)
 {
-    return p.variant == VAR_SMALLD ? launch_assign_smalld(c, p, w, st)
-                                   : launch_assign_generic(c, p, w, st);
+    if (p.variant == VAR_SMALLD) return launch_assign_smalld(c, p, w, st);
+    if (p.variant == VAR_MIDD) return launch_assign_midd(c, p, w, st);
+    return launch_assign_generic(c, p, w, st);
 }
 
 // Entries of the half-norm vector: every kernel variant pads K up to whole chunks of its own
@@ -72,6 +96,15 @@ size_t hcn_entries_max(ftk_dtype dtype, int64_t N, int D, int K)
             AssignPlan p;
             memset(&p, 0, sizeof(p));
             plan_smalld(N, D, K, ft, p);
+            const size_t e = (size_t)p.nkc * p.KC;
+            if (e > need) need = e;
+        }
+    }
+    if (midd_supported(dtype, D, K)) {
+        for (ftk_ft_mode ft : {FTK_FT_OFF, FTK_FT_CORRECT}) {
+            AssignPlan p;
+            memset(&p, 0, sizeof(p));
+            plan_midd(N, D, K, ft, p);
             const size_t e = (size_t)p.nkc * p.KC;
             if (e > need) need = e;
         }

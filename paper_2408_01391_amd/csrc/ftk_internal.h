@@ -29,7 +29,7 @@ static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // ---- kernel-selection overrides (ftk_tuning_override; -1 = built-in rule) ------------------
 struct Tuning {
-    int assign_variant;  // 0 generic, 1 small-D where it applies
+    int assign_variant;  // 0 generic, 1 register-resident (small-D / mid-D) where it applies
     int kt;              // centroid tiles per chunk of the generic kernel: 1, 2 or 4
     int update_path;     // 0 LDS tables, 1 label-sorted
 };
@@ -41,7 +41,8 @@ extern Tuning g_tuning;
 // accumulators per point tile; a workgroup has 4 waves.
 enum AssignVariant : int {
     VAR_GENERIC = 0,  // any D, any K: K in chunks of KT tiles, D streamed through LDS
-    VAR_SMALLD = 1    // fp32, D <= 32: point fragments stay in registers for the whole sweep
+    VAR_SMALLD = 1,   // fp32, D <= 32: point fragments stay in registers for the whole sweep
+    VAR_MIDD = 2      // fp32, 32 < D <= 128: the same blocking, centroids LDS-resident, scores of the best tile kept
 };
 
 struct AssignPlan {

@@ -172,7 +172,7 @@ ftk_status launch_centroid_prologue(const AssignCall &c, const AssignPlan &p, co
                                (const double *)c.C, (const double *)w.hcn, c.D, p.D8, c.K, p.KC,
                                (double *)w.chk_v1, (double *)w.chk_v2, w.chk_sd);
     }
-    if (c.ft != FTK_FT_OFF && p.variant == VAR_SMALLD) FTK_TRY(launch_smalld_checksums(c, p, w, st));
+    if (c.ft != FTK_FT_OFF && p.variant != VAR_GENERIC) FTK_TRY(launch_smalld_checksums(c, p, w, st));
     FTK_TRY_HIP(hipGetLastError());
     return FTK_OK;
 }

@@ -74,6 +74,42 @@ __device__ __forceinline__ void eval_rows(const floatx4 (&xlo)[NQ], const floatx
     }
 }
 
+constexpr int SMALLD_MAX_FAULTS = 4;  // injected faults honoured per point block
+
+// Sum of the 15 scores of one lane group, added pairwise: partial sums stay small, which roughly
+// halves the rounding noise of a running sum (and the four sub-sums are independent chains).
+__device__ __forceinline__ float sum15(const floatx16 &a)
+{
+    const float p0 = (a[0] + a[1]) + (a[2] + a[3]);
+    const float p1 = (a[4] + a[5]) + (a[6] + a[7]);
+    const float p2 = (a[8] + a[9]) + (a[10] + a[11]);
+    const float p3 = (a[12] + a[13]) + a[14];
+    return (p0 + p1) + (p2 + p3);
+}
+
+// Work-list entries of a workgroup are collected in LDS: one device-wide atomic per wave of
+// entries when they are handed over, instead of one per wave and point tile (tens of thousands of
+// atomics on one word keep a dispatch open long after its last wave).  A wave that finds the
+// buffer full appends to the global list directly.
+constexpr int SMALLD_LIST_CAP = 512;
+__device__ __forceinline__ void block_list_push(bool need, int32_t point, int32_t *sh_list, int *sh_count,
+                                                int32_t *wl, int32_t *wl_count)
+{
+    const unsigned long long m = __ballot(need);
+    if (m == 0ull) return;
+    const int lane = (int)(threadIdx.x & 63);
+    const int leader = __ffsll((long long)m) - 1;
+    const int n = (int)__popcll(m);
+    int base = 0;
+    if (lane == leader) base = atomicAdd(sh_count, n);
+    base = __shfl(base, leader, 64);
+    if (base + n <= SMALLD_LIST_CAP) {
+        if (need) sh_list[base + (int)__popcll(m & ((1ull << lane) - 1ull))] = point;
+    } else {
+        worklist_push(need, point, wl, wl_count);
+    }
+}
+
 // Best tile maximum, the tile it came from, and the runner-up tile maximum of one lane.
 struct TileBest {
     float m1, m2;

@@ -65,6 +65,8 @@ def tune(args):
             cands = {"g1": (0, 1), "g2": (0, 2), "g4": (0, 4)}
             if args.dtype == "f32" and D <= 32 and D % 4 == 0:
                 cands["s"] = (1, -1)
+            if args.dtype == "f32" and 32 < D <= 128 and D % 4 == 0:
+                cands["m"] = (1, -1)
             if args.dtype == "f64":
                 cands["g8"] = (0, 8)  # eight centroid tiles of one point tile (fp64 only)
             times = {}
@@ -99,7 +101,7 @@ def tune(args):
                 {k: round(v, 1) for k, v in tu.items()}, tu_rule), flush=True)
         rows_a.append((D, ca))
         rows_u.append((D, cu))
-    for title, rows in (("Assignment kernel: fastest candidate (s = small-D, gN = generic with N centroid tiles per chunk)", rows_a),
+    for title, rows in (("Assignment kernel: fastest candidate (s = small-D, m = mid-D, gN = generic with N centroid tiles per chunk)", rows_a),
                         ("Update: fastest path (labels of the rule-picked assignment)", rows_u)):
         print()
         print("%s; N = 2^%d, %s, FT %s; in brackets the built-in rule where it is more than 5 %% slower" % (
@@ -147,7 +149,10 @@ def main():
             ms, n = ftk.profile_read()
             t = ms / n * 1e-3
             tf = 2.0 * N * D * K / t / 1e12
-            variant = "s" if (args.dtype == "f32" and D <= 32 and D % 4 == 0) else "g"
+            # the register-resident kernels run eight waves per workgroup, the generic one four
+            code = ftk.F32 if args.dtype == "f32" else ftk.F64
+            resident = ftk.assign_geometry(code, N, D, K, mode).waves_per_workgroup == 8
+            variant = ("s" if D <= 32 else "m") if resident else "g"
             cell = "%s %.0f us %.0f%%" % (variant, t * 1e6, 100.0 * tf / PEAK[args.dtype])
             if variant == "s" and args.ft == "off":  # the split-bf16 fast path covers the same shapes
                 for _ in range(3):
@@ -163,7 +168,7 @@ def main():
                 D, K, variant, t * 1e6, tf, 100.0 * tf / PEAK[args.dtype], PEAK[args.dtype]), flush=True)
         rows.append((D, cells))
     print()
-    print("N = 2^%d, %s, FT %s; cell: variant (s = small-D, g = generic), kernel time, %% of the MFMA peak"
+    print("N = 2^%d, %s, FT %s; cell: variant (s = small-D, m = mid-D, g = generic), kernel time, %% of the MFMA peak"
           " (in brackets: kernels of the split-bf16 fast path on the same shape)" % (args.logn, args.dtype, args.ft))
     print("| D \\\\ K | " + " | ".join(str(k) for k in args.grid_k) + " |")
     print("|---|" + "---|" * len(args.grid_k))
