@@ -908,11 +908,17 @@ static UpdateLaunch plan_update_launch(ftk_dtype dtype, const void *X, int64_t N
     L.u = plan_update(dtype, X, N, D, K);
     const size_t esz = dtype == FTK_F32 ? 4 : 8;
     // Rows of at least half a cache line gather efficiently, and the label-sorted path streams
-    // them at nearly the HBM rate - but it is six kernels with a fixed cost of about 45 us.
-    // The two-kernel LDS path is taken for short rows, for small problems, and wherever the
-    // table is at most four 64 KB slices and X below 256 MB (measured crossover: it reads every
-    // row once per slice-wide piece and pays LDS atomics per element, which the sorted path does not).
-    const bool small_table = (int64_t)K * D <= 4 * UPD_CELLS && (double)N * D * esz < 268435456.0;
+    // them at nearly the HBM rate - but it is six kernels with a fixed cost of about 45 us, and the
+    // two-kernel LDS path reads X exactly once as long as one slice holds every cluster (K <= 256:
+    // the slices then split the features only).  Measured crossovers (both paths forced, N = 2^17
+    // .. 2^20, fp32 and fp64): with all clusters resident the LDS path wins up to about 0.75 GB of
+    // X (e.g. 2^20 x 128, K = 256: 128 against 159 us; 2^17 x 1024, K = 128: 141 against 180 us)
+    // and loses beyond (LDS atomics per element against a streaming reduction: 2^20 x 256: 253
+    // against 224 us); with the clusters split over several slices it re-reads X once per slice
+    // and wins only for small tables on data that stay in the memory-side cache.
+    const double x_bytes = (double)N * D * esz;
+    const bool small_table = (L.u.nks == 1 && x_bytes < 805306368.0) ||
+                             ((int64_t)K * D <= 4 * UPD_CELLS && x_bytes < 268435456.0);
     L.sorted_path = (size_t)D * esz >= 64 && N >= 65536 && !small_table;
     if (g_tuning.update_path >= 0) L.sorted_path = g_tuning.update_path == 1;
     L.E = L.u.aligned ? (dtype == FTK_F32 ? 4 : 2) : 1;
