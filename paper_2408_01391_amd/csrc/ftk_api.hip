@@ -600,8 +600,8 @@ ftk_status ftk_kmeans_step_batched(ftk_dtype dtype, const void *X, int64_t N, in
     FTK_TRY(launch_zero_ints(w.batch_counters, (int)(4 * nbatch), st));
     // norms of the centroids once: they do not change inside the iteration
     AssignCall whole{dtype, X, C, batch_rows < N ? batch_rows : N, D, K, labels, mindist, FTK_FT_OFF, nullptr, 0, nullptr};
-    const AssignPlan p0 = plan_assign(dtype, whole.N, D, K, FTK_FT_OFF, aligned16);
-    FTK_TRY(launch_centroid_prologue(whole, p0, w, st));
+    AssignPlan pprev = plan_assign(dtype, whole.N, D, K, FTK_FT_OFF, aligned16);
+    FTK_TRY(launch_centroid_prologue(whole, pprev, w, st));
     for (int64_t b = 0; b < nbatch; ++b) {
         const int64_t r0 = b * batch_rows;
         const int64_t nb = N - r0 < batch_rows ? N - r0 : batch_rows;
@@ -609,9 +609,10 @@ ftk_status ftk_kmeans_step_batched(ftk_dtype dtype, const void *X, int64_t N, in
         AssignCall c{dtype, Xb, C, nb, D, K, labels + r0, mindist ? (void *)((char *)mindist + (size_t)r0 * esz) : nullptr,
                      FTK_FT_OFF, nullptr, 0, nullptr};
         AssignPlan p = plan_assign(dtype, nb, D, K, FTK_FT_OFF, aligned16);
-        if (p.variant != p0.variant || p.nkc * p.KC != p0.nkc * p0.KC) {
-            set_error("internal: the last batch plans a different kernel layout than the first");
-            return FTK_EINVAL;
+        if (p.variant != pprev.variant || p.nkc * p.KC != pprev.nkc * pprev.KC || p.hcn_pad_inf != pprev.hcn_pad_inf) {
+            // a shorter last batch may be planned for another kernel, whose padded norm vector differs
+            FTK_TRY(launch_centroid_prologue(c, p, w, st));
+            pprev = p;
         }
         Workspace wb = w;
         wb.wl_count = w.batch_counters + 4 * b;  // fresh work-list counters per batch

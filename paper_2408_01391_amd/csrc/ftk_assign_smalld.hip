@@ -135,23 +135,42 @@ __global__ __launch_bounds__(smalld_waves(NQ, FT) * 64, smalld_min_wgs(NQ, FT)) 
     };
 
     // stage tiles [ch*tpc, (ch+1)*tpc) into LDS: centroid rows (and checksum rows) plus the
-    // accumulator start values
+    // accumulator start values.  A thread keeps its 16-byte piece of the row and walks the rows
+    // with a fixed stride; the loads are branch-free (clamped addresses, zeros selected
+    // afterwards) and issued up to eight at a time: a chunk costs a few memory round trips, not
+    // one per row, which matters where the chunks change inside the sweep (K * D beyond the LDS).
     auto stage_chunk = [&](int ch) {
-        constexpr int PPR = 2 * NQ;  // 16-byte pieces per row
+        constexpr int PPR = 2 * NQ;                    // 16-byte pieces per row
+        constexpr int RSTEP = SMALLD_THREADS / PPR;    // rows per pass of the workgroup (left-over threads idle)
+        constexpr int SU = NQ == 1 ? 4 : 8;            // loads in flight (the 128-register variant has room for four)
         const int rows = a.tpc * 32;
-        for (int idx = tid; idx < rows * PPR; idx += SMALLD_THREADS) {
-            const int rrow = idx / PPR, pc = idx % PPR;
-            const int tl = rrow >> 5, lr = rrow & 31;
-            const int T = ch * a.tpc + tl;
-            const int gg = (lr >> 2) & 1, r = (lr >> 3) * 4 + (lr & 3);
-            floatx4 f = {0.f, 0.f, 0.f, 0.f};
-            if (!FT || r < RG) {
-                const int j = G::centroid(T, gg, r);
-                if (j < a.K) f = load_frag<float, true>(a.C + (size_t)j * D, 4 * pc, D);
-            } else if (T < a.tiles_total) {
-                f = *reinterpret_cast<const floatx4 *>(a.chk_v1 + (size_t)(T * 2 + gg) * D8 + 4 * pc);
+        const int st_pc = tid % PPR, st_r0 = tid / PPR;
+        if (st_r0 < RSTEP) {
+            for (int rb = st_r0; rb < rows; rb += SU * RSTEP) {
+                floatx4 f[SU];
+#pragma unroll
+                for (int u = 0; u < SU; ++u) {
+                    const int rrow = min(rb + u * RSTEP, rows - 1);
+                    const int tl = rrow >> 5, lr = rrow & 31;
+                    const int T = ch * a.tpc + tl;
+                    const int gg = (lr >> 2) & 1, r = (lr >> 3) * 4 + (lr & 3);
+                    const bool chk = FT && r >= RG;  // a checksum row (D8 wide), else a centroid row (D wide)
+                    const int j = G::centroid(T, gg, r);
+                    const int width = chk ? D8 : D;
+                    const bool keep = (chk ? T < a.tiles_total : j < a.K) && 4 * st_pc < width;
+                    const float *src = chk ? a.chk_v1 + (size_t)(min(T, a.tiles_total - 1) * 2 + gg) * D8
+                                           : a.C + (size_t)min(j, a.K - 1) * D;
+                    const floatx4 v = *reinterpret_cast<const floatx4 *>(src + min(4 * st_pc, width - 4));
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) f[u][e] = keep ? v[e] : 0.f;
+                }
+#pragma unroll
+                for (int u = 0; u < SU; ++u) {
+                    const int rrow = rb + u * RSTEP;
+                    if (rrow < rows)
+                        *reinterpret_cast<floatx4 *>(ldsC + (size_t)(rrow >> 5) * TS + (rrow & 31) * SW + 4 * st_pc) = f[u];
+                }
             }
-            *reinterpret_cast<floatx4 *>(ldsC + (size_t)tl * TS + lr * SW + 4 * pc) = f;
         }
         for (int idx = tid; idx < rows; idx += SMALLD_THREADS) {
             const int tl = idx >> 5, gg = (idx >> 4) & 1, r = idx & 15;

@@ -57,3 +57,21 @@ def test_batched_step_keeps_empty_clusters_and_rejects_bad_batch_sizes():
         ftk.kmeans_step_batched(Xd, Cd, 0)
     with pytest.raises(ftk.FtkError):
         ftk.kmeans_step_batched(to_dev(np.zeros((10000, 4), np.float32)), to_dev(np.zeros((2, 4), np.float32)), 2)
+
+
+def test_batched_step_whose_last_batch_is_planned_for_another_kernel():
+    """A first batch of 2^17 rows and more goes to the mid-D kernel, the shorter last batch to the
+    generic one, whose padded norm vector differs: the norms are then written again for it."""
+    N, D, K, batch = 200_000, 64, 128, 140_000
+    first = ftk.assign_geometry(ftk.F32, batch, D, K, ftk.FT_OFF)
+    last = ftk.assign_geometry(ftk.F32, N - batch, D, K, ftk.FT_OFF)
+    assert first.waves_per_workgroup != last.waves_per_workgroup, "the two batches no longer plan different kernels"
+    X, C = synth.random_problem(17, N, D, K, "f32", spread=5.0)
+    Xd, C_b = to_dev(X), to_dev(C).clone()
+    labels, mind, counts = ftk.kmeans_step_batched(Xd, C_b, batch)
+    torch.cuda.synchronize()
+    lab = labels.cpu().numpy()
+    check_assign(X, C, lab, mind.cpu().numpy())
+    C_o, counts_o = oracle.update(X, lab, C)
+    assert np.array_equal(counts.cpu().numpy(), counts_o)
+    check_centroids(C_b.cpu().numpy(), C_o)

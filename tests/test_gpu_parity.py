@@ -205,3 +205,27 @@ def test_error_paths_return_codes_without_touching_the_gpu_state():
     labels, _ = ftk.kmeans_assign(X, C)             # still usable afterwards
     torch.cuda.synchronize()
     assert labels.cpu().tolist() == [0] * 16
+
+
+@pytest.mark.parametrize("N,D,K", [(600_000, 8, 64), (300_000, 64, 64)])
+def test_every_point_ambiguous_overflows_the_workgroup_lists_and_is_still_exact(N, D, K):
+    """Centroids that differ by a few units in the last place: every score lies inside the rounding
+    bound of every other, so every point needs the exact recomputation.  The register-resident
+    kernels collect such points in a list of 512 entries per workgroup before handing them over;
+    a workgroup here sees more than a thousand of them, so most go to the device-wide list
+    directly.  Labels as the oracle's, and the same with checksums on (other tile layout, for the
+    wider rows another kernel)."""
+    rng = np.random.default_rng(N + D)
+    X = rng.normal(size=(N, D)).astype(np.float32)
+    base = rng.normal(size=(1, D)).astype(np.float32)
+    C = (base * (1.0 + 2.0e-7 * rng.integers(-3, 4, size=(K, D)))).astype(np.float32)
+    C[K - 1] = C[5]  # and an exact duplicate: lowest index wins
+    stats = ftk.new_stats(torch.device("cuda:0"))
+    labels, mind = gpu_assign(X, C, stats=stats)
+    st = ftk.stats_dict(stats)
+    assert st["refined"] > 0.9 * N, st
+    check_assign(X, C, labels, mind)
+    assert not np.any(labels == K - 1)
+    labels_ft, mind_ft = gpu_assign(X, C, ft_mode=ftk.FT_CORRECT)
+    assert np.array_equal(labels, labels_ft)
+    assert np.array_equal(mind, mind_ft)
