@@ -203,34 +203,46 @@ def injection_leg(torch, ftk, np, s, rate, step_s, seconds, warmup):
 
 def fast_mode_times(torch, ftk, s, steps, warmup, repeats, sec_per_step_fp32):
     """Lloyd steps with the assignment on the split-bf16 matrix path (the counterpart of the paper's
-    TF32 variant): reported next to the headline, never as the headline."""
-    def run(n, C):
+    TF32 variant), without and with its checksums (strict mode, DMR update): reported next to the
+    headline, never as the headline."""
+    def run(n, C, mode):
         for _ in range(n):
-            ftk.kmeans_assign_fast(s.Xd, C, labels=s.labels, mindist=s.mind, workspace=s.ws)
-            ftk.kmeans_update(s.Xd, s.labels, C, counts=s.counts, x_absmax=s.absmax, workspace=s.ws)
+            ftk.kmeans_assign_fast(s.Xd, C, labels=s.labels, mindist=s.mind, workspace=s.ws, ft_mode=mode)
+            ftk.kmeans_update(s.Xd, s.labels, C, counts=s.counts, x_absmax=s.absmax, workspace=s.ws, ft_mode=mode)
 
-    C = s.C0d.clone()
-    run(warmup, C)
-    times = []
-    for _ in range(repeats):
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        run(steps, C)
-        torch.cuda.synchronize()
-        times.append((time.perf_counter() - t0) / steps)
-    sec = statistics.median(times)
+    def step_seconds(mode):
+        C = s.C0d.clone()
+        run(warmup, C, mode)
+        times = []
+        for _ in range(repeats):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            run(steps, C, mode)
+            torch.cuda.synchronize()
+            times.append((time.perf_counter() - t0) / steps)
+        return statistics.median(times), C
+
+    sec, C = step_seconds(ftk.FT_OFF)
     ftk.profile_enable(True)
-    run(5, C)
+    run(5, C, ftk.FT_OFF)
     ftk.profile_enable(False)
     ms, launches = ftk.profile_read()
+    sec_strict, _ = step_seconds(ftk.FT_STRICT)
     ref, _ = ftk.kmeans_assign(s.Xd, s.C0d, workspace=s.ws)
     fast, _ = ftk.kmeans_assign_fast(s.Xd, s.C0d, workspace=s.ws)
+    stats = ftk.new_stats(s.Xd.device)
+    fast_ft, _ = ftk.kmeans_assign_fast(s.Xd, s.C0d, workspace=s.ws, ft_mode=ftk.FT_STRICT, stats=stats)
+    torch.cuda.synchronize()
     w = s.w
     kern_ms = ms / max(launches, 1)
     return {"iters_per_s": 1.0 / sec, "ms_per_step": 1e3 * sec, "speedup_vs_fp32_step": sec_per_step_fp32 / sec,
             "assign_kernels_ms": kern_ms, "dtype": "bf16x3 split of f32, f32 accumulate",
             "fp32_equivalent_tflops": 2.0 * w.N * w.D * w.K / (kern_ms * 1e-3) / 1e12,
-            "labels_differing_from_fp32_path": int((ref != fast).sum().item())}
+            "labels_differing_from_fp32_path": int((ref != fast).sum().item()),
+            "ft_strict": {"iters_per_s": 1.0 / sec_strict, "overhead_step": sec_strict / sec - 1.0,
+                          "speedup_vs_fp32_step_ft_off": sec_per_step_fp32 / sec_strict,
+                          "labels_differing_from_fp32_path": int((ref != fast_ft).sum().item()),
+                          "stats": ftk.stats_dict(stats)}}
 
 
 def ablation_times(ftk, torch, s, esz):

@@ -173,11 +173,25 @@ ftk_status ftk_kmeans_assign_static(ftk_dtype dtype, const void *X, const void *
  * meet the same tolerance (identical to the exact arg-min except on near-exact ties) and
  * mindist is the exact-form distance to the chosen centroid.
  * Covers dtype == FTK_F32 with D <= 32 and D a multiple of 4, X and C 16-byte aligned; anything
- * else returns FTK_EINVAL / FTK_EALIGN.  No checksums and no fault injection on this path.
- * workspace: ftk_workspace_bytes(dtype, N, D, K, FTK_FT_OFF) bytes. */
+ * else returns FTK_EINVAL / FTK_EALIGN.
+ * ft, faults, stats as for ftk_kmeans_assign: the paper protects its tensor-core variant with the
+ * same checksums as the fp32 one (Sections 3.1.5 and 4), and so does this path - tiles of 30
+ * centroids whose two checksum rows are split into bf16 pieces like any centroid row and go
+ * through the same matrix instructions as the scores they must equal; detection, location,
+ * correction, strict mode, the detection threshold (ftk_fast_plan reports it) and the injection
+ * hook are those of the fp32 kernel for D <= 32.
+ * workspace: ftk_workspace_bytes(dtype, N, D, K, ft) bytes. */
 ftk_status ftk_kmeans_assign_fast(ftk_dtype dtype, const void *X, const void *C, int64_t N, int32_t D,
                                   int32_t K, int32_t *labels, void *mindist /* nullable */,
-                                  void *workspace, size_t workspace_bytes, void *hip_stream);
+                                  ftk_ft_mode ft, const ftk_fault *faults /* nullable */, int32_t n_faults,
+                                  ftk_ft_stats *stats /* nullable */, void *workspace, size_t workspace_bytes,
+                                  void *hip_stream);
+
+/* (host) What ftk_assign_geometry and ftk_ft_thresholds report, for the reduced-precision path:
+ * the extents fault descriptors are taken modulo, the detection threshold and the settlement band
+ * (both as multiples of B_i, see ftk_ft_thresholds).  Any output may be NULL. */
+ftk_status ftk_fast_plan(ftk_dtype dtype, int64_t N, int32_t D, int32_t K, ftk_ft_mode ft,
+                         ftk_geometry *geometry, double *detect_coef, double *band_coef);
 
 /* Largest finite |x| over `count` elements, written as one double to out_absmax (device); NaN and
  * Inf elements are skipped.  ftk_kmeans_update needs it to fix the scale of its
@@ -271,15 +285,16 @@ ftk_status ftk_kmeans_fit(ftk_dtype dtype, const void *X, int64_t N, int32_t D, 
                           ftk_ft_mode ft, ftk_ft_stats *stats, void *workspace,
                           size_t workspace_bytes, void *hip_stream);
 
-/* The same loop with the assignment on the split-bf16 matrix path (ftk_kmeans_assign_fast) and
- * the plain update: fp32 data with D <= 32, D a multiple of 4, X 16-byte aligned; no fault
- * tolerance on this path.  Arguments as for ftk_kmeans_fit; workspace of
- * ftk_workspace_bytes(dtype, N, D, K, FTK_FT_OFF) bytes. */
+/* The same loop with the assignment on the split-bf16 matrix path (ftk_kmeans_assign_fast):
+ * fp32 data with D <= 32, D a multiple of 4, X 16-byte aligned.  Arguments as for
+ * ftk_kmeans_fit, fault-tolerance mode (checksummed assignment, DMR update) and counters
+ * included; workspace of ftk_workspace_bytes(dtype, N, D, K, ft) bytes. */
 ftk_status ftk_kmeans_fit_fast(ftk_dtype dtype, const void *X, int64_t N, int32_t D, int32_t K,
                                int32_t iters, uint64_t seed, const void *C_init /* nullable */,
                                void *C_out, int32_t *labels_out, int32_t *counts_out,
-                               double *inertia_per_iter /* (host) nullable */, void *workspace,
-                               size_t workspace_bytes, void *hip_stream);
+                               double *inertia_per_iter /* (host) nullable */, ftk_ft_mode ft,
+                               ftk_ft_stats *stats /* nullable */, void *workspace, size_t workspace_bytes,
+                               void *hip_stream);
 
 /* (host) K distinct indices in [0, N) by the seeded procedure ftk_kmeans_fit uses. */
 ftk_status ftk_seeded_indices(uint64_t seed, int64_t N, int32_t K, int64_t *idx_host);

@@ -58,8 +58,10 @@ def load():
     L.ftk_kmeans_assign_static.restype = i32
     L.ftk_static_scratch_bytes.argtypes = []
     L.ftk_static_scratch_bytes.restype = sz
-    L.ftk_kmeans_assign_fast.argtypes = [i32, vp, vp, i64, i32, i32, vp, vp, vp, sz, vp]
+    L.ftk_kmeans_assign_fast.argtypes = [i32, vp, vp, i64, i32, i32, vp, vp, i32, vp, i32, vp, vp, sz, vp]
     L.ftk_kmeans_assign_fast.restype = i32
+    L.ftk_fast_plan.argtypes = [i32, i64, i32, i32, i32, vp, vp, vp]
+    L.ftk_fast_plan.restype = i32
     L.ftk_absmax.argtypes = [i32, vp, i64, vp, vp]
     L.ftk_absmax.restype = i32
     L.ftk_kmeans_update.argtypes = [i32, vp, vp, i64, i32, i32, vp, vp, vp, vp, sz, vp]
@@ -72,7 +74,7 @@ def load():
     L.ftk_update_geometry.restype = i32
     L.ftk_kmeans_fit.argtypes = [i32, vp, i64, i32, i32, i32, u64, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
     L.ftk_kmeans_fit.restype = i32
-    L.ftk_kmeans_fit_fast.argtypes = [i32, vp, i64, i32, i32, i32, u64, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.ftk_kmeans_fit_fast.argtypes = [i32, vp, i64, i32, i32, i32, u64, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
     L.ftk_kmeans_fit_fast.restype = i32
     L.ftk_seeded_indices.argtypes = [u64, i64, i32, vp]
     L.ftk_seeded_indices.restype = i32
@@ -88,7 +90,7 @@ def load():
     return L
 
 
-EXPORTS = ("ftk_workspace_bytes", "ftk_assign_geometry", "ftk_plan_padded_rows", "ftk_ft_thresholds", "ftk_kmeans_assign_static", "ftk_static_scratch_bytes", "ftk_kmeans_assign", "ftk_kmeans_assign_fast", "ftk_absmax",
+EXPORTS = ("ftk_workspace_bytes", "ftk_assign_geometry", "ftk_plan_padded_rows", "ftk_ft_thresholds", "ftk_kmeans_assign_static", "ftk_static_scratch_bytes", "ftk_kmeans_assign", "ftk_kmeans_assign_fast", "ftk_fast_plan", "ftk_absmax",
            "ftk_kmeans_update", "ftk_kmeans_update_ft", "ftk_kmeans_step_batched", "ftk_update_geometry", "ftk_kmeans_fit", "ftk_kmeans_fit_fast", "ftk_seeded_indices", "ftk_profile_enable",
            "ftk_profile_read", "ftk_tuning_override", "ftk_last_error", "ftk_version")
 
@@ -216,7 +218,17 @@ def kmeans_assign_static(X, C, labels, mindist=None, ft_mode=FT_OFF, faults=None
     return labels, mindist
 
 
-def kmeans_assign_fast(X, C, labels=None, mindist=None, workspace=None, want_mindist=True):
+def fast_plan(dtype_code: int, N: int, D: int, K: int, ft_mode: int = FT_OFF):
+    """(geometry, detect_coef, band_coef) of the split-bf16 path: what assign_geometry and
+    ft_thresholds report for the fp32 path."""
+    g = Geometry()
+    a, b = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    _check(load().ftk_fast_plan(dtype_code, N, D, K, ft_mode, ctypes.byref(g), ctypes.byref(a), ctypes.byref(b)))
+    return g, a.value, b.value
+
+
+def kmeans_assign_fast(X, C, labels=None, mindist=None, workspace=None, want_mindist=True, ft_mode=FT_OFF,
+                       faults=None, stats=None):
     """Assignment step on the split-bf16 matrix path (fp32 data, D <= 32).  Returns (labels, mindist)."""
     _dev2d(X, "X"), _dev2d(C, "C")
     if X.dtype != C.dtype or X.shape[1] != C.shape[1]:
@@ -228,10 +240,12 @@ def kmeans_assign_fast(X, C, labels=None, mindist=None, workspace=None, want_min
     if mindist is None and want_mindist:
         mindist = torch.empty(N, dtype=X.dtype, device=X.device)
     if workspace is None:
-        workspace = new_workspace(X, K, FT_OFF)
+        workspace = new_workspace(X, K, ft_mode)
     wp, wn = _ws_args(workspace)
+    nf = 0 if faults is None else faults.shape[0]
     _check(load().ftk_kmeans_assign_fast(_dtype_code(X), X.data_ptr(), C.data_ptr(), N, D, K,
-                                         labels.data_ptr(), _ptr(mindist), wp, wn, _stream()))
+                                         labels.data_ptr(), _ptr(mindist), ft_mode, _ptr(faults), nf,
+                                         _ptr(stats), wp, wn, _stream()))
     return labels, mindist
 
 
@@ -321,7 +335,7 @@ def profile_read():
 def kmeans_fit(X, K, iters, seed=0, C_init=None, ft_mode=FT_OFF, stats=None, workspace=None,
                want_inertia=True, fast=False):
     """Lloyd loop.  Returns dict(C, labels, counts, inertia (numpy, host) or None).
-    fast=True runs the assignment on the split-bf16 matrix path (fp32, D <= 32, FT off)."""
+    fast=True runs the assignment on the split-bf16 matrix path (fp32, D <= 32)."""
     import numpy as np
     _dev2d(X, "X")
     N, D = X.shape
@@ -337,11 +351,10 @@ def kmeans_fit(X, K, iters, seed=0, C_init=None, ft_mode=FT_OFF, stats=None, wor
         workspace = new_workspace(X, K, ft_mode)
     wp, wn = _ws_args(workspace)
     if fast:
-        if ft_mode != FT_OFF or stats is not None:
-            raise ValueError("the fast path carries no fault tolerance")
         _check(load().ftk_kmeans_fit_fast(_dtype_code(X), X.data_ptr(), N, D, K, iters, seed & (2**64 - 1),
                                           _ptr(C_init), C.data_ptr(), labels.data_ptr(), counts.data_ptr(),
-                                          None if inertia is None else inertia.ctypes.data, wp, wn, _stream()))
+                                          None if inertia is None else inertia.ctypes.data, ft_mode,
+                                          _ptr(stats), wp, wn, _stream()))
         return dict(C=C, labels=labels, counts=counts, inertia=inertia)
     _check(load().ftk_kmeans_fit(_dtype_code(X), X.data_ptr(), N, D, K, iters, seed & (2**64 - 1),
                                  _ptr(C_init), C.data_ptr(), labels.data_ptr(), counts.data_ptr(),

@@ -110,7 +110,7 @@ size_t hcn_entries_max(ftk_dtype dtype, int64_t N, int D, int K)
         }
     }
     if (fast_supported(dtype, D)) {
-        const size_t e = (size_t)ceil_div(K, 32) * 32;
+        const size_t e = (size_t)ceil_div(K, 30) * 32;  // tiles of 30 centroids with checksums
         if (e > need) need = e;
     }
     return (size_t)ceil_div((int64_t)need, 512) * 512 + 512;
@@ -256,7 +256,7 @@ static ftk_status assign_impl(const AssignCall &c, void *workspace, hipStream_t 
     AssignPlan p;
     if (fast) {
         memset(&p, 0, sizeof(p));
-        plan_fast_prologue(c.D, c.K, p);
+        plan_fast(c.N, c.D, c.K, c.ft, p);
     } else {
         p = plan_assign(c.dtype, c.N, c.D, c.K, c.ft, aligned16);
     }
@@ -275,7 +275,7 @@ static ftk_status assign_impl(const AssignCall &c, void *workspace, hipStream_t 
         FTK_TRY_HIP(hipEventRecord(e0, st));
     }
     if (fast)
-        FTK_TRY(launch_assign_fast(c, w, st));
+        FTK_TRY(launch_assign_fast(c, p, w, st));
     else
         FTK_TRY(launch_assign(c, p, w, st));
     if (profile) {
@@ -430,11 +430,13 @@ ftk_status ftk_plan_padded_rows(ftk_dtype dtype, int64_t N, int32_t D, int32_t K
             }
     g_tuning = saved;
     if (fast_supported(dtype, D)) {
-        AssignPlan p;
-        memset(&p, 0, sizeof(p));
-        plan_fast_prologue(D, K, p);
-        const int64_t rows = (int64_t)p.nkc * p.KC;
-        if (rows > worst) worst = rows;
+        for (ftk_ft_mode ft : {FTK_FT_OFF, FTK_FT_CORRECT}) {
+            AssignPlan p;
+            memset(&p, 0, sizeof(p));
+            plan_fast(N, D, K, ft, p);
+            const int64_t rows = (int64_t)p.nkc * p.KC;
+            if (rows > worst) worst = rows;
+        }
     }
     *planned_max = worst;
     *reserved = (int64_t)hcn_entries_max(dtype, N, D, K);
@@ -495,24 +497,57 @@ ftk_status ftk_kmeans_assign_static(ftk_dtype dtype, const void *X, const void *
     return assign_impl(c, scratch, (hipStream_t)hip_stream, false, false);
 }
 
-ftk_status ftk_kmeans_assign_fast(ftk_dtype dtype, const void *X, const void *C, int64_t N, int32_t D,
-                                  int32_t K, int32_t *labels, void *mindist, void *workspace,
-                                  size_t workspace_bytes, void *hip_stream)
+static ftk_status check_fast(ftk_dtype dtype, int D)
 {
-    FTK_TRY(check_problem(dtype, N, D, K, FTK_FT_OFF));
     if (!fast_supported(dtype, D)) {
         set_error("the fast assignment covers fp32 data with D <= 32 and D a multiple of 4 (got dtype=%d D=%d)",
                   (int)dtype, D);
         return FTK_EINVAL;
     }
+    return FTK_OK;
+}
+
+ftk_status ftk_kmeans_assign_fast(ftk_dtype dtype, const void *X, const void *C, int64_t N, int32_t D,
+                                  int32_t K, int32_t *labels, void *mindist, ftk_ft_mode ft,
+                                  const ftk_fault *faults, int32_t n_faults, ftk_ft_stats *stats,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    FTK_TRY(check_problem(dtype, N, D, K, ft));
+    FTK_TRY(check_fast(dtype, D));
     FTK_TRY(check_ptr(X, 16, "X"));
     FTK_TRY(check_ptr(C, 16, "C"));
     FTK_TRY(check_ptr(labels, 4, "labels"));
     if (mindist) FTK_TRY(check_ptr(mindist, 4, "mindist"));
-    FTK_TRY(check_workspace(workspace, workspace_bytes, ftk_workspace_bytes(dtype, N, D, K, FTK_FT_OFF)));
+    if (stats) FTK_TRY(check_ptr(stats, 8, "stats"));
+    if (n_faults < 0 || (n_faults > 0 && !faults)) {
+        set_error("n_faults=%d with faults=%p", n_faults, (const void *)faults);
+        return FTK_EINVAL;
+    }
+    FTK_TRY(check_workspace(workspace, workspace_bytes, ftk_workspace_bytes(dtype, N, D, K, ft)));
     FTK_TRY(check_device());
-    AssignCall c{dtype, X, C, N, D, K, labels, mindist, FTK_FT_OFF, nullptr, 0, nullptr};
+    AssignCall c{dtype, X, C, N, D, K, labels, mindist, ft, faults, n_faults, stats};
     return assign_impl(c, workspace, (hipStream_t)hip_stream, true);
+}
+
+ftk_status ftk_fast_plan(ftk_dtype dtype, int64_t N, int32_t D, int32_t K, ftk_ft_mode ft, ftk_geometry *geometry,
+                         double *detect_coef, double *band_coef)
+{
+    FTK_TRY(check_problem(dtype, N, D, K, ft));
+    FTK_TRY(check_fast(dtype, D));
+    AssignPlan p;
+    memset(&p, 0, sizeof(p));
+    plan_fast(N, D, K, ft, p);
+    if (geometry) {
+        geometry->workgroups = (uint32_t)p.workgroups;
+        geometry->waves_per_workgroup = (uint32_t)p.waves;
+        geometry->tiles_per_wave = (uint32_t)p.tiles_per_wave;
+        geometry->regs_per_tile = (uint32_t)p.regs_per_tile;
+        geometry->lanes = 64;
+        geometry->bits = 32;
+    }
+    if (detect_coef) *detect_coef = ft == FTK_FT_OFF ? 0.0 : p.ft_coef;
+    if (band_coef) *band_coef = p.band_coef;
+    return FTK_OK;
 }
 
 ftk_status ftk_absmax(ftk_dtype dtype, const void *X, int64_t count, double *out_absmax, void *hip_stream)
@@ -669,11 +704,7 @@ static ftk_status fit_impl(ftk_dtype dtype, const void *X, int64_t N, int32_t D,
 {
     FTK_TRY(check_problem(dtype, N, D, K, ft));
     if (fast) {
-        if (!fast_supported(dtype, D)) {
-            set_error("the fast assignment covers fp32 data with D <= 32 and D a multiple of 4 (got dtype=%d D=%d)",
-                      (int)dtype, D);
-            return FTK_EINVAL;
-        }
+        FTK_TRY(check_fast(dtype, D));
         FTK_TRY(check_ptr(X, 16, "X"));
     }
     if (iters < 0 || iters > FIT_MAX_ITERS_IN_WS) {
@@ -736,10 +767,11 @@ ftk_status ftk_kmeans_fit(ftk_dtype dtype, const void *X, int64_t N, int32_t D, 
 ftk_status ftk_kmeans_fit_fast(ftk_dtype dtype, const void *X, int64_t N, int32_t D, int32_t K,
                                int32_t iters, uint64_t seed, const void *C_init, void *C_out,
                                int32_t *labels_out, int32_t *counts_out, double *inertia_per_iter,
-                               void *workspace, size_t workspace_bytes, void *hip_stream)
+                               ftk_ft_mode ft, ftk_ft_stats *stats, void *workspace, size_t workspace_bytes,
+                               void *hip_stream)
 {
-    return fit_impl(dtype, X, N, D, K, iters, seed, C_init, C_out, labels_out, counts_out, inertia_per_iter,
-                    FTK_FT_OFF, nullptr, workspace, workspace_bytes, hip_stream, true);
+    return fit_impl(dtype, X, N, D, K, iters, seed, C_init, C_out, labels_out, counts_out, inertia_per_iter, ft,
+                    stats, workspace, workspace_bytes, hip_stream, true);
 }
 
 }  // extern "C"

@@ -132,8 +132,8 @@ ftk_status launch_assign(const AssignCall &c, const AssignPlan &p, const Workspa
 ftk_status launch_refine(const AssignCall &c, const Workspace &w, int n_wg, hipStream_t st);
 bool fast_supported(ftk_dtype dtype, int D);
 size_t fast_split_bytes(ftk_dtype dtype, int D, int K);
-void plan_fast_prologue(int D, int K, AssignPlan &p);
-ftk_status launch_assign_fast(const AssignCall &c, const Workspace &w, hipStream_t st);
+void plan_fast(int64_t N, int D, int K, ftk_ft_mode ft, AssignPlan &p);
+ftk_status launch_assign_fast(const AssignCall &c, const AssignPlan &p, const Workspace &w, hipStream_t st);
 
 ftk_status launch_absmax(ftk_dtype dtype, const void *X, int64_t count, double *out, hipStream_t st);
 ftk_status launch_update(ftk_dtype dtype, const void *X, const int32_t *labels, int64_t N, int D,

@@ -66,13 +66,14 @@ def check_assign(X: np.ndarray, C: np.ndarray, labels_g: np.ndarray, mindist_g=N
     return int(diff.size), int(idx.size)
 
 
-def check_moved_labels_within_detection_threshold(X, C, lab, lab_clean, ft_mode):
+def check_moved_labels_within_detection_threshold(X, C, lab, lab_clean, ft_mode, coefs=None):
     """Labels under injected faults against the fault-free labels of the same mode.
 
     STRICT: identical.  CORRECT (the paper's scheme): an error below the detection threshold of
     Section 2.3 passes unnoticed and may move the point whose score it hit, but only to a centroid
     whose exact squared distance exceeds the oracle's best by less than twice (scores are half
-    distances) the threshold plus the settlement band of THAT point, as the library reports them.
+    distances) the threshold plus the settlement band of THAT point, as the library reports them
+    (``coefs`` = (detect_coef, band_coef) for a path other than the one ftk_ft_thresholds describes).
     Returns the number of moved labels."""
     diff = np.flatnonzero(lab != lab_clean)
     if ft_mode == ftk.FT_STRICT:
@@ -81,7 +82,7 @@ def check_moved_labels_within_detection_threshold(X, C, lab, lab_clean, ft_mode)
     if diff.size == 0:
         return 0
     code = ftk.F32 if X.dtype == np.float32 else ftk.F64
-    detect, band = ftk.ft_thresholds(code, X.shape[0], X.shape[1], C.shape[0], ft_mode)
+    detect, band = coefs if coefs is not None else ftk.ft_thresholds(code, X.shape[0], X.shape[1], C.shape[0], ft_mode)
     _, d1, _ = oracle.assign(X, C, diff)
     d_new = exact_dist_to(X, C, diff, lab[diff])
     cmax2 = (C.astype(np.float64) ** 2).sum(1).max()
