@@ -94,9 +94,14 @@ struct GenericCfg {
 template <typename T>
 constexpr int generic_kt(int K) { return K <= Mma<T>::TM ? 1 : (K <= 2 * Mma<T>::TM ? 2 : 4); }
 
-template <typename T, int KTV, bool ALIGNED, bool FT>
+// FULL: every stage holds real features only (D a multiple of the stage width) and every chunk
+// real centroids only (K a multiple of the chunk) - the stage loop is then compiled without its
+// per-quad, per-tile and per-element conditions: one straight run of matrix instructions per stage
+// instead of a branch every KT of them, and no masking selects on the point fragments.
+template <typename T, int KTV, bool ALIGNED, bool FT, bool FULL>
 __global__ __launch_bounds__(256, (GenericCfg<T, KTV>::WAVES_PER_SIMD)) void assign_generic_kernel(GenericArgs<T> a)
 {
+    static_assert(ALIGNED || !FULL, "the condition-free stage loop is compiled for aligned rows only");
     using M = Mma<T>;
     using Cfg = GenericCfg<T, KTV>;
     using frag_t = typename M::frag_t;
@@ -289,12 +294,12 @@ __global__ __launch_bounds__(256, (GenericCfg<T, KTV>::WAVES_PER_SIMD)) void ass
             }
 #pragma unroll
             for (int q = 0; q < DQ; ++q) {
-                if (q0 + q < nq) {
+                if (FULL || q0 + q < nq) {
                     if (kc == 0) {
                         const int d0 = (q0 + q) * 8 + E * g;
 #pragma unroll
                         for (int pt = 0; pt < PT; ++pt) {
-                            const frag_t xm = frag_keep<T>(xs[pt][q], d0, D, true);
+                            const frag_t xm = FULL ? xs[pt][q] : frag_keep<T>(xs[pt][q], d0, D, true);
 #pragma unroll
                             for (int e = 0; e < E; ++e) xn[pt] = fma(xm[e], xm[e], xn[pt]);
                         }
@@ -320,7 +325,7 @@ __global__ __launch_bounds__(256, (GenericCfg<T, KTV>::WAVES_PER_SIMD)) void ass
                     // their accumulators keep the start value of a zero row, exactly zero
 #pragma unroll
                     for (int t = 0; t < KT; ++t) {
-                        if (t < kt_act) {
+                        if (FULL || t < kt_act) {
 #pragma unroll
                             for (int e = 0; e < E; ++e)
 #pragma unroll
@@ -806,14 +811,18 @@ static ftk_status launch_generic_t(const AssignCall &c, const AssignPlan &p, con
     const bool aligned = (c.D % Mma<T>::E == 0) && ((uintptr_t)c.X % 16 == 0) && ((uintptr_t)c.C % 16 == 0);
     const bool ft = c.ft != FTK_FT_OFF;
     dim3 grid((unsigned)p.workgroups), block(256);
-#define FTK_LAUNCH_GEN(KV, AL, F) \
-    hipLaunchKernelGGL((assign_generic_kernel<T, KV, AL, F>), grid, block, p.lds_bytes, st, a)
+    // whole stages and whole chunks: the condition-free stage loop
+    const bool full = aligned && c.D % (8 * p.DQ) == 0 && c.K % p.KC == 0;
+#define FTK_LAUNCH_GEN(KV, AL, F, FU) \
+    hipLaunchKernelGGL((assign_generic_kernel<T, KV, AL, F, FU>), grid, block, p.lds_bytes, st, a)
 #define FTK_LAUNCH_GEN_K(KV)                          \
     do {                                              \
-        if (aligned && ft) FTK_LAUNCH_GEN(KV, true, true);     \
-        else if (aligned) FTK_LAUNCH_GEN(KV, true, false);     \
-        else if (ft) FTK_LAUNCH_GEN(KV, false, true);          \
-        else FTK_LAUNCH_GEN(KV, false, false);                 \
+        if (full && ft) FTK_LAUNCH_GEN(KV, true, true, true);          \
+        else if (full) FTK_LAUNCH_GEN(KV, true, false, true);          \
+        else if (aligned && ft) FTK_LAUNCH_GEN(KV, true, true, false); \
+        else if (aligned) FTK_LAUNCH_GEN(KV, true, false, false);      \
+        else if (ft) FTK_LAUNCH_GEN(KV, false, true, false);           \
+        else FTK_LAUNCH_GEN(KV, false, false, false);                  \
     } while (0)
     if (p.KT == 8) FTK_LAUNCH_GEN_K(8);
     else if (p.KT == 4) FTK_LAUNCH_GEN_K(4);
