@@ -129,6 +129,21 @@ __global__ __launch_bounds__(256, (GenericCfg<T, KTV>::WAVES_PER_SIMD)) void ass
         if (p >= a.N) p = a.N - 1;  // clamped rows are computed and discarded
         xrow[pt] = a.X + p * D;
     }
+    // FULL: the hot-loop loads address memory as a wave-uniform base plus a 32-bit lane offset
+    // (one vector add per load instead of 64-bit pointer arithmetic): the rows of this workgroup
+    // against its first row, the staged centroid pieces against C.  The launcher checks that the
+    // offsets fit 32 bits.
+    const char *const xbase = reinterpret_cast<const char *>(a.X + (int64_t)blockIdx.x * (Cfg::WAVES * PT * TN) * D);
+    unsigned xoff[PT];
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt)
+        xoff[pt] = (unsigned)((xrow[pt] - reinterpret_cast<const T *>(xbase)) + E * g) * (unsigned)sizeof(T);
+    auto load_x = [&](int pt, int quad) -> frag_t {
+        if constexpr (FULL)
+            return *reinterpret_cast<const frag_t *>(xbase + (xoff[pt] + (unsigned)(quad * 8 * (int)sizeof(T))));
+        else
+            return load_frag_clamped<T, ALIGNED>(xrow[pt], quad * 8 + E * g, D);
+    };
 
     // Epilogue state per point tile: best tile maximum, runner-up maximum over the OTHER tiles and
     // the best tile's number; the best tile's accumulators are parked in a per-lane LDS slot and the
@@ -196,17 +211,26 @@ __global__ __launch_bounds__(256, (GenericCfg<T, KTV>::WAVES_PER_SIMD)) void ass
         st_row[i] = idx / PPR;
         st_pc[i] = idx % PPR;
     }
+    unsigned coff[NP];  // FULL: byte offset of this thread's pieces inside a chunk's first stage
+#pragma unroll
+    for (int i = 0; i < NP; ++i) coff[i] = (unsigned)(st_row[i] * D + st_pc[i] * E) * (unsigned)sizeof(T);
+    const char *const cbase = reinterpret_cast<const char *>(a.C);
     frag_t pf[NP], pfx;
     // fetch only issues the loads (clamped into the matrix, so always valid); rows beyond K and
     // features beyond D are cleared when the stage is committed to LDS, i.e. after the matrix work
     // of the stage in between - a select right behind the load would make the wave wait for it here
     auto fetch = [&](int kc, int dc) {
         const int q0 = dc * DQ;
+        const unsigned stage_off = (unsigned)(kc * KC * D + q0 * 8) * (unsigned)sizeof(T);  // wave-uniform
 #pragma unroll
         for (int i = 0; i < NP; ++i) {
-            const int j = kc * KC + st_row[i];
-            const int d0 = q0 * 8 + st_pc[i] * E;
-            pf[i] = load_frag_clamped<T, ALIGNED>(a.C + (int64_t)min(j, a.K - 1) * D, d0, D);
+            if constexpr (FULL) {
+                pf[i] = *reinterpret_cast<const frag_t *>(cbase + (coff[i] + stage_off));
+            } else {
+                const int j = kc * KC + st_row[i];
+                const int d0 = q0 * 8 + st_pc[i] * E;
+                pf[i] = load_frag_clamped<T, ALIGNED>(a.C + (int64_t)min(j, a.K - 1) * D, d0, D);
+            }
         }
 #pragma unroll
         for (int e = 0; e < E; ++e) pfx[e] = T(0);
@@ -225,7 +249,7 @@ __global__ __launch_bounds__(256, (GenericCfg<T, KTV>::WAVES_PER_SIMD)) void ass
                 const int j = kc * KC + st_row[i];
                 const int d0 = q0 * 8 + st_pc[i] * E;
                 *reinterpret_cast<frag_t *>(base + st_row[i] * SB + st_pc[i] * 16) =
-                    frag_keep<T>(pf[i], d0, D, j < a.K);
+                    FULL ? pf[i] : frag_keep<T>(pf[i], d0, D, j < a.K);
             }
         }
         if (dc == 0 && tid < KC / E)
@@ -244,7 +268,7 @@ __global__ __launch_bounds__(256, (GenericCfg<T, KTV>::WAVES_PER_SIMD)) void ass
 #pragma unroll
     for (int pt = 0; pt < PT; ++pt)
 #pragma unroll
-        for (int q = 0; q < DQ; ++q) xs[pt][q] = load_frag_clamped<T, ALIGNED>(xrow[pt], q * 8 + E * g, D);
+        for (int q = 0; q < DQ; ++q) xs[pt][q] = load_x(pt, q);
 
     fetch(0, 0);
     commit(0, 0, 0);
@@ -290,7 +314,7 @@ __global__ __launch_bounds__(256, (GenericCfg<T, KTV>::WAVES_PER_SIMD)) void ass
                 for (int pt = 0; pt < PT; ++pt)
 #pragma unroll
                     for (int q = 0; q < DQ; ++q)
-                        xnx[pt][q] = load_frag_clamped<T, ALIGNED>(xrow[pt], (qn0 + q) * 8 + E * g, D);
+                        xnx[pt][q] = load_x(pt, qn0 + q);
             }
 #pragma unroll
             for (int q = 0; q < DQ; ++q) {
@@ -812,7 +836,9 @@ static ftk_status launch_generic_t(const AssignCall &c, const AssignPlan &p, con
     const bool ft = c.ft != FTK_FT_OFF;
     dim3 grid((unsigned)p.workgroups), block(256);
     // whole stages and whole chunks: the condition-free stage loop
-    const bool full = aligned && c.D % (8 * p.DQ) == 0 && c.K % p.KC == 0;
+    // (and 32-bit byte offsets inside C and inside a workgroup's block of rows)
+    const bool full = aligned && c.D % (8 * p.DQ) == 0 && c.K % p.KC == 0 &&
+                      (double)c.K * c.D * sizeof(T) < 4.0e9 && (double)p.points_per_wg * c.D * sizeof(T) < 4.0e9;
 #define FTK_LAUNCH_GEN(KV, AL, F, FU) \
     hipLaunchKernelGGL((assign_generic_kernel<T, KV, AL, F, FU>), grid, block, p.lds_bytes, st, a)
 #define FTK_LAUNCH_GEN_K(KV)                          \
