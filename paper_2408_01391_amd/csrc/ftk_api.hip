@@ -52,17 +52,21 @@ AssignPlan plan_assign(ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft,
     const bool want_smalld = g_tuning.assign_variant == 1 || (g_tuning.assign_variant == -1 && !few_centroids);
     // The mid-D kernel (rows of 33..128 features in registers, centroids in LDS) works in blocks of
     // 512 points, one workgroup per compute unit: it needs 2^17 points.  Measured against the
-    // generic kernel at 2^17..2^20 points (A/B in one process): 7-18 % faster for D <= 96 from 64
-    // centroids on, 6-7 % for wider rows from 1024 on (at D = 128 its 128 point registers leave the
-    // compiler no room); equal at D = 128, K = 256..512.  With checksums its tiles hold 30
-    // centroids (the generic kernel verifies 128 at a time on the vector units at a third of the
-    // cost), so it is chosen only where its lead is larger than that: D <= 64 from 512 centroids,
-    // D <= 96 from 1024, any width from 4096, and only for rows that fill the compiled width.
+    // generic kernel at 2^17..2^20 points (A/B in one process).  Where the generic kernel runs its
+    // condition-free stage loop (D a multiple of 16, K a multiple of 128) the mid-D kernel is 4-8 %
+    // faster for D <= 64 from 256 centroids and for D <= 96 from 1024, equal or slower elsewhere,
+    // and never faster with checksums (its tiles hold 30 centroids; the generic kernel verifies 128
+    // at a time on the vector units at a third of the cost).  Against the guarded stage loop
+    // (ragged D or K) it leads by 7-18 % for D <= 96 from 64 centroids on and by 6-7 % for wider
+    // rows from 1024 on; with checksums for D <= 64 from 512 centroids, D <= 96 from 1024, any
+    // width from 4096, and only for rows that fill the compiled width.
     bool midd_rule = false;
     if (N >= 131072) {
+        const bool generic_whole = D % 16 == 0 && K % 128 == 0;
         if (ft == FTK_FT_OFF) {
-            midd_rule = (D <= 96 && K >= 64) || K >= 1024;
-        } else {
+            midd_rule = generic_whole ? ((D <= 64 && K >= 256) || (D <= 96 && K >= 1024))
+                                      : ((D <= 96 && K >= 64) || K >= 1024);
+        } else if (!generic_whole) {
             const int width = D <= 48 ? 48 : (D <= 64 ? 64 : (D <= 96 ? 96 : 128));
             midd_rule = 8 * D >= 7 * width && ((D <= 64 && K >= 512) || (D <= 96 && K >= 1024) || K >= 4096);
         }

@@ -252,8 +252,12 @@ __global__ __launch_bounds__(256, (GenericCfg<T, KTV>::WAVES_PER_SIMD)) void ass
                     FULL ? pf[i] : frag_keep<T>(pf[i], d0, D, j < a.K);
             }
         }
-        if (dc == 0 && tid < KC / E)
-            *reinterpret_cast<frag_t *>(lds_hcn + ((kc & 1) * KC + tid * E) * (int)sizeof(T)) = pfx;
+        if (dc == 0 && tid < KC / E) {  // stored negated: the accumulators start from -||c||^2/2
+            frag_t neg;
+#pragma unroll
+            for (int e = 0; e < E; ++e) neg[e] = -pfx[e];
+            *reinterpret_cast<frag_t *>(lds_hcn + ((kc & 1) * KC + tid * E) * (int)sizeof(T)) = neg;
+        }
         if (FT && tid >= 64 && tid < 64 + PPR)
             *reinterpret_cast<frag_t *>(base + KC * SB + (tid - 64) * 16) = pfx;
     };
@@ -287,7 +291,7 @@ __global__ __launch_bounds__(256, (GenericCfg<T, KTV>::WAVES_PER_SIMD)) void ass
                 for (int r = 0; r < R; ++r) {
                     const T h = hl[t * TM + M::row(r, g)];
 #pragma unroll
-                    for (int pt = 0; pt < PT; ++pt) acc[pt][t][r] = -h;
+                    for (int pt = 0; pt < PT; ++pt) acc[pt][t][r] = h;
                 }
             }
         }

@@ -62,7 +62,7 @@ def test_batched_step_keeps_empty_clusters_and_rejects_bad_batch_sizes():
 def test_batched_step_whose_last_batch_is_planned_for_another_kernel():
     """A first batch of 2^17 rows and more goes to the mid-D kernel, the shorter last batch to the
     generic one, whose padded norm vector differs: the norms are then written again for it."""
-    N, D, K, batch = 200_000, 64, 128, 140_000
+    N, D, K, batch = 200_000, 64, 300, 140_000
     first = ftk.assign_geometry(ftk.F32, batch, D, K, ftk.FT_OFF)
     last = ftk.assign_geometry(ftk.F32, N - batch, D, K, ftk.FT_OFF)
     assert first.waves_per_workgroup != last.waves_per_workgroup, "the two batches no longer plan different kernels"

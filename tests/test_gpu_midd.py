@@ -158,7 +158,7 @@ def test_mid_d_as_dispatched_by_the_built_in_rule_at_a_full_grid(mode):
     """2^17 points fill every compute unit with one workgroup: the size from which the rule picks
     this kernel.  Every row against the oracle; with checksums, one flip per workgroup on top."""
     ftk.tuning_override(-1, -1, -1)
-    N, D, K = 1 << 17, 64, 512
+    N, D, K = 1 << 17, 64, 520
     geom = ftk.assign_geometry(ftk.F32, N, D, K, mode)
     assert geom.waves_per_workgroup == 8 and geom.workgroups == N // 512, "the rule no longer picks the mid-D kernel"
     X, C = _problem(N, D, K, seed=21)
