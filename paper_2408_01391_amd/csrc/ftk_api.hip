@@ -48,7 +48,20 @@ AssignPlan plan_assign(ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft,
     // centroids to sweep; with few of them (K <= 128) and rows beyond 8 features the generic kernel
     // with its one- and two-tile blockings is faster (measured with the shape sweep's --tune: e.g.
     // D = 32, K = 32: 52 against 85 us for 2^20 points).
-    const bool few_centroids = D > 8 && K <= 128;
+    bool few_centroids = D > 8 && (K <= 128 || (D >= 28 && K <= 256));
+    if (ft != FTK_FT_OFF && smalld_supported(dtype, D, K)) {
+        // With checksums the small-D kernel pays for its 30-centroid tiles, the per-tile verification
+        // and (strict mode) the second sweep, the generic kernel for one vector-unit checksum per 128
+        // centroids.  Measured at 2^20 points (whole call, CORRECT / STRICT): D = 32, K = 256: 196 against
+        // 296 us for the generic kernel; D = 16, K = 256: 126 against 149; D = 32, K = 1024 - where the
+        // checksummed tiles no longer fit LDS at once - 703 against 860; the small-D kernel keeps its
+        // lead for D <= 12, for K >= 512 while its tiles stay resident, and from K = 4096 on.
+        AssignPlan q;
+        memset(&q, 0, sizeof(q));
+        plan_smalld(N, D, K, ft, q);
+        few_centroids = few_centroids || (D >= 16 && K <= 384) || (D >= 24 && K <= 512) ||
+                        (D >= 24 && q.nkc > 1 && K <= 2048);
+    }
     const bool want_smalld = g_tuning.assign_variant == 1 || (g_tuning.assign_variant == -1 && !few_centroids);
     // The mid-D kernel (rows of 33..128 features in registers, centroids in LDS) works in blocks of
     // 512 points, one workgroup per compute unit: it needs 2^17 points.  Measured against the

@@ -37,6 +37,18 @@ def _problem(N, D, K, dtype, seed=0):
     return X, C
 
 
+@pytest.fixture(autouse=True)
+def _kernel_family_named_by_the_shape(request):
+    """Shapes named "small-D" run on the small-D kernel whatever the dispatch rule would pick with
+    checksums on (the rule prefers the generic kernel for some of them)."""
+    params = getattr(getattr(request.node, "callspec", None), "params", {})
+    forced = str(params.get("name", "")).startswith("small-D ") and "goes generic" not in str(params.get("name", ""))
+    if forced:
+        ftk.tuning_override(1, -1, -1)
+    yield
+    ftk.tuning_override(-1, -1, -1)
+
+
 def _run(X, C, ft_mode, faults=None):
     Xd, Cd = to_dev(X), to_dev(C)
     stats = ftk.new_stats(DEV)
