@@ -18,6 +18,9 @@ CASES = [
     (50000, 4096, 64, "f64"),
     (300000, 1, 7, "f64"),          # one feature
     (70000, 3, 65537, "f32"),       # more centroids than points per workgroup sweep, odd D
+    (60000, 1024, 1024, "f32"),     # whole stages and chunks: the generic kernel's condition-free loop, 4 MB of C
+    (200000, 128, 8192, "f32"),     # the same with 64 K-chunks
+    (300000, 100, 5000, "f32"),     # mid-D kernel: ragged width, centroids staged in 19 chunks
 ]
 
 
