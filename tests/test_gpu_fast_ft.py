@@ -142,3 +142,28 @@ def test_fast_fit_with_fault_tolerance_follows_the_oracle():
     assert np.allclose(out["C"].cpu().numpy(), ref["C"], rtol=1e-4, atol=1e-5)
     st = ftk.stats_dict(stats)
     assert st["tiles_checked"] > 0 and st["detected"] == 0
+
+
+@pytest.mark.parametrize("name", ["c2", "c5"])
+def test_fast_ft_at_full_size_under_injection(name):
+    """BASELINE-sized workloads in the launch configuration the benchmark times: the checksummed
+    fast path raises no alarm on a clean run, agrees with the oracle on sampled rows and with the
+    unprotected path everywhere outside near-ties, and with 512 flips injected strict mode returns
+    the clean labels exactly (CORRECT: moved only within the detection threshold)."""
+    w = synth.WORKLOADS[name]
+    X, _ = synth.make_points(w)
+    C = X[synth.init_indices(w, w.N)].copy()
+    rows = np.sort(np.random.default_rng(2).choice(w.N, 3000, replace=False))
+    lab_off, _, _ = _run(X, C, ftk.FT_OFF)
+    for mode in MODES:
+        geom, detect, band = ftk.fast_plan(ftk.F32, w.N, w.D, w.K, mode)
+        print("fast ft full size", name, "mode", mode, flush=True)
+        lab_clean, md_clean, st = _run(X, C, mode)
+        assert st["detected"] == 0 and st["tiles_checked"] > 0 and st["max_residual_ppm"] < 500_000, st
+        check_assign(X, C, lab_clean, md_clean, rows=rows)
+        assert int((lab_clean != lab_off).sum()) <= w.N // 100000 + 2
+        faults = ftk.make_faults(_random_faults(geom, 512, seed=7), DEV)
+        lab, _, st = _run(X, C, mode, faults)
+        assert st["injected"] == min(512, geom.workgroups), st
+        assert st["corrected"] + st["recomputed"] == st["detected"] and st["uncorrectable"] == 0, st
+        check_moved_labels_within_detection_threshold(X, C, lab, lab_clean, mode, coefs=(detect, band))
