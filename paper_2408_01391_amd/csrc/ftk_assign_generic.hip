@@ -106,7 +106,7 @@ __global__ __launch_bounds__(256, (GenericCfg<T, KTV>::WAVES_PER_SIMD)) void ass
     using Cfg = GenericCfg<T, KTV>;
     using frag_t = typename M::frag_t;
     using acc_t = typename M::acc_t;
-    constexpr int TM = M::TM, TN = M::TN, G = M::G, R = M::R, E = M::E;
+    constexpr int TM = M::TM, TN = M::TN, R = M::R, E = M::E;
     constexpr int PT = Cfg::PT, KT = Cfg::KT, KC = KT * TM;
 
     extern __shared__ __align__(16) unsigned char lds_raw[];
