@@ -167,19 +167,22 @@ ftk_status ftk_kmeans_assign_static(ftk_dtype dtype, const void *X, const void *
 /* Assignment step on the reduced-precision matrix path - the counterpart of the paper's TF32
  * tensor-core variant (Section 3.1.5; gfx950 has no TF32 format, its fast matrix format is bf16).
  * Same outputs and tie rule as ftk_kmeans_assign with fault tolerance off.  fp32 operands are
- * split into three bf16 pieces each and the six largest piece products are accumulated in fp32 by
- * the bf16 matrix instructions; the rounding bound of that evaluation is known, and points whose
- * best scores fall inside it are settled by exact re-evaluation as in the fp32 path, so labels
- * meet the same tolerance (identical to the exact arg-min except on near-exact ties) and
- * mindist is the exact-form distance to the chosen centroid.
- * Covers dtype == FTK_F32 with D <= 32 and D a multiple of 4, X and C 16-byte aligned; anything
+ * split into bf16 pieces and the piece products are accumulated in fp32 by the bf16 matrix
+ * instructions: three pieces each and the six largest products for D <= 32, two pieces each and
+ * all four products for 32 < D <= 128 (the wider rows' instruction count makes the certified
+ * bound of the three-piece form nearly as wide, see ftk_fast_plan's band_coef).  The error bound
+ * of that evaluation is known, and points whose best scores fall inside it are settled by exact
+ * re-evaluation as in the fp32 path, so labels meet the same tolerance (identical to the exact
+ * arg-min except on near-exact ties) and mindist is the exact-form distance to the chosen
+ * centroid.
+ * Covers dtype == FTK_F32 with D <= 128 and D a multiple of 4, X and C 16-byte aligned; anything
  * else returns FTK_EINVAL / FTK_EALIGN.
  * ft, faults, stats as for ftk_kmeans_assign: the paper protects its tensor-core variant with the
  * same checksums as the fp32 one (Sections 3.1.5 and 4), and so does this path - tiles of 30
  * centroids whose two checksum rows are split into bf16 pieces like any centroid row and go
  * through the same matrix instructions as the scores they must equal; detection, location,
  * correction, strict mode, the detection threshold (ftk_fast_plan reports it) and the injection
- * hook are those of the fp32 kernel for D <= 32.
+ * hook are those of the register-resident fp32 kernels.
  * workspace: ftk_workspace_bytes(dtype, N, D, K, ft) bytes. */
 ftk_status ftk_kmeans_assign_fast(ftk_dtype dtype, const void *X, const void *C, int64_t N, int32_t D,
                                   int32_t K, int32_t *labels, void *mindist /* nullable */,
@@ -286,7 +289,7 @@ ftk_status ftk_kmeans_fit(ftk_dtype dtype, const void *X, int64_t N, int32_t D, 
                           size_t workspace_bytes, void *hip_stream);
 
 /* The same loop with the assignment on the split-bf16 matrix path (ftk_kmeans_assign_fast):
- * fp32 data with D <= 32, D a multiple of 4, X 16-byte aligned.  Arguments as for
+ * fp32 data with D <= 128, D a multiple of 4, X 16-byte aligned.  Arguments as for
  * ftk_kmeans_fit, fault-tolerance mode (checksummed assignment, DMR update) and counters
  * included; workspace of ftk_workspace_bytes(dtype, N, D, K, ft) bytes. */
 ftk_status ftk_kmeans_fit_fast(ftk_dtype dtype, const void *X, int64_t N, int32_t D, int32_t K,

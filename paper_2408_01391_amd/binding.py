@@ -229,7 +229,7 @@ def fast_plan(dtype_code: int, N: int, D: int, K: int, ft_mode: int = FT_OFF):
 
 def kmeans_assign_fast(X, C, labels=None, mindist=None, workspace=None, want_mindist=True, ft_mode=FT_OFF,
                        faults=None, stats=None):
-    """Assignment step on the split-bf16 matrix path (fp32 data, D <= 32).  Returns (labels, mindist)."""
+    """Assignment step on the split-bf16 matrix path (fp32 data, D <= 128).  Returns (labels, mindist)."""
     _dev2d(X, "X"), _dev2d(C, "C")
     if X.dtype != C.dtype or X.shape[1] != C.shape[1]:
         raise ValueError("X [N,D] and C [K,D] must share dtype and D")
@@ -335,7 +335,7 @@ def profile_read():
 def kmeans_fit(X, K, iters, seed=0, C_init=None, ft_mode=FT_OFF, stats=None, workspace=None,
                want_inertia=True, fast=False):
     """Lloyd loop.  Returns dict(C, labels, counts, inertia (numpy, host) or None).
-    fast=True runs the assignment on the split-bf16 matrix path (fp32, D <= 32)."""
+    fast=True runs the assignment on the split-bf16 matrix path (fp32, D <= 128)."""
     import numpy as np
     _dev2d(X, "X")
     N, D = X.shape

@@ -517,7 +517,7 @@ ftk_status ftk_kmeans_assign_static(ftk_dtype dtype, const void *X, const void *
 static ftk_status check_fast(ftk_dtype dtype, int D)
 {
     if (!fast_supported(dtype, D)) {
-        set_error("the fast assignment covers fp32 data with D <= 32 and D a multiple of 4 (got dtype=%d D=%d)",
+        set_error("the fast assignment covers fp32 data with D <= 128 and D a multiple of 4 (got dtype=%d D=%d)",
                   (int)dtype, D);
         return FTK_EINVAL;
     }

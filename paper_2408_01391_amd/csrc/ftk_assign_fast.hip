@@ -37,43 +37,12 @@
 #include <cmath>
 #include <type_traits>
 
+#include "ftk_fast.h"
 #include "ftk_internal.h"
 #include "ftk_mma.h"
 #include "ftk_smalld.h"
 
 namespace ftk {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-
-struct FastArgs {
-    const float *X;
-    const float *C;
-    const float *hcn;     // half squared norms of the K centroids
-    const double *scal;   // scal[0] = max_j ||c_j||^2
-    const uint4 *csplit;  // [tiles_total][32][row units] centroid pieces, 16-byte units
-    int64_t N;
-    int D, K;
-    int tpc;          // tiles staged in LDS at a time
-    int nch;          // chunks
-    int tiles_total;  // ceil(K / 32)
-    int nblocks;      // point blocks (waves*PT*32 points each)
-    int nunits;       // wave units (PT*32 points each)
-    int32_t *labels;
-    float *mindist;
-    int32_t *wl;
-    int32_t *wl_count;
-    double band_coef;
-    // fault tolerance / injection (as in the fp32 small-D kernel)
-    ftk_ft_stats *stats;
-    const float *chk_v1;  // [tiles_total*2][D8] plain checksum rows per (tile, lane group)
-    const float *chk_v2;  // [tiles_total*2][D8] weighted (1..15) checksum rows
-    const float *chk_s;   // [tiles_total*2][2]  matching sums of the half norms
-    const ftk_fault *faults;
-    int n_faults;
-    int ft_mode;
-    double ft_coef;       // detection threshold = ft_coef * (||x|| max||c|| + max||c||^2/2)
-    float widen;          // 1 in strict mode, else 0
-};
 
 // 16-byte units per centroid row in the LDS image: 3 pieces of NQ blocks, padded to an odd count
 // so that the 32 rows of a tile spread over the banks
@@ -529,12 +498,13 @@ __global__ __launch_bounds__(fast_waves(NQ) * 64, fast_waves_per_simd(NQ)) void 
 
 bool fast_supported(ftk_dtype dtype, int D)
 {
-    return dtype == FTK_F32 && D <= 32 && D % 4 == 0;
+    return dtype == FTK_F32 && D <= 128 && D % 4 == 0;
 }
 
 size_t fast_split_bytes(ftk_dtype dtype, int D, int K)
 {
     if (!fast_supported(dtype, D)) return 0;
+    if (D > 32) return fast_wide_split_bytes(D, K);
     const int nq = (int)ceil_div(D, 8);
     // tiles of 30 centroids when checksums are on
     return (size_t)ceil_div(K, 30) * 32 * fast_row_units(nq) * sizeof(uint4);
@@ -564,6 +534,10 @@ static int fast_tpc(int nq, int tiles_total)
 // this fills what it and the geometry queries need.
 void plan_fast(int64_t N, int D, int K, ftk_ft_mode ft, AssignPlan &p)
 {
+    if (D > 32) {
+        plan_fast_wide(N, D, K, ft, p);
+        return;
+    }
     const bool FT = ft != FTK_FT_OFF;
     const int nq = (int)ceil_div(D, 8);
     p.variant = VAR_SMALLD;
@@ -602,6 +576,7 @@ static void launch_fast_t(FastArgs a, const AssignPlan &p, const float *chk_v1, 
 
 ftk_status launch_assign_fast(const AssignCall &c, const AssignPlan &p, const Workspace &w, hipStream_t st)
 {
+    if (c.D > 32) return launch_assign_fast_wide(c, p, w, st);
     if ((uintptr_t)c.X % 16 || (uintptr_t)c.C % 16) {
         set_error("the fast variant needs 16-byte aligned X and C");
         return FTK_EALIGN;

@@ -94,7 +94,7 @@ struct Workspace {
     double *partials;   // [1024] block partial sums
     int64_t *idx;       // [K]   seeded initial point indices
     // fast (split-bf16) assignment
-    void *csplit;       // centroid pieces in LDS image order (fp32 data with D <= 32, else empty)
+    void *csplit;       // centroid pieces in LDS image order (fp32 data with D <= 128, else empty)
     int32_t *batch_counters;  // [4 * MAX_BATCHES] work-list counters per batch of the batched step
     size_t total;
 };

@@ -154,7 +154,8 @@ def main():
             resident = ftk.assign_geometry(code, N, D, K, mode).waves_per_workgroup == 8
             variant = ("s" if D <= 32 else "m") if resident else "g"
             cell = "%s %.0f us %.0f%%" % (variant, t * 1e6, 100.0 * tf / PEAK[args.dtype])
-            if variant == "s" and args.ft == "off":  # the split-bf16 fast path covers the same shapes
+            # the split-bf16 fast path covers fp32 rows of up to 128 features
+            if args.dtype == "f32" and D <= 128 and D % 4 == 0 and args.ft == "off":
                 for _ in range(3):
                     ftk.kmeans_assign_fast(Xd, Cd, labels=lab, mindist=md, workspace=ws)
                 ftk.profile_enable(True)

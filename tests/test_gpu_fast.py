@@ -81,8 +81,8 @@ def test_fast_assign_full_size_sampled_rows(name):
 
 
 def test_fast_assign_rejects_what_it_does_not_cover():
-    X = torch.zeros(64, 40, device="cuda:0")
-    C = torch.zeros(4, 40, device="cuda:0")
+    X = torch.zeros(64, 132, device="cuda:0")
+    C = torch.zeros(4, 132, device="cuda:0")
     with pytest.raises(ftk.FtkError):
         ftk.kmeans_assign_fast(X, C)
     Xd = torch.zeros(64, 8, dtype=torch.float64, device="cuda:0")

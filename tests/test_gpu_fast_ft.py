@@ -50,7 +50,7 @@ def test_fast_plan_reports_the_checksummed_tile_layout():
     assert g_off.tiles_per_wave == 2 * 32 and g_on.tiles_per_wave == 2 * 34  # 32 resp. 30 centroids per tile
     assert g_on.workgroups == g_off.workgroups and g_on.regs_per_tile == 16 and g_on.bits == 32
     with pytest.raises(ftk.FtkError):
-        ftk.fast_plan(ftk.F32, 1000, 40, 10, ftk.FT_OFF)
+        ftk.fast_plan(ftk.F32, 1000, 132, 10, ftk.FT_OFF)
 
 
 @pytest.mark.parametrize("name,N,D,K", SHAPES)
