@@ -192,7 +192,10 @@ ftk_status ftk_kmeans_assign_fast(ftk_dtype dtype, const void *X, const void *C,
 
 /* (host) What ftk_assign_geometry and ftk_ft_thresholds report, for the reduced-precision path:
  * the extents fault descriptors are taken modulo, the detection threshold and the settlement band
- * (both as multiples of B_i, see ftk_ft_thresholds).  Any output may be NULL. */
+ * (both as multiples of B_i, see ftk_ft_thresholds).  For 32 < D <= 128 detect_coef is an upper
+ * bound: the kernel's threshold is the rounding term plus ||x_i|| times the measured truncation
+ * of the two-piece checksum rows, which is at most (and typically a tenth of) the 2^-16 * 15 *
+ * max||c|| counted here.  Any output may be NULL. */
 ftk_status ftk_fast_plan(ftk_dtype dtype, int64_t N, int32_t D, int32_t K, ftk_ft_mode ft,
                          ftk_geometry *geometry, double *detect_coef, double *band_coef);
 

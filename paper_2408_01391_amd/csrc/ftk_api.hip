@@ -562,7 +562,7 @@ ftk_status ftk_fast_plan(ftk_dtype dtype, int64_t N, int32_t D, int32_t K, ftk_f
         geometry->lanes = 64;
         geometry->bits = 32;
     }
-    if (detect_coef) *detect_coef = ft == FTK_FT_OFF ? 0.0 : p.ft_coef;
+    if (detect_coef) *detect_coef = ft == FTK_FT_OFF ? 0.0 : p.ft_coef + p.ft_trunc_coef;
     if (band_coef) *band_coef = p.band_coef;
     return FTK_OK;
 }

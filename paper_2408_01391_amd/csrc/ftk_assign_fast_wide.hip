@@ -71,11 +71,42 @@ __device__ __forceinline__ void split2(float x, __bf16 &p0, __bf16 &p1)
 // Without checksums row 32T + i holds centroid 32T + i; with them a tile holds 30 centroids in the
 // rows their accumulator registers read (register r of lane group g sits in row 8(r/4) + 4g + r%4)
 // and the two rows of register 15 hold the sums of the groups' 15 two-piece centroids.
+// Blocks beyond the image's (FT only): one wave per checksum row adds up the same 15 two-piece
+// centroids and measures what the row loses when it is reduced to two pieces itself,
+// delta = sum - (p0 + p1): the residual of a fault-free tile contains x . delta, which does not
+// shrink with rounding noise, so the detection threshold carries ||x|| max ||delta|| (scal[1]).
 template <int NH, bool FT>
-__global__ __launch_bounds__(256) void split2_centroids_kernel(const float *C, int D, int K, int tiles_total, uint4 *img)
+__global__ __launch_bounds__(256) void split2_centroids_kernel(const float *C, int D, int K, int tiles_total, uint4 *img,
+                                                               int image_blocks, double *scal)
 {
     constexpr int SU = fw_row_units(NH);
     constexpr int NU = 2 * NH;
+    if constexpr (FT) {
+        if ((int)blockIdx.x >= image_blocks) {
+            const int tg = ((int)blockIdx.x - image_blocks) * 4 + (int)(threadIdx.x >> 6);  // tile * 2 + lane group
+            if (tg >= tiles_total * 2) return;
+            const int lane = threadIdx.x & 63;
+            const int j0 = 30 * (tg >> 1) + 15 * (tg & 1);
+            float acc = 0.f;
+            for (int d = lane; d < D; d += 64) {
+                float sum = 0.f;
+                for (int i = 0; i < 15 && j0 + i < K; ++i) {
+                    __bf16 q0, q1;
+                    split2(C[(size_t)(j0 + i) * D + d], q0, q1);
+                    sum += (float)q0 + (float)q1;
+                }
+                __bf16 q0, q1;
+                split2(sum, q0, q1);
+                const float delta = sum - ((float)q0 + (float)q1);
+                acc = fmaf(delta, delta, acc);
+            }
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+            if (lane == 0 && acc > 0.f)
+                atomicMax((unsigned long long *)(scal + 1), (unsigned long long)__double_as_longlong((double)sqrtf(acc)));
+            return;
+        }
+    }
     const int rows = tiles_total * 32;
     const int t = blockIdx.x * 256 + threadIdx.x;
     if (t >= rows * NU) return;
@@ -150,6 +181,8 @@ __global__ __launch_bounds__(FW_WAVES * 64, FW_WAVES / 4) void assign_fast_wide_
     const int D = a.D;
     const float cmax2 = (float)a.scal[0];
     const float cmax = sqrtf(cmax2);
+    // largest ||delta|| of a checksum row (see split2_centroids_kernel), with room for ||x0 + x1|| over ||x||
+    const float dnmax = FT ? 1.001f * (float)a.scal[1] : 0.f;
     const bool resident = a.nch == 1;
     int n_injected = 0, n_detected = 0, n_corrected = 0, n_recomputed = 0;
     float worst_resid = 0.f;
@@ -269,7 +302,7 @@ __global__ __launch_bounds__(FW_WAVES * 64, FW_WAVES / 4) void assign_fast_wide_
                     b1[pt][hb] = __builtin_bit_cast(uint4, q1);
                 }
                 xn[pt] = s + __shfl_xor(s, 32, 64);
-                tau[pt] = (float)a.ft_coef * (sqrtf(xn[pt]) * cmax + 0.5f * cmax2);
+                tau[pt] = (float)a.ft_coef * (sqrtf(xn[pt]) * cmax + 0.5f * cmax2) + sqrtf(xn[pt]) * dnmax;
                 inv_tau[pt] = 1.0f / tau[pt];
                 force_refine[pt] = 0;
                 rmax[pt] = 0.f;
@@ -619,16 +652,18 @@ size_t fast_wide_split_bytes(int D, int K)
     return (size_t)ceil_div(K, 30) * 32 * fw_row_units(fw_nh(D)) * sizeof(uint4);
 }
 
-// Detection threshold coefficient: the form of the fp32 small-D tiles (15 scores against one
-// checksum) with a factor for what the two-piece checksum row adds: its own truncation, up to
-// 2^-16 of the sum of 15 centroids, does not cancel in the residual (that of the centroids does).
-// Calibrated so that the largest fault-free residual seen stays below half the threshold.
-static constexpr double FW_FT_KAPPA = 1.5;
+// Detection threshold: the rounding part has the form of the fp32 small-D tiles (15 scores against
+// one checksum; the instructions sum 16 exact products and round once, so the coefficient is that
+// of the three-piece kernel), and the kernel adds ||x|| max ||delta|| for what the two-piece
+// checksum rows lose (measured per call by split2_centroids_kernel; at most 2^-16 of the sum of
+// 15 centroids per feature, typically a tenth of that bound).
+static constexpr double FW_FT_KAPPA = 1.0;
 static double fw_ft_coef(int D)
 {
     const double n = 15.0;
     return FW_FT_KAPPA * Mma<float>::kEps * n * (std::sqrt(n) + std::sqrt((double)D + 4.0));
 }
+static constexpr double FW_TRUNC_COEF = 1.001 * 15.0 / 65536.0;  // ||delta|| <= 2^-16 * 15 max ||c||
 
 void plan_fast_wide(int64_t N, int D, int K, ftk_ft_mode ft, AssignPlan &p)
 {
@@ -659,6 +694,7 @@ void plan_fast_wide(int64_t N, int D, int K, ftk_ft_mode ft, AssignPlan &p)
     p.regs_per_tile = 16;
     p.lds_bytes = (size_t)tpc * tile_bytes;
     p.ft_coef = fw_ft_coef(D);
+    p.ft_trunc_coef = FT ? FW_TRUNC_COEF : 0.0;
     // two scores, each: truncation of both operands to two pieces (2^-15 = 512 u of the magnitude),
     // 4*nh instructions at 7 u, and 2 u for the fp32 evaluation of the magnitude itself
     p.band_coef = 2.0 * (512.0 + 28.0 * nh + 4.0) * Mma<float>::kEps;
@@ -668,9 +704,10 @@ template <int NH, bool FT>
 static void launch_fast_wide_t(const FastArgs &a, const AssignPlan &p, hipStream_t st)
 {
     const int rows = a.tiles_total * 32;
-    const dim3 sgrid((unsigned)ceil_div((int64_t)rows * 2 * NH, 256));
-    hipLaunchKernelGGL((split2_centroids_kernel<NH, FT>), sgrid, dim3(256), 0, st, a.C, a.D, a.K, a.tiles_total,
-                       const_cast<uint4 *>(a.csplit));
+    const int image_blocks = (int)ceil_div((int64_t)rows * 2 * NH, 256);
+    const int delta_blocks = FT ? (int)ceil_div(a.tiles_total * 2, 4) : 0;
+    hipLaunchKernelGGL((split2_centroids_kernel<NH, FT>), dim3(image_blocks + delta_blocks), dim3(256), 0, st, a.C, a.D,
+                       a.K, a.tiles_total, const_cast<uint4 *>(a.csplit), image_blocks, const_cast<double *>(a.scal));
     if (a.D == 16 * NH)
         hipLaunchKernelGGL((assign_fast_wide_kernel<NH, FT, true>), dim3(p.grid), dim3(FW_WAVES * 64), p.lds_bytes, st, a);
     else

@@ -62,6 +62,7 @@ struct AssignPlan {
     int kch;                    // centroids staged in LDS at a time (small-D variant)
     double ft_coef;             // checksum detection threshold = ft_coef * (||x|| max||c|| + max||c||^2/2)
     double band_coef;           // rounding band of a score comparison, same scale
+    double ft_trunc_coef;       // upper bound of what the kernel adds to ft_coef for truncated checksum rows (else 0)
 };
 AssignPlan plan_assign(ftk_dtype dtype, int64_t N, int D, int K, ftk_ft_mode ft, bool aligned16);
 
@@ -70,7 +71,8 @@ struct Workspace {
     // assignment
     void *hcn;          // [Kpad] half squared centroid norms (dtype), zero padded
     size_t hcn_entries; // Kpad: entries reserved for hcn
-    double *scal;       // [8]   0: max_j ||c_j||^2 (as double bits, atomically maximised)
+    double *scal;       // [8]   0: max_j ||c_j||^2 (as double bits, atomically maximised);
+                        //       1: max truncation norm of a checksum row (two-piece fast path, same encoding)
     void *chk_v1;       // [nkc*KT][D8] per-tile plain checksum rows (dtype)
     void *chk_v2;       // [nkc*KT][D8] per-tile weighted checksum rows (dtype)
     void *chk_s;        // [nkc*KT][2]  their half-norm terms (dtype; small-D variant)

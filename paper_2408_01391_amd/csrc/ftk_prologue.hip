@@ -10,6 +10,7 @@ __global__ void reset_assign_state_kernel(double *scal, int32_t *wl_count)
 {
     if (threadIdx.x == 0) {
         scal[0] = 0.0;
+        scal[1] = 0.0;    // largest truncation norm of a checksum row (two-piece fast path)
         wl_count[0] = 0;  // refine work-list length
         wl_count[1] = 0;  // dynamic point-block counter of the persistent small-D kernel
     }
@@ -64,6 +65,7 @@ __global__ __launch_bounds__(SINGLE ? 1024 : 256) void centroid_norms_kernel(con
         if (threadIdx.x == 0) {
             for (int i = 1; i < (int)(blockDim.x >> 6); ++i) m = sh_m[i] > m ? sh_m[i] : m;
             scal[0] = m;
+            scal[1] = 0.0;    // largest truncation norm of a checksum row (two-piece fast path)
             wl_count[0] = 0;  // refine work-list length
             wl_count[1] = 0;  // dynamic point-block counter of the persistent small-D kernel
         }

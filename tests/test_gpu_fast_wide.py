@@ -71,6 +71,18 @@ def test_fast_wide_assignment_matches_oracle(N, D, K, mode):
         assert st["max_residual_ppm"] < 500_000, st  # headroom of the threshold over rounding noise
 
 
+@pytest.mark.parametrize("N,D,K,spread", [(13619, 36, 1000, 10.0), (20000, 40, 2048, 10.0), (9000, 36, 300, 0.5)])
+def test_fast_wide_checksum_rows_truncation_raises_no_alarm(N, D, K, spread):
+    """Narrow rows, many far-out centroids: what a checksum row loses when it is reduced to two
+    pieces is largest against the threshold here (it does not shrink with D like rounding noise);
+    the threshold carries its measured norm, so a clean run stays silent in every mode."""
+    X, C = _problem(N, D, K, seed=17, spread=spread)
+    for mode in (ftk.FT_DETECT, ftk.FT_STRICT):
+        labels, mind, st = _run(X, C, mode)
+        check_assign(X, C, labels, mind)
+        assert st["tiles_checked"] > 0 and st["detected"] == 0 and st["max_residual_ppm"] < 600_000, st
+
+
 @pytest.mark.parametrize("N,D,K", [(4099, 128, 256), (2500, 100, 300)])
 def test_fast_wide_exact_ties_go_to_the_lowest_index(N, D, K):
     """Duplicated centroids score identically: both lie inside the bound and are settled exactly."""
