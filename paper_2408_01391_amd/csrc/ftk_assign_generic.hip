@@ -633,6 +633,50 @@ __global__ __launch_bounds__(256, (GenericCfg<T, KTV>::WAVES_PER_SIMD)) void ass
     }
 }
 
+// The end of a batch: every thread holds its best (distance, index) per point; combined over the
+// wave, then over the four waves, lowest index on equal distances; written by one thread per point.
+template <typename T, int P>
+__device__ __forceinline__ void refine_settle(double (&best)[P], int (&bj)[P], const int32_t *__restrict__ wl, int first,
+                                              int np, int32_t *labels, T *mindist, double (*sh_best)[8], int (*sh_j)[8])
+{
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+#pragma unroll
+    for (int u = 0; u < P; ++u) {
+#pragma unroll
+        for (int mask = 1; mask < 64; mask <<= 1) {
+            const double ob = __shfl_xor(best[u], mask, 64);
+            const int oj = __shfl_xor(bj[u], mask, 64);
+            const bool take = ob < best[u] || (ob == best[u] && oj < bj[u]);
+            best[u] = take ? ob : best[u];
+            bj[u] = take ? oj : bj[u];
+        }
+        if (lane == 0) {
+            sh_best[wave][u] = best[u];
+            sh_j[wave][u] = bj[u];
+        }
+    }
+    __syncthreads();
+    if (tid < np) {
+        double b = sh_best[0][tid];
+        int j = sh_j[0][tid];
+#pragma unroll
+        for (int v = 1; v < 4; ++v) {
+            const double ob = sh_best[v][tid];
+            const int oj = sh_j[v][tid];
+            if (ob < b || (ob == b && oj < j)) {
+                b = ob;
+                j = oj;
+            }
+        }
+        const int64_t p = wl[first + tid];
+        labels[p] = j == 0x7fffffff ? 0 : j;
+        if (mindist) mindist[p] = (T)b;
+    }
+    __syncthreads();  // the slots are rewritten for the next batch
+}
+
 // Exact settlement of the queued points: all K distances of a point in the direct-difference form
 // (double), then the arg-min with the lowest index on ties.  A workgroup settles a batch of up to
 // P queued points at a time: thread t owns centroid rows t, t + 256, ... and evaluates each of
@@ -723,42 +767,94 @@ __device__ __forceinline__ void refine_batch(const T *__restrict__ X, const T *_
             }
         }
     }
-#pragma unroll
-    for (int u = 0; u < P; ++u) {
-#pragma unroll
-        for (int mask = 1; mask < 64; mask <<= 1) {
-            const double ob = __shfl_xor(best[u], mask, 64);
-            const int oj = __shfl_xor(bj[u], mask, 64);
-            const bool take = ob < best[u] || (ob == best[u] && oj < bj[u]);
-            best[u] = take ? ob : best[u];
-            bj[u] = take ? oj : bj[u];
-        }
-        if (lane == 0) {
-            sh_best[wave][u] = best[u];
-            sh_j[wave][u] = bj[u];
-        }
-    }
-    __syncthreads();
-    if (tid < np) {
-        double b = sh_best[0][tid];
-        int j = sh_j[0][tid];
-#pragma unroll
-        for (int v = 1; v < 4; ++v) {
-            const double ob = sh_best[v][tid];
-            const int oj = sh_j[v][tid];
-            if (ob < b || (ob == b && oj < j)) {
-                b = ob;
-                j = oj;
-            }
-        }
-        const int64_t p = wl[first + tid];
-        labels[p] = j == 0x7fffffff ? 0 : j;
-        if (mindist) mindist[p] = (T)b;
-    }
-    __syncthreads();  // the slots are rewritten for the next batch
+    refine_settle<T, P>(best, bj, wl, first, np, labels, mindist, sh_best, sh_j);
 }
 
-template <typename T, bool ALIGNED, int JU>
+// The same for aligned rows of 16 fragments and more: L lanes share a centroid row (8, or the whole
+// wave from 128 fragments on), each taking every L-th 16-byte fragment.  With a thread per row a
+// load instruction touches 64 different rows - 64 requests to the vector cache, a whole line read
+// for each 16 bytes used - and the kernel's time was those requests (2^18 x 128, K = 256: 12 us
+// for a few hundred points); here an instruction reads runs of 128 bytes and more.  The L partial
+// sums of a row are added by the same tree for every row, so identical centroids still tie exactly.
+template <typename T, int L, int P>
+__device__ __forceinline__ void refine_batch_wide(const T *__restrict__ X, const T *__restrict__ C, int D, int K,
+                                                  const int32_t *__restrict__ wl, int first, int np,
+                                                  int32_t *labels, T *mindist, double (*sh_best)[8], int (*sh_j)[8])
+{
+    constexpr int E = Mma<T>::E;
+    constexpr int ROWS = 256 / L;          // centroid rows per pass of the workgroup
+    constexpr int JU = P >= 4 ? 2 : 4;     // rows in flight per thread
+    constexpr int DU = P >= 4 ? 2 : 4;     // fragments per row in flight
+    using F = typename Mma<T>::frag_t;
+    const int tid = threadIdx.x;
+    const int sub = tid & (L - 1);
+    const int slot = tid / L;
+    const int nfrag = D / E;
+    const T *x[P];
+#pragma unroll
+    for (int u = 0; u < P; ++u)  // slots beyond the batch repeat its last point
+        x[u] = X + (int64_t)wl[first + min(u, np - 1)] * D;
+    double best[P];
+    int bj[P];
+#pragma unroll
+    for (int u = 0; u < P; ++u) {
+        best[u] = __builtin_huge_val();
+        bj[u] = 0x7fffffff;
+    }
+    for (int j0 = slot; j0 < K; j0 += ROWS * JU) {
+        const T *c[JU];
+        double s[JU][P];
+#pragma unroll
+        for (int r = 0; r < JU; ++r) {
+            c[r] = C + (int64_t)min(j0 + ROWS * r, K - 1) * D;
+#pragma unroll
+            for (int u = 0; u < P; ++u) s[r][u] = 0.0;
+        }
+        for (int f0 = sub; f0 < nfrag; f0 += L * DU) {
+            F cf[JU][DU], xf[P][DU];
+#pragma unroll
+            for (int v = 0; v < DU; ++v) {
+                const int off = min(f0 + L * v, nfrag - 1) * E;
+#pragma unroll
+                for (int r = 0; r < JU; ++r) cf[r][v] = *reinterpret_cast<const F *>(c[r] + off);
+#pragma unroll
+                for (int u = 0; u < P; ++u) xf[u][v] = *reinterpret_cast<const F *>(x[u] + off);
+            }
+#pragma unroll
+            for (int v = 0; v < DU; ++v) {
+                const bool keep = f0 + L * v < nfrag;  // a clamped copy beyond the row counts nothing
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+#pragma unroll
+                    for (int u = 0; u < P; ++u) {
+                        const double xd = (double)xf[u][v][e];
+#pragma unroll
+                        for (int r = 0; r < JU; ++r) {
+                            const double diff = keep ? xd - (double)cf[r][v][e] : 0.0;
+                            s[r][u] = fma(diff, diff, s[r][u]);
+                        }
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < JU; ++r) {  // j increases within a thread: first minimum kept
+            const int j = j0 + ROWS * r;
+#pragma unroll
+            for (int u = 0; u < P; ++u) {
+                double t = s[r][u];
+#pragma unroll
+                for (int mask = L >> 1; mask >= 1; mask >>= 1) t += __shfl_xor(t, mask, 64);
+                const bool better = j < K && t < best[u];
+                best[u] = better ? t : best[u];
+                bj[u] = better ? j : bj[u];
+            }
+        }
+    }
+    refine_settle<T, P>(best, bj, wl, first, np, labels, mindist, sh_best, sh_j);
+}
+
+template <typename T, bool ALIGNED, int JU, int L>
 __global__ __launch_bounds__(256) void refine_kernel(const T *__restrict__ X, const T *__restrict__ C, int D, int K,
                                                      const int32_t *__restrict__ wl, const int32_t *__restrict__ wl_count,
                                                      int32_t *labels, T *mindist, ftk_ft_stats *stats,
@@ -774,14 +870,25 @@ __global__ __launch_bounds__(256) void refine_kernel(const T *__restrict__ X, co
     for (int b = blockIdx.x; b < nbatch; b += gridDim.x) {
         const int first = b * bs;
         const int np = min(bs, count - first);
-        if (bs == 1)
-            refine_batch<T, ALIGNED, JU, 1>(X, C, D, K, wl, first, np, labels, mindist, sh_best, sh_j);
-        else if (bs == 2)
-            refine_batch<T, ALIGNED, (JU > 4 ? 4 : JU), 2>(X, C, D, K, wl, first, np, labels, mindist, sh_best, sh_j);
-        else if (bs == 4)
-            refine_batch<T, ALIGNED, (JU > 2 ? 2 : JU), 4>(X, C, D, K, wl, first, np, labels, mindist, sh_best, sh_j);
-        else
-            refine_batch<T, ALIGNED, (JU > 2 ? 2 : JU), 8>(X, C, D, K, wl, first, np, labels, mindist, sh_best, sh_j);
+        if constexpr (L > 1) {
+            if (bs == 1)
+                refine_batch_wide<T, L, 1>(X, C, D, K, wl, first, np, labels, mindist, sh_best, sh_j);
+            else if (bs == 2)
+                refine_batch_wide<T, L, 2>(X, C, D, K, wl, first, np, labels, mindist, sh_best, sh_j);
+            else if (bs == 4)
+                refine_batch_wide<T, L, 4>(X, C, D, K, wl, first, np, labels, mindist, sh_best, sh_j);
+            else
+                refine_batch_wide<T, L, 8>(X, C, D, K, wl, first, np, labels, mindist, sh_best, sh_j);
+        } else {
+            if (bs == 1)
+                refine_batch<T, ALIGNED, JU, 1>(X, C, D, K, wl, first, np, labels, mindist, sh_best, sh_j);
+            else if (bs == 2)
+                refine_batch<T, ALIGNED, (JU > 4 ? 4 : JU), 2>(X, C, D, K, wl, first, np, labels, mindist, sh_best, sh_j);
+            else if (bs == 4)
+                refine_batch<T, ALIGNED, (JU > 2 ? 2 : JU), 4>(X, C, D, K, wl, first, np, labels, mindist, sh_best, sh_j);
+            else
+                refine_batch<T, ALIGNED, (JU > 2 ? 2 : JU), 8>(X, C, D, K, wl, first, np, labels, mindist, sh_best, sh_j);
+        }
     }
     if (stats && blockIdx.x == 0) {
         // statistics: queued points plus those the main kernel's workgroups settled in place
@@ -876,17 +983,20 @@ static void launch_refine_t(const AssignCall &c, const Workspace &w, int n_wg, h
 {
     const bool aligned = (c.D % Mma<T>::E == 0) && ((uintptr_t)c.X % 16 == 0) && ((uintptr_t)c.C % 16 == 0);
     dim3 grid(1024), block(256);
-#define FTK_LAUNCH_REFINE(AL, JU)                                                                      \
-    hipLaunchKernelGGL((refine_kernel<T, AL, JU>), grid, block, 0, st, (const T *)c.X, (const T *)c.C, \
+#define FTK_LAUNCH_REFINE(AL, JU, LV)                                                                      \
+    hipLaunchKernelGGL((refine_kernel<T, AL, JU, LV>), grid, block, 0, st, (const T *)c.X, (const T *)c.C, \
                        c.D, c.K, w.wl, w.wl_count, c.labels, (T *)c.mindist, c.stats, w.wg_refined, n_wg)
 #define FTK_LAUNCH_REFINE_J(JU)                   \
     do {                                          \
-        if (aligned) FTK_LAUNCH_REFINE(true, JU); \
-        else FTK_LAUNCH_REFINE(false, JU);        \
+        if (aligned) FTK_LAUNCH_REFINE(true, JU, 1); \
+        else FTK_LAUNCH_REFINE(false, JU, 1);        \
     } while (0)
     // sixteen 16-byte loads in flight per thread: short rows leave room for more rows at once
     const int nfrag = (int)ceil_div(c.D, Mma<T>::E);
-    if (nfrag <= 2) FTK_LAUNCH_REFINE_J(8);
+    // long aligned rows: lanes share a row (see refine_batch_wide)
+    if (aligned && nfrag >= 128) FTK_LAUNCH_REFINE(true, 1, 64);
+    else if (aligned && nfrag >= 16) FTK_LAUNCH_REFINE(true, 1, 8);
+    else if (nfrag <= 2) FTK_LAUNCH_REFINE_J(8);
     else if (nfrag <= 4) FTK_LAUNCH_REFINE_J(4);
     else if (nfrag <= 8) FTK_LAUNCH_REFINE_J(2);
     else FTK_LAUNCH_REFINE_J(1);
