@@ -29,13 +29,13 @@
 // it) - the winner always, up to three more - the two lanes of a point each covering the features
 // they hold.  More candidates than that go to the refine kernel.
 //
-// What bounds it (measured): not the matrix unit, which is busy a third of the time, but the
-// per-lane row accesses - the first fetch, the second one and the winner's centroid row are 16-byte
-// pieces at a stride of one row between lanes, each a request of its own to the vector cache, and
-// their number grows with D like the matrix work does.  All loads of a phase are therefore issued
-// together (and the compiler kept from folding the second fetch into the first, which would hold
-// the fp32 row in registers across the sweep); evaluating the distances with row-contiguous loads
-// shared by the wave was tried and cost more vector instructions than the requests it saved.
+// What bounds it (measured): not the matrix unit, which is busy a quarter of the time, but the two
+// phases of a unit that wait for memory - the fetch of the rows and their second fetch with the
+// winners' centroid rows - each as long as the sweep, with one other wave on the SIMD to fill the
+// time.  All loads of a phase are therefore issued together, and the compiler is kept from folding
+// the second fetch into the first, which would hold the fp32 row in registers across the sweep.
+// Evaluating the distances with row-contiguous loads shared by the wave was tried and cost more
+// vector instructions than it saved in waiting.
 //
 // Fault tolerance (Sections 2.3, 4): tiles of 30 centroids and two checksum rows, verification,
 // location and correction as in the fp32 small-D kernel.  A checksum row is the sum of its 15
