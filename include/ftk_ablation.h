@@ -62,6 +62,22 @@ int ftk_abl_fused_alu_assign(int dtype, const void *X, const void *C, int64_t N,
                              int32_t *labels, void *mindist, int32_t variant, void *workspace,
                              size_t workspace_bytes, void *hip_stream);
 
+/* One bf16 matrix instruction (v_mfma_f32_32x32x16_bf16) per problem on plain matrices, all device
+ * pointers: D = A B + C with A [tiles][32][16] and B [tiles][16][32] as bf16 bit patterns, C and D
+ * [tiles][32][32] fp32, row-major.  A probe for tests: the error bound of the reduced-precision
+ * assignment (the counterpart of the TF32 path of Section 3.1.5) is built on how this instruction
+ * rounds, which only measurement tells. */
+int ftk_abl_mfma_bf16(const uint16_t *A, const uint16_t *B, const float *C, float *D, int32_t tiles,
+                      void *hip_stream);
+
+/* The same for the instructions of the main path: v_mfma_f32_32x32x2_f32 (A [tiles][32][2],
+ * B [tiles][2][32], C and D [tiles][32][32]) and v_mfma_f64_16x16x4_f64 (A [tiles][16][4],
+ * B [tiles][4][16], C and D [tiles][16][16]).  The rounding band of the assignment (twice (D+4) u
+ * of the magnitude) assumes a chain of fused multiply-adds over the contraction index in order. */
+int ftk_abl_mfma_f32(const float *A, const float *B, const float *C, float *D, int32_t tiles, void *hip_stream);
+int ftk_abl_mfma_f64(const double *A, const double *B, const double *C, double *D, int32_t tiles,
+                     void *hip_stream);
+
 const char *ftk_abl_last_error(void);
 
 #ifdef __cplusplus

@@ -291,6 +291,69 @@ int fused_alu_t(const void *X, const void *C, int64_t N, int32_t D, int32_t K, i
     return 0;
 }
 
+// One v_mfma_f32_32x32x16_bf16 per wave on operands given as plain matrices: D = A B + C with A
+// [32][16] and B [16][32] in bf16 (bit patterns) and C, D [32][32] in fp32, `tiles` independent
+// problems.  Lane l supplies A[l % 32][8 (l / 32) .. + 7] and B[8 (l / 32) .. + 7][l % 32]; its
+// register r holds D[8 (r / 4) + 4 (l / 32) + r % 4][l % 32].  Exists so that a test can hold the
+// instruction's rounding behaviour - which the fast assignment's error bound is built on and no
+// document states - against the exact sums.
+typedef __bf16 abl_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float abl_floatx16 __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(64) void abl_mfma_bf16_kernel(const uint16_t *A, const uint16_t *B, const float *C, float *Dout)
+{
+    const int lane = threadIdx.x, col = lane & 31, g = lane >> 5;
+    const size_t t = blockIdx.x;
+    const uint16_t *a = A + t * 32 * 16, *b = B + t * 16 * 32;
+    const float *c = C + t * 32 * 32;
+    float *d = Dout + t * 32 * 32;
+    abl_bf16x8 av, bv;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        av[e] = __builtin_bit_cast(__bf16, a[col * 16 + 8 * g + e]);
+        bv[e] = __builtin_bit_cast(__bf16, b[(8 * g + e) * 32 + col]);
+    }
+    abl_floatx16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = c[(8 * (r / 4) + 4 * g + r % 4) * 32 + col];
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc, 0, 0, 0);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) d[(8 * (r / 4) + 4 * g + r % 4) * 32 + col] = acc[r];
+}
+
+
+// The fp32 and fp64 instructions of the main path, the same way: v_mfma_f32_32x32x2_f32 (A [32][2],
+// B [2][32], C and D [32][32]; lane l supplies A[l % 32][l / 32] and B[l / 32][l % 32]) and
+// v_mfma_f64_16x16x4_f64 (A [16][4], B [4][16], C and D [16][16]; lane l supplies A[l % 16][l / 16]
+// and B[l / 16][l % 16], register r holds D[4 r + l / 16][l % 16]).
+__global__ __launch_bounds__(64) void abl_mfma_f32_kernel(const float *A, const float *B, const float *C, float *Dout)
+{
+    const int lane = threadIdx.x, col = lane & 31, g = lane >> 5;
+    const size_t t = blockIdx.x;
+    const float *c = C + t * 32 * 32;
+    float *d = Dout + t * 32 * 32;
+    abl_floatx16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = c[(8 * (r / 4) + 4 * g + r % 4) * 32 + col];
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(A[t * 64 + col * 2 + g], B[t * 64 + g * 32 + col], acc, 0, 0, 0);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) d[(8 * (r / 4) + 4 * g + r % 4) * 32 + col] = acc[r];
+}
+
+typedef double abl_doublex4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(64) void abl_mfma_f64_kernel(const double *A, const double *B, const double *C, double *Dout)
+{
+    const int lane = threadIdx.x, col = lane & 15, g = lane >> 4;
+    const size_t t = blockIdx.x;
+    const double *c = C + t * 16 * 16;
+    double *d = Dout + t * 16 * 16;
+    abl_doublex4 acc;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) acc[r] = c[(4 * r + g) * 16 + col];
+    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(A[t * 64 + col * 4 + g], B[t * 64 + g * 16 + col], acc, 0, 0, 0);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) d[(4 * r + g) * 16 + col] = acc[r];
+}
+
 }  // namespace
 
 extern "C" {
@@ -412,6 +475,48 @@ int ftk_abl_fused_alu_assign(int dtype, const void *X, const void *C, int64_t N,
     hipStream_t st = (hipStream_t)hip_stream;
     return dtype == 0 ? fused_alu_t<float>(X, C, N, D, K, labels, mindist, variant, (char *)workspace, st)
                       : fused_alu_t<double>(X, C, N, D, K, labels, mindist, variant, (char *)workspace, st);
+}
+
+int ftk_abl_mfma_bf16(const uint16_t *A, const uint16_t *B, const float *C, float *D, int32_t tiles, void *hip_stream)
+{
+    if (!A || !B || !C || !D || tiles <= 0) {
+        set_err("invalid argument");
+        return 1;
+    }
+    hipLaunchKernelGGL(abl_mfma_bf16_kernel, dim3((unsigned)tiles), dim3(64), 0, (hipStream_t)hip_stream, A, B, C, D);
+    if (hipGetLastError() != hipSuccess) {
+        set_err("kernel launch failed");
+        return 4;
+    }
+    return 0;
+}
+
+int ftk_abl_mfma_f32(const float *A, const float *B, const float *C, float *D, int32_t tiles, void *hip_stream)
+{
+    if (!A || !B || !C || !D || tiles <= 0) {
+        set_err("invalid argument");
+        return 1;
+    }
+    hipLaunchKernelGGL(abl_mfma_f32_kernel, dim3((unsigned)tiles), dim3(64), 0, (hipStream_t)hip_stream, A, B, C, D);
+    if (hipGetLastError() != hipSuccess) {
+        set_err("kernel launch failed");
+        return 4;
+    }
+    return 0;
+}
+
+int ftk_abl_mfma_f64(const double *A, const double *B, const double *C, double *D, int32_t tiles, void *hip_stream)
+{
+    if (!A || !B || !C || !D || tiles <= 0) {
+        set_err("invalid argument");
+        return 1;
+    }
+    hipLaunchKernelGGL(abl_mfma_f64_kernel, dim3((unsigned)tiles), dim3(64), 0, (hipStream_t)hip_stream, A, B, C, D);
+    if (hipGetLastError() != hipSuccess) {
+        set_err("kernel launch failed");
+        return 4;
+    }
+    return 0;
 }
 
 }  // extern "C"
