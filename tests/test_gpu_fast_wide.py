@@ -211,3 +211,23 @@ def test_fit_on_the_fast_path_matches_the_fp32_fit_on_wide_rows():
     assert torch.equal(out["labels"], ref["labels"])
     assert torch.equal(out["C"], ref["C"]) and torch.equal(out["counts"], ref["counts"])
     assert np.allclose(out["inertia"], ref["inertia"], rtol=1e-6)
+
+
+@pytest.mark.parametrize("D", [12, 64, 128])
+def test_fast_nonfinite_points_do_not_disturb_the_others(D):
+    """Inputs are required to be finite; a NaN or Inf coordinate must not fault, must leave the
+    labels in range and every other point's label as it was (both fast kernels)."""
+    N, K = 20000, 90
+    X, C = _problem(N, D, K, seed=41)
+    bad_rows = np.array([5, 777, 19999])
+    Xb = X.copy()
+    Xb[5, 3] = np.nan
+    Xb[777, 0] = np.inf
+    Xb[19999, D - 1] = -np.inf
+    keep = np.ones(N, dtype=bool)
+    keep[bad_rows] = False
+    for mode in (ftk.FT_OFF, ftk.FT_STRICT):
+        lab_clean, _, _ = _run(X, C, mode)
+        lab, _, _ = _run(Xb, C, mode)
+        assert lab.min() >= 0 and lab.max() < K
+        assert np.array_equal(lab[keep], lab_clean[keep])
