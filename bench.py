@@ -438,9 +438,9 @@ def measure(name, args, torch, ftk, synth, np, headline):
             inj["overhead_step_vs_ft_off"] = sec_inj / off["sec"] - 1.0
             ft["under_injection"] = inj
         out["ft"] = ft
+    if w.dtype == "f32" and w.D <= 128 and w.D % 4 == 0 and not args.no_fast:
+        out["fast_mode"] = fast_mode_times(torch, ftk, s, steps, args.warmup, args.repeats, off["sec"])
     if headline:
-        if w.dtype == "f32" and w.D <= 128 and w.D % 4 == 0 and not args.no_fast:
-            out["fast_mode"] = fast_mode_times(torch, ftk, s, steps, args.warmup, args.repeats, off["sec"])
         if args.ablation:
             out["ablation"] = ablation_times(ftk, torch, s, esz)
         if args.batched:
