@@ -18,9 +18,9 @@
 // Layout: the 32x32x16 instruction contracts 16 values per lane pair - lane group g supplies
 // k = 8g .. 8g+7 - and here the two groups take different FEATURES, as in the fp32 kernels: of a
 // block of 16 features group g holds features 8g .. 8g+7.  A lane therefore keeps the pieces of
-// half a row of its point (D/2 registers for two pieces) for the whole sweep, two points per lane,
-// and per block of 16 features two 16-byte LDS reads (its 8 features of c0 and of c1) feed eight
-// instructions (2 x 2 piece pairs, two points).  The centroid pieces are prepared once per call by
+// half a row of its point (D/2 registers for two pieces) for the whole sweep, two points per lane
+// (one in the streaming variant), and per block of 16 features two 16-byte LDS reads (its 8
+// features of c0 and of c1) feed eight instructions (2 x 2 piece pairs, two points).  The centroid pieces are prepared once per call by
 // split2_centroids_kernel, already in LDS image order, so staging is a plain copy.
 //
 // Per tile, each lane keeps the 16 scores of its best tile; at the end only the centroids whose
@@ -29,13 +29,15 @@
 // it) - the winner always, up to three more - the two lanes of a point each covering the features
 // they hold.  More candidates than that go to the refine kernel.
 //
-// What bounds it (measured): not the matrix unit, which is busy a quarter of the time, but the two
-// phases of a unit that wait for memory - the fetch of the rows and their second fetch with the
-// winners' centroid rows - each as long as the sweep, with one other wave on the SIMD to fill the
-// time.  All loads of a phase are therefore issued together, and the compiler is kept from folding
-// the second fetch into the first, which would hold the fp32 row in registers across the sweep.
-// Evaluating the distances with row-contiguous loads shared by the wave was tried and cost more
-// vector instructions than it saved in waiting.
+// What bounds it (measured): not the matrix unit, which is busy a quarter to a third of the time,
+// but the two phases of a unit that wait for memory - the fetch of the rows and their second fetch
+// with the winners' centroid rows - each as long as the sweep, with one other wave on the SIMD to
+// fill the time.  All loads of a phase are therefore issued together, the compiler is kept from
+// folding the second fetch into the first (which would hold the fp32 row in registers across the
+// sweep), and where every tile is resident the rows of the NEXT unit are requested before the
+// sweep of the current one (the STREAM variant: one point tile per unit).  Evaluating the
+// distances with row-contiguous loads shared by the wave was tried and cost more vector
+// instructions than it saved in waiting.
 //
 // Fault tolerance (Sections 2.3, 4): tiles of 30 centroids and two checksum rows, verification,
 // location and correction as in the fp32 small-D kernel.  A checksum row is the sum of its 15
@@ -152,11 +154,14 @@ __global__ __launch_bounds__(256) void split2_centroids_kernel(const float *C, i
     if (u == 0) dst[2 * NU] = make_uint4(0u, 0u, 0u, 0u);  // the padding unit travels with the copy
 }
 
-template <int NH, bool FT, bool WHOLE>
+// STREAM (every tile resident, no faults listed): one point tile per unit, and the rows of a wave's
+// next unit are requested before the sweep of the current one, so that the first of the two
+// memory phases of a unit passes under matrix work instead of in front of it.
+template <int NH, bool FT, bool WHOLE, bool STREAM>
 __global__ __launch_bounds__(FW_WAVES * 64, FW_WAVES / 4) void assign_fast_wide_kernel(FastArgs a)
 {
     constexpr int THREADS = FW_WAVES * 64;
-    constexpr int PT = fw_pt(NH);
+    constexpr int PT = STREAM ? 1 : fw_pt(NH);
     using M = Mma<float>;
     using G = TileGeom<FT>;
     constexpr int SU = fw_row_units(NH);
@@ -262,8 +267,13 @@ __global__ __launch_bounds__(FW_WAVES * 64, FW_WAVES / 4) void assign_fast_wide_
         request_frags(a.X + p * D, raw);
     };
 
-    // one unit of work of a wave: 64 points starting at p0, swept over all tiles and settled
-    auto process = [&](int64_t p0, int blk) {
+    // the fp32 rows of a unit between their request and their split: STREAM keeps them across units
+    floatx4 raws_stream[STREAM ? PT : 1][STREAM ? NU : 1];
+    bool have_rows = false;  // STREAM: the rows of the unit about to be processed have been requested
+
+    // one unit of work of a wave: PT*32 points starting at p0, swept over all tiles and settled
+    // (p0_next: the wave's next unit, or negative)
+    auto process = [&](int64_t p0, int blk, int64_t p0_next) {
         uint4 b0[PT][NH], b1[PT][NH];  // pieces x0 and x1 of the lane's features, 8 per block
         float xn[PT];
         float tau[PT];
@@ -274,14 +284,21 @@ __global__ __launch_bounds__(FW_WAVES * 64, FW_WAVES / 4) void assign_fast_wide_
         floatx16 bacc[PT];  // the scores of this lane's best tile
         // fetch the rows (all loads of both tiles in flight together), split them into pieces;
         // norms, thresholds, empty records
-        auto load_points = [&]() {
-            floatx4 raws[PT][NU];
+        floatx4 raws_unit[STREAM ? 1 : PT][STREAM ? 1 : NU];
+        auto &raws = [&]() -> auto & {
+            if constexpr (STREAM) return raws_stream;
+            else return raws_unit;
+        }();
+        auto request_unit = [&](int64_t q0) {
 #pragma unroll
             for (int pt = 0; pt < PT; ++pt) {
-                int64_t p = p0 + pt * 32 + col;
+                int64_t p = q0 + pt * 32 + col;
                 if (p >= a.N) p = a.N - 1;
                 request_row(p, raws[pt]);
             }
+        };
+        auto load_points = [&]() {
+            if (!(STREAM && have_rows)) request_unit(p0);
 #pragma unroll
             for (int pt = 0; pt < PT; ++pt) {
                 const floatx4 (&raw)[NU] = raws[pt];
@@ -311,8 +328,12 @@ __global__ __launch_bounds__(FW_WAVES * 64, FW_WAVES / 4) void assign_fast_wide_
 #pragma unroll
                 for (int r = 0; r < 16; ++r) bacc[pt][r] = M::neg_inf();
             }
+            if (STREAM) {  // the next unit's rows travel while this one is swept
+                have_rows = p0_next >= 0;
+                if (have_rows) request_unit(p0_next);
+            }
         };
-        const bool head = resident && !staged && a.n_faults == 0;  // the out-of-step start (see above)
+        const bool head = !STREAM && resident && !staged && a.n_faults == 0;  // the out-of-step start (see above)
         const bool late = head && wave >= FW_WAVES / 2;
         if (!late) load_points();
 
@@ -596,16 +617,28 @@ __global__ __launch_bounds__(FW_WAVES * 64, FW_WAVES / 4) void assign_fast_wide_
     // Otherwise the waves of a workgroup walk the blocks in step (chunks are staged, faults are
     // listed per block) and draw them from an atomic counter, one draw per block.
     int blk = blockIdx.x;
-    while (blk < a.nblocks) {
-        process(((int64_t)blk * FW_WAVES + wave) * (PT * 32), blk);
-        if (resident && a.n_faults == 0) {
-            blk += (int)gridDim.x;
-            continue;
+    if constexpr (STREAM) {
+        stage_chunk(0, 0, THREADS);
+        __syncthreads();
+        staged = true;
+        while (blk < a.nblocks) {
+            const int nxt = blk + (int)gridDim.x;
+            process(((int64_t)blk * FW_WAVES + wave) * (PT * 32), blk,
+                    nxt < a.nblocks ? ((int64_t)nxt * FW_WAVES + wave) * (PT * 32) : -1);
+            blk = nxt;
         }
-        __syncthreads();
-        if (tid == 0) sh_next = (int)gridDim.x + atomicAdd(a.wl_count + 1, 1);
-        __syncthreads();
-        blk = sh_next;
+    } else {
+        while (blk < a.nblocks) {
+            process(((int64_t)blk * FW_WAVES + wave) * (PT * 32), blk, -1);
+            if (resident && a.n_faults == 0) {
+                blk += (int)gridDim.x;
+                continue;
+            }
+            __syncthreads();
+            if (tid == 0) sh_next = (int)gridDim.x + atomicAdd(a.wl_count + 1, 1);
+            __syncthreads();
+            blk = sh_next;
+        }
     }
 
     // hand the collected work-list entries over to the refine kernel
@@ -708,10 +741,26 @@ static void launch_fast_wide_t(const FastArgs &a, const AssignPlan &p, hipStream
     const int delta_blocks = FT ? (int)ceil_div(a.tiles_total * 2, 4) : 0;
     hipLaunchKernelGGL((split2_centroids_kernel<NH, FT>), dim3(image_blocks + delta_blocks), dim3(256), 0, st, a.C, a.D,
                        a.K, a.tiles_total, const_cast<uint4 *>(a.csplit), image_blocks, const_cast<double *>(a.scal));
-    if (a.D == 16 * NH)
-        hipLaunchKernelGGL((assign_fast_wide_kernel<NH, FT, true>), dim3(p.grid), dim3(FW_WAVES * 64), p.lds_bytes, st, a);
-    else
-        hipLaunchKernelGGL((assign_fast_wide_kernel<NH, FT, false>), dim3(p.grid), dim3(FW_WAVES * 64), p.lds_bytes, st, a);
+    // every tile resident and no faults listed: the streaming variant, one point tile per unit
+    // (measured: 13 % faster at 128 features, 5 % at 96, and 10-25 % with checksums at every width -
+    // one tile's verification state instead of two keeps the sweep loop free of spills; without
+    // checksums up to 64 features the two-tile units are 4 % ahead)
+    const bool stream = a.nch == 1 && a.n_faults == 0 && (NH >= 6 || FT);
+    FastArgs b = a;
+    int grid = p.grid;
+    if (stream) {
+        const int64_t blocks = ceil_div(a.N, (int64_t)FW_WAVES * 32);
+        b.nblocks = (int)blocks;
+        grid = (int)(blocks < 256 ? blocks : 256);
+    }
+    const dim3 g((unsigned)grid), t(FW_WAVES * 64);
+    if (a.D == 16 * NH) {
+        if (stream) hipLaunchKernelGGL((assign_fast_wide_kernel<NH, FT, true, true>), g, t, p.lds_bytes, st, b);
+        else hipLaunchKernelGGL((assign_fast_wide_kernel<NH, FT, true, false>), g, t, p.lds_bytes, st, b);
+    } else {
+        if (stream) hipLaunchKernelGGL((assign_fast_wide_kernel<NH, FT, false, true>), g, t, p.lds_bytes, st, b);
+        else hipLaunchKernelGGL((assign_fast_wide_kernel<NH, FT, false, false>), g, t, p.lds_bytes, st, b);
+    }
 }
 
 ftk_status launch_assign_fast_wide(const AssignCall &c, const AssignPlan &p, const Workspace &w, hipStream_t st)
